@@ -1,0 +1,508 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without a GPU.
+
+Each test targets a different kind of plausible mistake (a dropped term, a wrong
+index, a transposed operand, a non-strict comparison, a wrong merge direction).
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sttm_oracle as O
+from paper_2507_07990_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_video(seed, T, H, W, D, blocks=True):
+    cfg = wl.Workload("t", seed, 1, T, H, W, D, "f32", int(math.log2(wl.pow2_ceil(max(H, W)))), 0.1, 0.7)
+    if blocks:
+        return wl.generate(cfg)
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((1, T, H, W, D)).astype(np.float32)
+
+
+# ---------------------------------------------------------------- O1 / O2 ----
+def test_pyramid_matches_library_pooling_and_cosine():
+    """On a full power-of-two grid the pyramid is avg_pool2d applied level by level and the
+    child similarity is the library cosine (Sec. 3.2, downsampling by 2x2 averaging)."""
+    rng = np.random.default_rng(0)
+    H = W = 16
+    D = 24
+    frame = rng.standard_normal((H, W, D))
+    grid = O.Grid(H, W, 1)
+    mean, cnt = O.build_pyramid(frame, grid)
+    sims, m = O.child_similarities(mean, cnt, grid)
+    x = torch.from_numpy(frame).permute(2, 0, 1)[None]            # [1, D, H, W]
+    levels = [x]
+    for _ in range(grid.L):
+        levels.append(torch.nn.functional.avg_pool2d(levels[-1], 2))
+    for lvl in range(grid.L + 1):
+        ref = levels[lvl][0].permute(1, 2, 0).numpy()
+        np.testing.assert_allclose(mean[lvl], ref, rtol=0, atol=1e-13)
+        assert (cnt[lvl] == 4 ** lvl).all()
+    for lvl in range(1, grid.L + 1):
+        par = levels[lvl]
+        up = torch.nn.functional.interpolate(par, scale_factor=2, mode="nearest")
+        cs = torch.nn.functional.cosine_similarity(up, levels[lvl - 1], dim=1)[0].numpy()  # [side_c, side_c]
+        g = grid.side(lvl)
+        for by in range(g):
+            for bx in range(g):
+                got = sims[lvl][by, bx]
+                ref4 = [cs[2 * by + dy, 2 * bx + dx] for dy in (0, 1) for dx in (0, 1)]
+                np.testing.assert_allclose(got, np.minimum(ref4, 1.0), atol=1e-12)
+                assert m[lvl][by, bx] == pytest.approx(min(min(ref4), 1.0), abs=1e-12)
+
+
+def test_padded_grid_means_are_valid_cell_means():
+    """13x13 inside 16x16: every node's mean is the plain mean over its valid cells, nodes
+    fully in the padding do not exist, and partially padded nodes compare only existing children."""
+    rng = np.random.default_rng(1)
+    H = W = 13
+    frame = rng.standard_normal((H, W, 8))
+    grid = O.Grid(H, W, 1)
+    mean, cnt = O.build_pyramid(frame, grid)
+    sims, m = O.child_similarities(mean, cnt, grid)
+    for lvl in range(grid.L + 1):
+        s = 1 << lvl
+        for by in range(grid.side(lvl)):
+            for bx in range(grid.side(lvl)):
+                blk = frame[by * s:(by + 1) * s, bx * s:(bx + 1) * s].reshape(-1, 8)
+                assert cnt[lvl][by, bx] == len(blk) == grid.cells(lvl, by, bx)
+                if len(blk):
+                    np.testing.assert_allclose(mean[lvl][by, bx], blk.mean(axis=0), atol=1e-13)
+    # level-1 node (6,6) covers cells rows 12..13, cols 12..13 -> only (12,12) is valid: one child
+    assert cnt[1][6, 6] == 1
+    assert np.isnan(sims[1][6, 6, 1:]).all() and sims[1][6, 6, 0] == pytest.approx(1.0)
+    assert cnt[1][7, 7] == 0 and np.isnan(m[1][7, 7])
+    existing = sum(int((cnt[l] > 0).sum()) for l in range(grid.L + 1))
+    assert existing == 169 + 49 + 16 + 4 + 1
+
+
+def test_eq1_comparison_counts_golden():
+    """Eq. (1): number of parent-child comparisons on a full grid; Eq. (2): below 4HW/3."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eq1_comparison_counts.txt")) if l[0] != "#"]
+    for H, W, R, Lv, C in [[int(v) for v in r] for r in rows]:
+        feats = np.random.default_rng(H + R).standard_normal((1, 1, H, W, 4)).astype(np.float32)
+        grid, frames, ncmp = O.spatial_stats(feats, R)
+        assert grid.L == Lv
+        assert ncmp == C == sum(4 * H * W // 4 ** i for i in range(1, Lv + 1))
+        assert C <= 4 * H * W / 3
+
+
+def test_hand_worked_2x2_golden():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "hand_worked_2x2.txt")) if l[0] != "#"]
+    want = {int(r[0]): float(r[1]) for r in rows}
+    frames = np.array([
+        [[[3, 4], [4, 3]], [[3, 4], [4, 3]]],
+        [[[1, 0], [0, 1]], [[1, 0], [0, 1]]],
+        [[[1, 0], [1, 0]], [[1, 0], [-1, 0]]],
+    ], dtype=np.float32)[None]                                     # [1, 3, 2, 2, 2]
+    sp = O.spatial_quadtree(frames, 0.9)
+    for t in range(3):
+        assert float(sp.m[t][1][0, 0]) == pytest.approx(want[t], abs=1e-15)
+    assert len(sp.kept[0]) == 1 and len(sp.kept[1]) == 4 and len(sp.kept[2]) == 4
+    # strictness: tau exactly at the value => split ("higher than" the threshold)
+    exact = float(sp.m[1][1][0, 0])
+    assert len(O.spatial_quadtree(frames[:, 1:2], exact).kept[0]) == 4
+    assert len(O.spatial_quadtree(frames[:, 1:2], np.nextafter(exact, 0)).kept[0]) == 1
+
+
+def test_cosine_conventions():
+    assert O.cosine(np.array([0.0, 0.0]), np.array([1.0, 2.0])) == 0.0
+    assert O.cosine(np.array([1.0, 2.0]), np.array([1.0, 2.0]) * 3) <= 1.0
+    assert O.cosine(np.array([1.0, 0.0]), np.array([-2.0, 0.0])) == -1.0
+    assert O.cosine(np.array([1.0, 0.0]), np.array([0.0, 5.0])) == 0.0
+
+
+# --------------------------------------------------------------------- O3 ----
+def _enumerate_cuts(grid, lvl, by, bx):
+    """All quadtree cuts below a node: each is a frozenset of kept (lvl, by, bx)."""
+    if not grid.exists(lvl, by, bx):
+        return [frozenset()]
+    out = [frozenset([(lvl, by, bx)])]
+    if lvl > 0:
+        subs = [_enumerate_cuts(grid, lvl - 1, 2 * by + dy, 2 * bx + dx) for dy in (0, 1) for dx in (0, 1)]
+        for combo in itertools.product(*subs):
+            out.append(frozenset().union(*combo))
+    return out
+
+
+def _ancestors(node):
+    lvl, by, bx = node
+    return lvl + 1, by // 2, bx // 2
+
+
+def _cut_satisfies(cut, m, grid, tau):
+    """Declarative statement of Sec. 3.2: every kept coarse node has all child similarities above
+    tau, and every pruned ancestor of a kept node has some child similarity not above tau."""
+    for node in cut:
+        lvl, by, bx = node
+        if lvl > 0 and not (m[lvl][by, bx] > tau):
+            return False
+        a = node
+        while a[0] < grid.L:
+            a = _ancestors(a)
+            if m[a[0]][a[1], a[2]] > tau:
+                return False
+    return True
+
+
+@pytest.mark.parametrize("H,W,seed", [(4, 4, 0), (4, 4, 1), (4, 3, 2), (3, 4, 3), (8, 8, 4), (7, 5, 5)])
+def test_quadtree_search_is_the_unique_valid_cut(H, W, seed):
+    feats = _rand_video(seed, 1, H, W, 16)
+    grid, frames, _ = O.spatial_stats(feats, 1)
+    m = frames[0][3]
+    all_cuts = _enumerate_cuts(grid, grid.L, 0, 0)
+    if (H, W) == (4, 4):
+        assert len(all_cuts) == 17
+    if (H, W) == (8, 8):
+        assert len(all_cuts) == 1 + 17 ** 4
+    vals = sorted(float(v) for l in range(1, grid.L + 1) for v in m[l].ravel() if not np.isnan(v))
+    taus = [-2.0, 1.0] + [0.5 * (a + b) for a, b in zip(vals[:-1], vals[1:])][:: max(1, len(vals) // 6)]
+    for tau in taus:
+        good = [c for c in all_cuts if _cut_satisfies(c, m, grid, tau)]
+        assert len(good) == 1
+        _, _, _, kept, _ = O.quadtree_search(m, grid, tau)
+        assert frozenset(kept) == good[0]
+
+
+def test_quadtree_maps_tile_the_frame():
+    feats = _rand_video(7, 2, 13, 13, 32)
+    sp = O.spatial_quadtree(feats, 0.9)
+    H = W = 13
+    for t in range(2):
+        covered = np.zeros((H, W), dtype=int)
+        for lvl, by, bx in sp.kept[t]:
+            s = 1 << lvl
+            covered[by * s:(by + 1) * s, bx * s:(bx + 1) * s] += 1
+            blk = sp.node_map[0, t, by * s:(by + 1) * s, bx * s:(bx + 1) * s]
+            assert (blk == t * H * W + by * s * W + bx * s).all()
+            assert (sp.node_level[0, t, by * s:(by + 1) * s, bx * s:(bx + 1) * s] == lvl).all()
+        assert (covered == 1).all()
+
+
+def test_constant_frame_collapses_to_root_and_tau_ge_1_is_identity():
+    v = np.random.default_rng(3).standard_normal(16).astype(np.float32)
+    feats = np.broadcast_to(v, (1, 2, 13, 13, 16)).copy()
+    sp = O.spatial_quadtree(feats, 0.999999)
+    assert [len(k) for k in sp.kept] == [1, 1]
+    assert (sp.node_level == 4).all() and (sp.node_map[0, 1] == 169).all()
+    sp = O.spatial_quadtree(feats, 1.0)       # clamp + strict comparison
+    assert [len(k) for k in sp.kept] == [169, 169]
+    assert (sp.node_map.ravel() == np.arange(2 * 169)).all()
+    for R, n in ((2, 4), (4, 16)):
+        assert len(O.spatial_quadtree(feats, 0.5, root_grid=R).kept[0]) == n
+
+
+def test_spatial_map_commutes_with_transpose():
+    feats = _rand_video(11, 1, 8, 8, 16)
+    a = O.spatial_quadtree(feats, 0.8)
+    b = O.spatial_quadtree(np.ascontiguousarray(feats.transpose(0, 1, 3, 2, 4)), 0.8)
+    assert (a.node_level[0, 0] == b.node_level[0, 0].T).all()
+    ya, xa = np.divmod(a.node_map[0, 0], 8)
+    yb, xb = np.divmod(b.node_map[0, 0], 8)
+    assert (ya == xb.T).all() and (xa == yb.T).all()
+
+
+# --------------------------------------------------------------------- O5 ----
+def _rects(node_map_frame, node_level_frame, W, base):
+    out = {}
+    for n in np.unique(node_map_frame):
+        y0, x0 = divmod(int(n) - base, W)
+        s = 1 << int(node_level_frame[y0, x0])
+        out[int(n)] = (y0, x0, y0 + s, x0 + s)
+    return out
+
+
+@pytest.mark.parametrize("seed,H,W,tau_s,tau_t", [(0, 8, 8, 0.8, 0.8), (1, 13, 13, 0.9, 0.6), (2, 7, 6, 0.7, 0.3)])
+def test_temporal_edges_match_brute_force_rectangles(seed, H, W, tau_s, tau_t):
+    """All (source, destination) pairs of consecutive frames with intersecting rectangles,
+    features by a direct loop over cells, destination = smallest (y0, x0) among passing."""
+    T, D = 4, 12
+    feats = _rand_video(seed, T, H, W, D)
+    sp = O.spatial_quadtree(feats, tau_s)
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, tau_t)
+    x = feats[0].astype(np.float64)
+    HW = H * W
+
+    def feature(t, rect):
+        y0, x0, y1, x1 = rect
+        acc, k = np.zeros(D), 0
+        for y in range(y0, min(y1, H)):
+            for xx in range(x0, min(x1, W)):
+                acc += x[t, y, xx]
+                k += 1
+        return acc / k
+
+    ncmp = 0
+    for t in range(1, T):
+        src = _rects(sp.node_map[0, t], sp.node_level[0, t], W, t * HW)
+        dst = _rects(sp.node_map[0, t - 1], sp.node_level[0, t - 1], W, (t - 1) * HW)
+        for n, rn in src.items():
+            best = None
+            for d, rd in dst.items():
+                if rn[0] < rd[2] and rd[0] < rn[2] and rn[1] < rd[3] and rd[1] < rn[3]:
+                    ncmp += 1
+                    a, b = feature(t, rn), feature(t - 1, rd)
+                    sig = min(1.0, a @ b / math.sqrt((a @ a) * (b @ b)))
+                    if sig > tau_t and (best is None or (rd[0], rd[1]) < best[0]):
+                        best = ((rd[0], rd[1]), d)
+            y0, x0 = rn[0], rn[1]
+            assert tm.parent[0, t, y0, x0] == (best[1] if best else -1)
+    assert ncmp == tm.comparisons
+    assert (tm.parent[0, 0] == -1).all()
+    assert ((tm.parent < 0) | (tm.parent // HW == np.arange(T)[None, :, None, None] - 1)).all()
+
+
+def test_temporal_worst_case_comparison_count():
+    """Sec. 3.3: with every frame at the finest level there are (T-1)*H*W comparisons."""
+    feats = _rand_video(3, 5, 6, 7, 8)
+    sp = O.spatial_quadtree(feats, 1.0)
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.5)
+    assert tm.comparisons == 4 * 6 * 7
+
+
+def test_one_to_many_takes_top_left_passing_destination():
+    """Coarse source over four fine destinations (Sec. 3.3): the top-left-most *passing* one wins,
+    even when another destination is more similar."""
+    D = 8
+    e = np.eye(D, dtype=np.float32)
+    f0 = np.stack([e[0], e[1], e[2], e[3]]).reshape(2, 2, D)            # 4 distinct cells -> 4 nodes
+    src = (0.1 * e[0] + 0.6 * e[1] + 0.55 * e[2] + 0.9 * e[3]).astype(np.float32)
+    f1 = np.broadcast_to(src, (2, 2, D))                               # constant -> 1 root node
+    feats = np.stack([f0, f1])[None]
+    sp = O.spatial_quadtree(feats, 0.9)
+    assert len(sp.kept[0]) == 4 and len(sp.kept[1]) == 1
+    nrm = np.linalg.norm(src)
+    sig = [0.1 / nrm, 0.6 / nrm, 0.55 / nrm, 0.9 / nrm]
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.4)
+    assert sig[0] < 0.4 < min(sig[1:])
+    assert tm.parent[0, 1, 0, 0] == 1                                   # cell (0,1) of frame 0, not argmax (1,1)
+    assert tm.e[4] == pytest.approx(max(sig))
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.45)      # now (0,1) passes, (1,0) fails
+    assert tm.parent[0, 1, 0, 0] == 1
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.7)       # only (1,1) passes
+    assert tm.parent[0, 1, 0, 0] == 3
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.99)
+    assert tm.parent[0, 1, 0, 0] == -1 and (tm.cluster_ids[0, 1] == 4).all()
+
+
+def test_many_to_one_merges_fine_sources_into_coarse_destination():
+    D = 8
+    e = np.eye(D, dtype=np.float32)
+    f0 = np.broadcast_to(e[0] + e[1], (2, 2, D))                        # one coarse node
+    f1 = np.stack([e[0] + e[1], e[2], e[0] + 0.9 * e[1], e[3]]).reshape(2, 2, D)
+    feats = np.stack([f0, f1]).astype(np.float32)[None]
+    sp = O.spatial_quadtree(feats, 0.9)
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.9)
+    assert list(tm.parent[0, 1].ravel()) == [0, -1, 0, -1]
+    assert list(tm.cluster_ids[0].ravel()) == [0, 0, 0, 0, 0, 5, 0, 7]
+    rd = O.reduce_clusters(feats, tm.cluster_ids)
+    assert list(rd.counts) == [6, 1, 1] and list(rd.out_ids) == [0, 5, 7]
+
+
+# ---------------------------------------------------------------- O6 / O7 ----
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_roots_are_connected_components_with_earliest_member(seed):
+    import scipy.sparse as sps
+    from scipy.sparse.csgraph import connected_components
+    feats = _rand_video(seed, 6, 8, 8, 16)
+    sp = O.spatial_quadtree(feats, 0.85)
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.7)
+    N = feats.shape[1] * 64
+    nodes = np.unique(sp.node_map)
+    src = [n for n in nodes if tm.parent.ravel()[n] >= 0]
+    dst = [tm.parent.ravel()[n] for n in src]
+    g = sps.coo_matrix((np.ones(len(src)), (src, dst)), shape=(N, N))
+    _, lab = connected_components(g, directed=False)
+    cl = tm.cluster_ids.ravel()
+    for comp in np.unique(lab[nodes]):
+        members = nodes[lab[nodes] == comp]
+        root = members.min()
+        assert (cl[members] == root).all()
+        assert tm.parent.ravel()[root] == -1
+        first = members // 64 == root // 64
+        assert first.sum() == 1                          # exactly one node in the earliest frame
+        frames_present = np.unique(members // 64)
+        assert (np.diff(frames_present) == 1).all()      # contiguous frame interval
+    # every cell carries its node's cluster, which is the smallest flat index in the cluster
+    for cid in np.unique(cl):
+        assert np.nonzero(cl == cid)[0].min() == cid
+    assert (cl == cl[sp.node_map.ravel()]).all()
+
+
+def test_repeated_frame_merges_fully_into_predecessor():
+    feats = _rand_video(5, 3, 13, 13, 32)
+    feats[0, 2] = feats[0, 1]
+    sp = O.spatial_quadtree(feats, 0.9)
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.99)
+    assert (tm.cluster_ids[0, 2] < 2 * 169).all()
+    assert (sp.node_level[0, 2] == sp.node_level[0, 1]).all()
+    assert (tm.parent[0, 2][sp.node_map[0, 2] == np.arange(2 * 169, 3 * 169).reshape(13, 13)] >= 169).all()
+
+
+def test_temporal_only_is_run_length_along_time():
+    """tau_S >= 1 (all finest): clusters are runs along t of cos(x_t, x_{t-1}) > tau_T per cell."""
+    feats = _rand_video(9, 7, 5, 6, 16)
+    x = feats[0].astype(np.float64)
+    sp = O.spatial_quadtree(feats, 1.5)
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.6)
+    T, H, W = 7, 5, 6
+    want = np.empty((T, H, W), dtype=np.int64)
+    for y in range(H):
+        for xx in range(W):
+            cur = y * W + xx
+            want[0, y, xx] = cur
+            for t in range(1, T):
+                a, b = x[t, y, xx], x[t - 1, y, xx]
+                if min(1.0, a @ b / math.sqrt((a @ a) * (b @ b))) > 0.6:
+                    want[t, y, xx] = want[t - 1, y, xx]
+                else:
+                    want[t, y, xx] = t * H * W + y * W + xx
+    assert (tm.cluster_ids[0] == want).all()
+    # tau_T >= 1: no temporal merging at all
+    tm1 = O.temporal_merge(feats, sp.node_map, sp.node_level, 1.0)
+    assert (tm1.cluster_ids.ravel() == np.arange(T * H * W)).all()
+
+
+# --------------------------------------------------------------------- O8 ----
+def test_reduce_is_scatter_mean_and_counts_sum_to_tokens():
+    feats = _rand_video(4, 5, 8, 8, 16)
+    sp, tm, rd, _ = O.sttm(feats, tau_s=0.8, tau_t=0.7)
+    N = 5 * 64
+    flat = tm.cluster_ids.ravel()
+    inv = np.searchsorted(rd.out_ids, flat)
+    acc = torch.zeros(len(rd.out_ids), 16, dtype=torch.float64)
+    acc.index_add_(0, torch.from_numpy(inv), torch.from_numpy(feats.reshape(N, 16).astype(np.float64)))
+    cnt = np.bincount(inv, minlength=len(rd.out_ids))
+    np.testing.assert_allclose(rd.merged, acc.numpy() / cnt[:, None], atol=1e-13)
+    assert (rd.counts == cnt).all() and rd.counts.sum() == N
+    assert list(rd.offsets) == [0, len(rd.out_ids)]
+    assert (np.diff(rd.out_ids) > 0).all()
+
+
+def test_identity_and_full_collapse_extremes():
+    feats = _rand_video(6, 3, 4, 4, 8)
+    sp, tm, rd, _ = O.sttm(feats, tau_s=1.0, tau_t=1.0)
+    assert (rd.counts == 1).all() and len(rd.counts) == 48
+    np.testing.assert_array_equal(rd.merged, feats.reshape(48, 8).astype(np.float64))
+    sp, tm, rd, _ = O.sttm(feats, tau_s=-2.0, tau_t=-2.0)
+    assert len(rd.counts) == 1 and rd.counts[0] == 48
+    np.testing.assert_allclose(rd.merged[0], feats.reshape(48, 8).astype(np.float64).mean(0), atol=1e-14)
+    sp, tm, rd, _ = O.sttm(feats, tau_s=-2.0, tau_t=-2.0, root_grid=2)
+    assert len(rd.counts) == 4 and (rd.counts == 12).all()
+
+
+def test_power_of_two_scaling_leaves_maps_unchanged():
+    feats = _rand_video(8, 4, 8, 8, 16)
+    a = O.sttm(feats, tau_s=0.8, tau_t=0.8)
+    b = O.sttm(feats * np.float32(8.0), tau_s=0.8, tau_t=0.8)
+    assert (a[1].cluster_ids == b[1].cluster_ids).all()
+    np.testing.assert_array_equal(a[2].merged * 8.0, b[2].merged)
+
+
+def test_batched_videos_are_independent_and_offsets_are_per_video():
+    v0 = _rand_video(20, 3, 4, 4, 8)
+    v1 = _rand_video(21, 3, 4, 4, 8)
+    both = np.concatenate([v0, v1])
+    r0 = O.sttm(v0, tau_s=0.8, tau_t=0.7)
+    r1 = O.sttm(v1, tau_s=0.9, tau_t=0.6)
+    rb = O.sttm(both, tau_s=[0.8, 0.9], tau_t=[0.7, 0.6])
+    assert (rb[1].cluster_ids[0] == r0[1].cluster_ids[0]).all()
+    assert (rb[1].cluster_ids[1] == r1[1].cluster_ids[0] + 48).all()
+    k0 = len(r0[2].counts)
+    assert list(rb[2].offsets) == [0, k0, k0 + len(r1[2].counts)]
+    np.testing.assert_array_equal(rb[2].merged[k0:], r1[2].merged)
+
+
+# --------------------------------------------------------------------- O9 ----
+def test_budget_threshold_rule_small_cases():
+    tau, lo, hi, K = O.budget_threshold([0.2, 0.5, 0.5, 0.9], [3, 3, 1, 3], base=1, target=8)
+    assert (lo, hi, K) == (0.5, 0.9, 8) and tau == pytest.approx(0.7)
+    tau, lo, hi, K = O.budget_threshold([0.2, 0.5, 0.5, 0.9], [3, 3, 1, 3], base=1, target=7)
+    assert (lo, hi, K) == (0.2, 0.5, 4) and tau == pytest.approx(0.35)
+    tau, lo, hi, K = O.budget_threshold([0.2, 0.5], [3, 3], base=1, target=3)
+    assert (tau, K) == (pytest.approx(-0.9), 1) and lo == -2.0 and hi == 0.2
+    assert O.budget_threshold([0.2, 0.5], [3, 3], base=1, target=100)[0] == 1.0
+    assert O.budget_threshold([0.2, 0.5], [3, 3], base=5, target=4)[0] == -2.0
+    # zero-weight values are not breakpoints
+    tau, lo, hi, K = O.budget_threshold([0.2, 0.3, 0.5], [3, 0, 3], base=1, target=4)
+    assert (lo, hi) == (0.2, 0.5)
+
+
+@pytest.mark.parametrize("seed,keep", [(0, 0.5), (1, 0.3), (2, 0.7)])
+def test_budget_mode_matches_brute_force_over_breakpoints(seed, keep):
+    """Run the stages at every candidate threshold and pick by definition: the largest
+    threshold interval whose token count stays within the target; K(tau) is monotone."""
+    T, H, W = 4, 7, 7
+    feats = _rand_video(seed, T, H, W, 16)
+    N = T * H * W
+    sp, tm, rd, info = O.sttm(feats, keep=keep)
+    stats = O.spatial_stats(feats, 1)
+    vals = sorted({float(v) for f in stats[1] for l in range(1, stats[0].L + 1)
+                   for v in f[3][l].ravel() if not np.isnan(v)})
+    grid_pts = [-2.0] + vals + [1.0]
+    Ks = [len(np.unique(O.spatial_quadtree(feats, tau, stats=stats).node_map)) for tau in grid_pts]
+    assert all(a <= b for a, b in zip(Ks, Ks[1:]))
+    target_s = math.floor(math.sqrt(keep) * N)
+    best = max(i for i, k in enumerate(Ks) if k <= target_s)
+    n_spatial = len(np.unique(sp.node_map))
+    assert n_spatial == Ks[best] <= target_s
+    first = min(i for i, k in enumerate(Ks) if k == Ks[best])   # K is flat between real breakpoints
+    if best + 1 < len(grid_pts):
+        assert grid_pts[first] <= info["tau_s"][0] < grid_pts[best + 1] and Ks[best + 1] > target_s
+    # temporal stage
+    cands, _ = O.temporal_candidates(feats, sp.node_map, sp.node_level)
+    evals = sorted({max(s for _, s in lst) for lst in cands.values()})
+    pts = [-2.0] + evals + [1.0]
+    Kt = [len(np.unique(O.temporal_merge(feats, sp.node_map, sp.node_level, tau, cands=cands).cluster_ids))
+          for tau in pts]
+    assert all(a <= b for a, b in zip(Kt, Kt[1:]))
+    target = math.floor(keep * N)
+    best = max(i for i, k in enumerate(Kt) if k <= target)
+    assert len(rd.counts) == Kt[best] <= target
+    first = min(i for i, k in enumerate(Kt) if k == Kt[best])
+    if best + 1 < len(pts):
+        assert pts[first] <= info["tau_t"][0] < pts[best + 1] and Kt[best + 1] > target
+
+
+# --------------------------------------------------------------- planted -----
+def test_planted_partition_is_recovered_without_noise():
+    """Noise-free block data: any threshold in (0.9, 1) recovers exactly the generator's leaves
+    (independent Gaussian bases are nowhere near cos 0.9 to their mean at D=1024)."""
+    cfg = wl.Workload("planted", 5, 1, 3, 13, 13, 1024, "f32", 4, 0.0, 0.6)
+    feats, leaves = wl.generate(cfg, return_leaf_maps=True)
+    sp = O.spatial_quadtree(feats, 0.95)
+    for t in range(3):
+        assert len(sp.kept[t]) == len(np.unique(leaves[0, t]))
+        for lvl, by, bx in sp.kept[t]:
+            s = 1 << lvl
+            assert len(np.unique(leaves[0, t, by * s:(by + 1) * s, bx * s:(bx + 1) * s])) == 1
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, 0.95)
+    # a persisting leaf (same id in consecutive frames) stays in one cluster
+    same = leaves[0, 1:] == leaves[0, :-1]
+    assert (tm.cluster_ids[0, 1:][same] == tm.cluster_ids[0, :-1][same]).all()
+    assert (tm.cluster_ids[0, 1:][~same] >= 169).all()
+
+
+def test_same_block_similarity_statistics():
+    """Level-1 similarity inside one generator block is about 1 - 0.375 sigma^2 (4 noisy copies vs their mean)."""
+    rng = np.random.default_rng(0)
+    D, sigma = 4096, 0.1
+    base = rng.standard_normal(D)
+    frame = (base + sigma * rng.standard_normal((2, 2, D)))
+    grid = O.Grid(2, 2, 1)
+    mean, cnt = O.build_pyramid(frame, grid)
+    sims, _ = O.child_similarities(mean, cnt, grid)
+    assert np.nanmean(sims[1]) == pytest.approx(1 - 0.375 * sigma ** 2, abs=2e-4)
+
+
+def test_widen_is_exact():
+    bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x7F7F], dtype=np.uint16)
+    got = O.widen(bits)
+    assert list(got[:2]) == [1.0, -1.0] and got[2] == 3.140625 and got[3] == 0.0
+    assert got[4] == float(np.float32(3.3895313892515355e38))
