@@ -1,0 +1,156 @@
+/*
+ * libsttm -- spatio-temporal token merging for video token tensors on one AMD GPU (gfx950).
+ *
+ * The library turns a video's visual tokens Z_V in R^{T x H x W x C} into the reduced sequence
+ * Z_ST in R^{N_ST x C} (Sec. 3.1 of the STTM paper) in three stages:
+ *
+ *   1. spatial:  per frame, a coarse-to-fine search over a dense quadtree keeps a node when the cosine
+ *                similarity between its mean and each child's mean exceeds tau_S, else descends (Sec. 3.2);
+ *   2. temporal: every kept node of frame t is linked to an overlapping kept node of frame t-1 when their
+ *                cosine similarity exceeds tau_T (top-left-most passing destination wins); chains of links
+ *                are resolved to their common root, the earliest occurrence (Sec. 3.3);
+ *   3. reduce:   every connected graph becomes one token, the average of its member tokens, emitted in
+ *                order of the root's (video, frame, y, x) (Sec. 3.1, 3.3, 3.4).
+ * A fourth call picks tau_S / tau_T from a token budget (the paper sets them by hand, Sec. 4.1, and names an
+ * automatic rule as future work, Sec. 5; the rule here is defined below).
+ *
+ * Conventions
+ *   - plain C ABI; every function returns an sttm_status (0 = ok) unless stated otherwise and never throws
+ *     or aborts; sttm_last_error() gives the message of the last failure on that context.
+ *   - "device" pointers are HIP device memory on the context's device, owned by the caller; the library
+ *     never allocates or frees device memory: all intermediate tables live in a caller-provided workspace.
+ *   - "host" pointers are ordinary host memory, read or written before the call returns.
+ *   - all work is enqueued on the context's stream; calls return before the GPU finishes unless they
+ *     hand a value back through a host pointer (documented per call), in which case they synchronise the stream.
+ *   - feats is contiguous [B, T, H, W, D] (D fastest), B independent videos; tokens are addressed by the
+ *     flat cell index i = ((b*T + t)*H + y)*W + x.  Requirements: 1 <= H, W <= 32; D % 8 == 0;
+ *     B*T*H*W < 2^31; root_grid a power of two <= P, P = smallest power of two >= max(H, W).
+ *   - a grid that is not a power of two is embedded top-left in the P x P grid; padded cells take no part.
+ *   - quadtree level 0 is the finest (single cells), level log2(P/root_grid) holds the roots.
+ *   - similarities are clamped to <= 1 and compared strictly (">"): a threshold >= 1 merges nothing.
+ *     A zero-norm vector has similarity 0 to everything; NaN never passes a threshold.
+ */
+#ifndef STTM_H_
+#define STTM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sttm_ctx sttm_ctx; /* opaque; bound to one device and one stream */
+
+typedef enum {
+  STTM_OK = 0,
+  STTM_ERR_NULL = 1,      /* a required pointer is NULL */
+  STTM_ERR_SHAPE = 2,     /* a dimension or root_grid violates the requirements above */
+  STTM_ERR_DTYPE = 3,     /* unknown sttm_dtype */
+  STTM_ERR_ARG = 4,       /* any other bad argument (e.g. target_keep outside (0, 1]) */
+  STTM_ERR_WORKSPACE = 5, /* no workspace set, or it is smaller than sttm_workspace_bytes() */
+  STTM_ERR_STATE = 6,     /* stage called before the stage it depends on */
+  STTM_ERR_CAPACITY = 7,  /* more output tokens than the caller's capacity */
+  STTM_ERR_HIP = 8        /* a HIP runtime call failed; message holds hipGetErrorString */
+} sttm_status;
+
+typedef enum { STTM_F32 = 0, STTM_BF16 = 1 } sttm_dtype;
+typedef enum { STTM_STAGE_SPATIAL = 0, STTM_STAGE_TEMPORAL = 1 } sttm_stage;
+
+/* Tables sttm_export() can copy out (parity tests compare them with the CPU oracle). F = B*T frames,
+ * NN = nodes per frame over all levels of the P x P pyramid (see sttm_nodes_per_frame). */
+typedef enum {
+  STTM_TBL_CHILD_SIM = 0,  /* float [F, NN]: sigma(parent(n), n) for every node below the root level (Sec. 3.2) */
+  STTM_TBL_MIN_SIM = 1,    /* float [F, NN]: m_n = min over n's existing children; levels >= 1 */
+  STTM_TBL_NORM2 = 2,      /* float [F, NN]: squared norm of the sum of n's valid cells */
+  STTM_TBL_PAIR_SIM = 3,   /* float [F, H*W]: for frame f (t >= 1) and cell q that is the top-left cell of the finer
+                              of the two overlapping nodes (frame t vs t-1): their cosine similarity (Sec. 3.3) */
+  STTM_TBL_BEST_SIM = 4,   /* float [F, H*W]: at the top-left cell of every kept node of a frame t >= 1:
+                              e_n = max similarity over its overlapping nodes of frame t-1 */
+  STTM_TBL_PARENT = 5      /* int32 [F, H*W]: at the top-left cell of every kept node: flat index of the top-left
+                              cell of its destination node in frame t-1, or -1 (no edge; also all other cells) */
+} sttm_table;
+
+/* ---- context ---------------------------------------------------------------------------------------- */
+
+/* Creates a context on HIP device `device`. `hip_stream` is a hipStream_t owned by the caller (NULL = the
+ * default stream); every kernel and copy of this context is enqueued on it. Host memory only is allocated. */
+int sttm_create(sttm_ctx** out, int device, void* hip_stream);
+int sttm_destroy(sttm_ctx* ctx);
+/* Message of the last failing call on ctx (static text if ctx is NULL). Owned by the context. */
+const char* sttm_last_error(const sttm_ctx* ctx);
+/* Number of pyramid nodes per frame (all levels, padded P x P grid), or 0 for an invalid shape. */
+int sttm_nodes_per_frame(int H, int W, int root_grid);
+/* Index of node (level, by, bx) inside a frame's NN-entry table, or -1. */
+int sttm_node_index(int H, int W, int root_grid, int level, int by, int bx);
+
+/* Bytes of device workspace the four stages need for this shape (0 for an invalid shape). */
+size_t sttm_workspace_bytes(int B, int T, int H, int W, int D, int dtype, int root_grid);
+/* Hands the library a device buffer (256-byte aligned) it may overwrite at will until the next
+ * sttm_set_workspace / sttm_destroy. Tables of earlier stages live there between calls. */
+int sttm_set_workspace(sttm_ctx* ctx, void* workspace_dev, size_t bytes);
+
+/* ---- stage 1: spatial quadtree (Sec. 3.2) ------------------------------------------------------------- */
+
+/* Pyramid statistics only: block sums at every level, squared norms, parent-child cosine similarities and
+ * m_n = min over children, into the workspace. Binds the context to this shape. Asynchronous. */
+int sttm_spatial_stats(sttm_ctx* ctx, const void* feats_dev, int dtype, int B, int T, int H, int W, int D,
+                       int root_grid);
+
+/* Granularity decision. tau_s: host array of B thresholds (one per video), or NULL = use the thresholds last
+ * chosen by sttm_budget_threshold(STTM_STAGE_SPATIAL). With tau_s != NULL the statistics are (re)computed from
+ * feats first; with NULL they must already be in the workspace (STTM_ERR_STATE otherwise) and feats is not read.
+ * Outputs (device): node_map int32 [B,T,H,W] = flat index of the top-left cell of the kept node covering the
+ * cell; node_level uint8 [B,T,H,W] = that node's level (may be NULL). Asynchronous. */
+int sttm_spatial_quadtree(sttm_ctx* ctx, const void* feats_dev, int dtype, int B, int T, int H, int W, int D,
+                          int root_grid, const float* tau_s_host, int32_t* node_map_dev, uint8_t* node_level_dev);
+
+/* ---- stage 2: temporal merging (Sec. 3.3) ------------------------------------------------------------- */
+
+/* Similarities between every kept node of frame t >= 1 and each overlapping kept node of frame t-1, and the best
+ * one per node (tables PAIR_SIM, BEST_SIM). node_map / node_level as produced by stage 1 (any valid quadtree
+ * partition per frame is accepted). Needs the stage-1 statistics of the same feats in the workspace. Asynchronous. */
+int sttm_temporal_stats(sttm_ctx* ctx, const void* feats_dev, const int32_t* node_map_dev,
+                        const uint8_t* node_level_dev);
+
+/* Directed edges (similarity > tau_T, top-left-most passing destination), then the common root of every chain.
+ * tau_t: host array of B thresholds, or NULL = those chosen by sttm_budget_threshold(STTM_STAGE_TEMPORAL).
+ * With tau_t != NULL the temporal statistics are (re)computed first; with NULL they must be in the workspace.
+ * Output (device): cluster_ids int32 [B,T,H,W] = flat index of the top-left cell of the root node of the cell's
+ * cluster (= the smallest flat index in the cluster). Asynchronous. */
+int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* node_map_dev,
+                        const uint8_t* node_level_dev, const float* tau_t_host, int32_t* cluster_ids_dev);
+
+/* ---- thresholds from a token budget (Sec. 4.1 / Sec. 5) ------------------------------------------------ */
+
+/* target_keep: host array [B], each in (0, 1]: the fraction of that video's T*H*W tokens the whole path should
+ * keep. The spatial stage aims at floor(sqrt(keep)*T*H*W) nodes, the temporal stage at floor(keep*T*H*W) tokens.
+ * Token count as a function of the threshold is a step function K(tau) = base + sum_j w_j [v_j <= tau] (spatial:
+ * v = max of m over the path from the root to the node, w = children - 1; temporal: v = e_n, w = 1). The threshold
+ * chosen is the midpoint of the last interval between consecutive distinct v on which K <= target (1 if K never
+ * exceeds it, -2 if even merging everything exceeds it). Requires the stage's statistics in the workspace; stores
+ * the thresholds on the device for the following sttm_spatial_quadtree / sttm_temporal_merge call with NULL
+ * thresholds. tau_out: host array [B] or NULL; when non-NULL the stream is synchronised and the values copied out. */
+int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_host, float* tau_out_host);
+
+/* ---- stage 3: gather / average (Sec. 3.1, 3.3, 3.4) ---------------------------------------------------- */
+
+/* One output row per cluster, in ascending cluster id: merged [capacity, D] of out_dtype = mean of the member
+ * cells' features (fp32 accumulation, members in ascending flat index); counts int32 [capacity] = members;
+ * out_ids int32 [capacity] = cluster id; offsets int64 [B+1] = first row of each video, offsets[B] = K (all device,
+ * counts/out_ids may be NULL). Rows beyond capacity are not written. n_out: host pointer or NULL; when non-NULL
+ * the stream is synchronised, *n_out = K and STTM_ERR_CAPACITY is returned if K > capacity. Uses the shape bound by
+ * stage 1; cluster_ids may be any labelling in which a cluster's id is its smallest member's flat index. */
+int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids_dev, int out_dtype,
+                int64_t capacity, void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev,
+                int64_t* offsets_dev, int64_t* n_out_host);
+
+/* ---- inspection ---------------------------------------------------------------------------------------- */
+
+/* Copies an internal table (device to device, asynchronous) into dst_dev; bytes must equal the table's size. */
+int sttm_export(sttm_ctx* ctx, int table, void* dst_dev, size_t bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STTM_H_ */

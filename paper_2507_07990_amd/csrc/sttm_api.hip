@@ -1,0 +1,443 @@
+// C ABI of libsttm: argument checking, workspace layout, stage ordering. See include/sttm.h.
+#include "sttm_dev.h"
+#include "../../include/sttm.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace sttm;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+  size_t part, nrm2, sim, m, sc, tau_s, tau_t, target, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
+  size_t rank, blocksum, key_a, val_a, key_b, val_b, hist, seg, kdev;
+  size_t total;
+};
+
+bool make_geo(int B, int T, int H, int W, int D, int dtype, int root_grid, Geo* g) {
+  if (B < 1 || T < 1 || H < 1 || W < 1 || D < 8 || H > 32 || W > 32 || (D % 8) != 0) return false;
+  if (dtype != STTM_F32 && dtype != STTM_BF16) return false;
+  long long n = (long long)B * T * H * W;
+  if (n >= (1ll << 31) - 1) return false;
+  int P = 1;
+  while (P < (H > W ? H : W)) P *= 2;
+  if (root_grid < 1 || (root_grid & (root_grid - 1)) || root_grid > P) return false;
+  int L = 0;
+  while ((root_grid << L) < P) ++L;
+  g->B = B; g->T = T; g->H = H; g->W = W; g->D = D;
+  g->P = P; g->L = L; g->R = root_grid; g->HW = H * W; g->F = B * T;
+  int base = 0;
+  for (int l = 0; l <= kMaxLevels; ++l) {
+    g->lvl_base[l] = base;
+    if (l <= L) base += (P >> l) * (P >> l);
+  }
+  g->NN = base;
+  g->dtype = dtype;
+  g->vec = dtype == STTM_BF16 ? 8 : 4;
+  g->cch = 64 * g->vec;
+  g->nC = (D + g->cch - 1) / g->cch;
+  g->N = (int)n;
+  return true;
+}
+
+Layout make_layout(const Geo& g) {
+  Layout l;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  const size_t F = g.F, NN = g.NN, N = g.N;
+  l.part = take(F * g.nC * 2 * NN * sizeof(float));
+  l.nrm2 = take(F * NN * sizeof(float));
+  l.sim = take(F * NN * sizeof(float));
+  l.m = take(F * NN * sizeof(float));
+  l.sc = take(F * NN * sizeof(float));
+  l.tau_s = take(g.B * sizeof(float));
+  l.tau_t = take(g.B * sizeof(float));
+  l.target = take(g.B * sizeof(int));
+  l.lvl = take(N);
+  l.pd_part = take(F * g.nC * g.HW * sizeof(float));
+  l.sig = take(N * sizeof(float));
+  l.e = take(N * sizeof(float));
+  l.parent = take(N * sizeof(int32_t));
+  l.ptr_a = take(N * sizeof(int32_t));
+  l.ptr_b = take(N * sizeof(int32_t));
+  l.rank = take(N * sizeof(int32_t));
+  const size_t hist = reduce_hist_entries(g.N);
+  size_t sb = scan_blocks(g.N), sb2 = scan_blocks((int)hist);
+  l.blocksum = take((sb > sb2 ? sb : sb2) * sizeof(int32_t));
+  l.key_a = take(N * sizeof(int32_t));
+  l.val_a = take(N * sizeof(int32_t));
+  l.key_b = take(N * sizeof(int32_t));
+  l.val_b = take(N * sizeof(int32_t));
+  l.hist = take(hist * sizeof(int32_t));
+  l.seg = take((N + 1) * sizeof(int32_t));
+  l.kdev = take(sizeof(int32_t));
+  l.total = off;
+  return l;
+}
+
+}  // namespace
+
+struct sttm_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  bool bound = false;
+  Geo g{};
+  Layout lay{};
+  bool have_spatial = false, have_tau_s = false, have_temporal = false, have_tau_t = false;
+  const void* feats_spatial = nullptr;
+  const int32_t* node_map_temporal = nullptr;  // caller's node map of the last temporal statistics pass
+  std::vector<float> h_tau;                    // host staging that outlives the asynchronous uploads
+  std::vector<int> h_target;
+  std::string err;
+};
+
+namespace {
+
+int fail(sttm_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+
+int hip_check(sttm_ctx* c, hipError_t e, const char* what) {
+  if (e == hipSuccess) return STTM_OK;
+  return fail(c, STTM_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define STTM_HIP(c, call)                                   \
+  do {                                                      \
+    int rc_ = hip_check((c), (call), #call);                \
+    if (rc_ != STTM_OK) return rc_;                         \
+  } while (0)
+
+template <class T> T* at(sttm_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
+
+int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int root_grid) {
+  if (dtype != STTM_F32 && dtype != STTM_BF16) return fail(c, STTM_ERR_DTYPE, "dtype must be STTM_F32 or STTM_BF16");
+  Geo g;
+  if (!make_geo(B, T, H, W, D, dtype, root_grid, &g))
+    return fail(c, STTM_ERR_SHAPE,
+                "need B,T >= 1, 1 <= H,W <= 32, D % 8 == 0, B*T*H*W < 2^31, root_grid a power of two <= P");
+  Layout l = make_layout(g);
+  if (!c->ws) return fail(c, STTM_ERR_WORKSPACE, "no workspace set (sttm_set_workspace)");
+  if (c->ws_bytes < l.total) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "workspace too small: have %zu bytes, need %zu", c->ws_bytes, l.total);
+    return fail(c, STTM_ERR_WORKSPACE, buf);
+  }
+  c->g = g;
+  c->lay = l;
+  c->bound = true;
+  c->have_spatial = c->have_tau_s = c->have_temporal = c->have_tau_t = false;
+  return STTM_OK;
+}
+
+bool same_shape(const Geo& g, int dtype, int B, int T, int H, int W, int D, int root_grid) {
+  return g.dtype == dtype && g.B == B && g.T == T && g.H == H && g.W == W && g.D == D && g.R == root_grid;
+}
+
+int upload_tau(sttm_ctx* c, const float* host, float* dev) {
+  for (int b = 0; b < c->g.B; ++b)
+    if (host[b] != host[b]) return fail(c, STTM_ERR_ARG, "threshold is NaN");
+  c->h_tau.assign(host, host + c->g.B);
+  STTM_HIP(c, hipMemcpyAsync(dev, c->h_tau.data(), c->g.B * sizeof(float), hipMemcpyHostToDevice, c->stream));
+  return STTM_OK;
+}
+
+int after_launch(sttm_ctx* c) { return hip_check(c, hipGetLastError(), "kernel launch"); }
+
+int run_spatial_stats(sttm_ctx* c, const void* feats) {
+  launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), c->stream);
+  launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nrm2), at<float>(c, c->lay.sim),
+                          at<float>(c, c->lay.m), at<float>(c, c->lay.sc), c->stream);
+  int rc = after_launch(c);
+  if (rc == STTM_OK) {
+    c->have_spatial = true;
+    c->have_temporal = false;
+    c->feats_spatial = feats;
+  }
+  return rc;
+}
+
+int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, const uint8_t* node_level) {
+  launch_temporal_dots(c->g, feats, node_map, node_level, at<float>(c, c->lay.pd_part), c->stream);
+  launch_temporal_resolve(c->g, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
+                          at<float>(c, c->lay.sig), at<float>(c, c->lay.e), c->stream);
+  int rc = after_launch(c);
+  if (rc == STTM_OK) {
+    c->have_temporal = true;
+    c->node_map_temporal = node_map;
+  }
+  return rc;
+}
+
+int check_feats(sttm_ctx* c, const void* feats) {
+  if (!feats) return fail(c, STTM_ERR_NULL, "feats is NULL");
+  if (reinterpret_cast<uintptr_t>(feats) & 15) return fail(c, STTM_ERR_ARG, "feats must be 16-byte aligned");
+  return STTM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sttm_create(sttm_ctx** out, int device, void* hip_stream) {
+  if (!out) return STTM_ERR_NULL;
+  *out = nullptr;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return STTM_ERR_HIP;
+  sttm_ctx* c = new (std::nothrow) sttm_ctx();
+  if (!c) return STTM_ERR_HIP;
+  c->device = device;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  *out = c;
+  return STTM_OK;
+}
+
+int sttm_destroy(sttm_ctx* ctx) {
+  delete ctx;
+  return STTM_OK;
+}
+
+const char* sttm_last_error(const sttm_ctx* ctx) {
+  if (!ctx) return "null context";
+  return ctx->err.c_str();
+}
+
+int sttm_nodes_per_frame(int H, int W, int root_grid) {
+  Geo g;
+  if (!make_geo(1, 1, H, W, 8, STTM_F32, root_grid, &g)) return 0;
+  return g.NN;
+}
+
+int sttm_node_index(int H, int W, int root_grid, int level, int by, int bx) {
+  Geo g;
+  if (!make_geo(1, 1, H, W, 8, STTM_F32, root_grid, &g)) return -1;
+  if (level < 0 || level > g.L) return -1;
+  const int side = g.P >> level;
+  if (by < 0 || bx < 0 || by >= side || bx >= side) return -1;
+  return node_index(g, level, by, bx);
+}
+
+size_t sttm_workspace_bytes(int B, int T, int H, int W, int D, int dtype, int root_grid) {
+  Geo g;
+  if (!make_geo(B, T, H, W, D, dtype, root_grid, &g)) return 0;
+  return make_layout(g).total;
+}
+
+int sttm_set_workspace(sttm_ctx* ctx, void* workspace_dev, size_t bytes) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!workspace_dev && bytes) return fail(ctx, STTM_ERR_NULL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace_dev) & (kAlign - 1))
+    return fail(ctx, STTM_ERR_ARG, "workspace must be 256-byte aligned");
+  ctx->ws = static_cast<char*>(workspace_dev);
+  ctx->ws_bytes = bytes;
+  ctx->bound = false;
+  ctx->have_spatial = ctx->have_tau_s = ctx->have_temporal = ctx->have_tau_t = false;
+  return STTM_OK;
+}
+
+int sttm_spatial_stats(sttm_ctx* ctx, const void* feats_dev, int dtype, int B, int T, int H, int W, int D,
+                       int root_grid) {
+  if (!ctx) return STTM_ERR_NULL;
+  int rc = check_feats(ctx, feats_dev);
+  if (rc) return rc;
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  rc = bind_shape(ctx, dtype, B, T, H, W, D, root_grid);
+  if (rc) return rc;
+  return run_spatial_stats(ctx, feats_dev);
+}
+
+int sttm_spatial_quadtree(sttm_ctx* ctx, const void* feats_dev, int dtype, int B, int T, int H, int W, int D,
+                          int root_grid, const float* tau_s_host, int32_t* node_map_dev,
+                          uint8_t* node_level_dev) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!node_map_dev) return fail(ctx, STTM_ERR_NULL, "node_map is NULL");
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  int rc;
+  if (tau_s_host) {
+    rc = check_feats(ctx, feats_dev);
+    if (rc) return rc;
+    rc = bind_shape(ctx, dtype, B, T, H, W, D, root_grid);
+    if (rc) return rc;
+    rc = upload_tau(ctx, tau_s_host, at<float>(ctx, ctx->lay.tau_s));
+    if (rc) return rc;
+    ctx->have_tau_s = true;
+    rc = run_spatial_stats(ctx, feats_dev);
+    if (rc) return rc;
+  } else {
+    if (!ctx->bound || !ctx->have_spatial)
+      return fail(ctx, STTM_ERR_STATE, "no spatial statistics in the workspace (call sttm_spatial_stats first)");
+    if (!same_shape(ctx->g, dtype, B, T, H, W, D, root_grid))
+      return fail(ctx, STTM_ERR_SHAPE, "shape differs from the one the statistics were computed for");
+    if (!ctx->have_tau_s)
+      return fail(ctx, STTM_ERR_STATE, "no spatial threshold chosen (call sttm_budget_threshold first)");
+  }
+  launch_spatial_decide(ctx->g, at<float>(ctx, ctx->lay.m), at<float>(ctx, ctx->lay.tau_s), node_map_dev,
+                        node_level_dev, ctx->stream);
+  return after_launch(ctx);
+}
+
+static int temporal_prepare(sttm_ctx* ctx, const void* feats_dev, const int32_t* node_map_dev,
+                            const uint8_t** node_level_dev) {
+  if (!node_map_dev) return fail(ctx, STTM_ERR_NULL, "node_map is NULL");
+  if (!ctx->bound || !ctx->have_spatial)
+    return fail(ctx, STTM_ERR_STATE, "temporal stage needs the spatial statistics of the same features");
+  int rc = check_feats(ctx, feats_dev);
+  if (rc) return rc;
+  if (!*node_level_dev) {
+    launch_node_levels(ctx->g, node_map_dev, at<uint8_t>(ctx, ctx->lay.lvl), ctx->stream);
+    *node_level_dev = at<uint8_t>(ctx, ctx->lay.lvl);
+  }
+  return STTM_OK;
+}
+
+int sttm_temporal_stats(sttm_ctx* ctx, const void* feats_dev, const int32_t* node_map_dev,
+                        const uint8_t* node_level_dev) {
+  if (!ctx) return STTM_ERR_NULL;
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  int rc = temporal_prepare(ctx, feats_dev, node_map_dev, &node_level_dev);
+  if (rc) return rc;
+  return run_temporal_stats(ctx, feats_dev, node_map_dev, node_level_dev);
+}
+
+int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* node_map_dev,
+                        const uint8_t* node_level_dev, const float* tau_t_host, int32_t* cluster_ids_dev) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!cluster_ids_dev) return fail(ctx, STTM_ERR_NULL, "cluster_ids is NULL");
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  int rc = temporal_prepare(ctx, feats_dev, node_map_dev, &node_level_dev);
+  if (rc) return rc;
+  if (tau_t_host) {
+    rc = upload_tau(ctx, tau_t_host, at<float>(ctx, ctx->lay.tau_t));
+    if (rc) return rc;
+    ctx->have_tau_t = true;
+    rc = run_temporal_stats(ctx, feats_dev, node_map_dev, node_level_dev);
+    if (rc) return rc;
+  } else {
+    if (!ctx->have_temporal)
+      return fail(ctx, STTM_ERR_STATE, "no temporal statistics in the workspace (call sttm_temporal_stats first)");
+    if (!ctx->have_tau_t)
+      return fail(ctx, STTM_ERR_STATE, "no temporal threshold chosen (call sttm_budget_threshold first)");
+  }
+  launch_temporal_parent(ctx->g, node_map_dev, node_level_dev, at<float>(ctx, ctx->lay.sig),
+                         at<float>(ctx, ctx->lay.tau_t), at<int32_t>(ctx, ctx->lay.parent),
+                         at<int32_t>(ctx, ctx->lay.ptr_a), ctx->stream);
+  launch_roots(ctx->g, at<int32_t>(ctx, ctx->lay.ptr_a), at<int32_t>(ctx, ctx->lay.ptr_b), node_map_dev,
+               cluster_ids_dev, ctx->stream);
+  return after_launch(ctx);
+}
+
+int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_host, float* tau_out_host) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!target_keep_host) return fail(ctx, STTM_ERR_NULL, "target_keep is NULL");
+  if (stage != STTM_STAGE_SPATIAL && stage != STTM_STAGE_TEMPORAL) return fail(ctx, STTM_ERR_ARG, "unknown stage");
+  if (!ctx->bound || !ctx->have_spatial)
+    return fail(ctx, STTM_ERR_STATE, "no spatial statistics in the workspace");
+  if (stage == STTM_STAGE_TEMPORAL && !ctx->have_temporal)
+    return fail(ctx, STTM_ERR_STATE, "no temporal statistics in the workspace");
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  const Geo& g = ctx->g;
+  const double thw = (double)g.T * g.HW;
+  for (int b = 0; b < g.B; ++b) {
+    const double k = target_keep_host[b];
+    if (!(k > 0.0 && k <= 1.0)) return fail(ctx, STTM_ERR_ARG, "target_keep must be in (0, 1]");
+  }
+  ctx->h_target.resize(g.B);
+  for (int b = 0; b < g.B; ++b) {
+    const double k = target_keep_host[b];
+    ctx->h_target[b] = (int)std::floor((stage == STTM_STAGE_SPATIAL ? std::sqrt(k) : k) * thw);
+  }
+  int rc;
+  STTM_HIP(ctx, hipMemcpyAsync(at<int>(ctx, ctx->lay.target), ctx->h_target.data(), g.B * sizeof(int),
+                               hipMemcpyHostToDevice, ctx->stream));
+  float* tau_dev = at<float>(ctx, stage == STTM_STAGE_SPATIAL ? ctx->lay.tau_s : ctx->lay.tau_t);
+  if (stage == STTM_STAGE_SPATIAL)
+    launch_select_spatial(g, at<float>(ctx, ctx->lay.sc), at<int>(ctx, ctx->lay.target), tau_dev, ctx->stream);
+  else
+    launch_select_temporal(g, ctx->node_map_temporal, at<float>(ctx, ctx->lay.e), at<int>(ctx, ctx->lay.target),
+                           tau_dev, ctx->stream);
+  rc = after_launch(ctx);
+  if (rc) return rc;
+  if (stage == STTM_STAGE_SPATIAL) ctx->have_tau_s = true; else ctx->have_tau_t = true;
+  if (tau_out_host) {
+    STTM_HIP(ctx, hipMemcpyAsync(tau_out_host, tau_dev, g.B * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+    STTM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  }
+  return STTM_OK;
+}
+
+int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids_dev, int out_dtype,
+                int64_t capacity, void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev,
+                int64_t* offsets_dev, int64_t* n_out_host) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!cluster_ids_dev || !merged_dev || !offsets_dev)
+    return fail(ctx, STTM_ERR_NULL, "cluster_ids, merged and offsets are required");
+  if (out_dtype != STTM_F32 && out_dtype != STTM_BF16) return fail(ctx, STTM_ERR_DTYPE, "bad out_dtype");
+  if (capacity < 0) return fail(ctx, STTM_ERR_ARG, "capacity < 0");
+  if (!ctx->bound) return fail(ctx, STTM_ERR_STATE, "no shape bound (run the spatial stage first)");
+  int rc = check_feats(ctx, feats_dev);
+  if (rc) return rc;
+  if (reinterpret_cast<uintptr_t>(merged_dev) & 15) return fail(ctx, STTM_ERR_ARG, "merged must be 16-byte aligned");
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  ReduceBuffers rb;
+  rb.rank = at<int32_t>(ctx, ctx->lay.rank);
+  rb.blocksum = at<int32_t>(ctx, ctx->lay.blocksum);
+  rb.key_a = at<int32_t>(ctx, ctx->lay.key_a);
+  rb.val_a = at<int32_t>(ctx, ctx->lay.val_a);
+  rb.key_b = at<int32_t>(ctx, ctx->lay.key_b);
+  rb.val_b = at<int32_t>(ctx, ctx->lay.val_b);
+  rb.hist = at<int32_t>(ctx, ctx->lay.hist);
+  rb.seg = at<int32_t>(ctx, ctx->lay.seg);
+  rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
+  launch_reduce(ctx->g, feats_dev, cluster_ids_dev, out_dtype, capacity, merged_dev, counts_dev, out_ids_dev,
+                offsets_dev, rb, ctx->stream);
+  rc = after_launch(ctx);
+  if (rc) return rc;
+  if (n_out_host) {
+    int32_t k = 0;
+    STTM_HIP(ctx, hipMemcpyAsync(&k, rb.kdev, sizeof k, hipMemcpyDeviceToHost, ctx->stream));
+    STTM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    *n_out_host = k;
+    if (k > capacity) {
+      char buf[128];
+      snprintf(buf, sizeof buf, "%d output tokens exceed the capacity of %lld rows", k, (long long)capacity);
+      return fail(ctx, STTM_ERR_CAPACITY, buf);
+    }
+  }
+  return STTM_OK;
+}
+
+int sttm_export(sttm_ctx* ctx, int table, void* dst_dev, size_t bytes) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!dst_dev) return fail(ctx, STTM_ERR_NULL, "dst is NULL");
+  if (!ctx->bound || !ctx->have_spatial) return fail(ctx, STTM_ERR_STATE, "nothing to export yet");
+  const Geo& g = ctx->g;
+  size_t off = 0, want = 0;
+  bool temporal = false;
+  switch (table) {
+    case STTM_TBL_CHILD_SIM: off = ctx->lay.sim; want = (size_t)g.F * g.NN * 4; break;
+    case STTM_TBL_MIN_SIM: off = ctx->lay.m; want = (size_t)g.F * g.NN * 4; break;
+    case STTM_TBL_NORM2: off = ctx->lay.nrm2; want = (size_t)g.F * g.NN * 4; break;
+    case STTM_TBL_PAIR_SIM: off = ctx->lay.sig; want = (size_t)g.N * 4; temporal = true; break;
+    case STTM_TBL_BEST_SIM: off = ctx->lay.e; want = (size_t)g.N * 4; temporal = true; break;
+    case STTM_TBL_PARENT: off = ctx->lay.parent; want = (size_t)g.N * 4; temporal = true; break;
+    default: return fail(ctx, STTM_ERR_ARG, "unknown table");
+  }
+  if (temporal && !ctx->have_temporal) return fail(ctx, STTM_ERR_STATE, "no temporal statistics yet");
+  if (bytes != want) return fail(ctx, STTM_ERR_ARG, "byte count does not match the table size");
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  STTM_HIP(ctx, hipMemcpyAsync(dst_dev, ctx->ws + off, want, hipMemcpyDeviceToDevice, ctx->stream));
+  return STTM_OK;
+}
+
+}  // extern "C"

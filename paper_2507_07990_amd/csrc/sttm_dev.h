@@ -1,0 +1,146 @@
+// Shared declarations of the HIP kernels behind libsttm (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sttm {
+
+constexpr int kWave = 64;
+constexpr int kMaxLevels = 6;  // P <= 32  =>  levels 0..5
+
+// Problem geometry, passed by value to every kernel.
+struct Geo {
+  int B, T, H, W, D;
+  int P;         // padded power-of-two grid side
+  int L;         // root level = log2(P / R)
+  int R;         // root nodes per side
+  int HW;        // valid cells per frame
+  int F;         // frames = B*T
+  int NN;        // pyramid nodes per frame (levels 0..L of the P x P grid)
+  int lvl_base[kMaxLevels + 1];
+  int dtype;     // 0 = f32, 1 = bf16
+  int vec;       // channels per lane per 16-byte load: 4 (f32) / 8 (bf16)
+  int cch;       // channels per chunk = 64 * vec (one wavefront spans one chunk of a token row)
+  int nC;        // chunks per row = ceil(D / cch)
+  int N;         // B*T*H*W
+};
+
+__host__ __device__ inline int node_index(const Geo& g, int lvl, int by, int bx) {
+  return g.lvl_base[lvl] + by * (g.P >> lvl) + bx;
+}
+
+__host__ __device__ inline bool node_exists(const Geo& g, int lvl, int by, int bx) {
+  return (by << lvl) < g.H && (bx << lvl) < g.W;
+}
+
+// Decodes a per-frame node index into (level, by, bx).
+__host__ __device__ inline void node_decode(const Geo& g, int idx, int& lvl, int& by, int& bx) {
+  lvl = 0;
+  while (lvl < g.L && idx >= g.lvl_base[lvl + 1]) ++lvl;
+  int r = idx - g.lvl_base[lvl];
+  int side = g.P >> lvl;
+  by = r / side;
+  bx = r - by * side;
+}
+
+// ---- feature row access: one lane owns `VEC` consecutive channels ------------------------------------
+template <int DT> struct Row;  // DT: 0 = f32, 1 = bf16
+
+template <> struct Row<0> {
+  static constexpr int VEC = 4;
+  typedef float4 Raw;
+  typedef float Elem;
+  __device__ static inline Raw zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ static inline void unpack(const Raw& r, float (&x)[4]) {
+    x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
+  }
+};
+
+template <> struct Row<1> {
+  static constexpr int VEC = 8;
+  typedef uint4 Raw;
+  typedef uint16_t Elem;
+  __device__ static inline Raw zero() { return make_uint4(0u, 0u, 0u, 0u); }
+  __device__ static inline void unpack(const Raw& r, float (&x)[8]) {
+    x[0] = __uint_as_float(r.x << 16); x[1] = __uint_as_float(r.x & 0xffff0000u);
+    x[2] = __uint_as_float(r.y << 16); x[3] = __uint_as_float(r.y & 0xffff0000u);
+    x[4] = __uint_as_float(r.z << 16); x[5] = __uint_as_float(r.z & 0xffff0000u);
+    x[6] = __uint_as_float(r.w << 16); x[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+};
+
+__device__ inline uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// cos(a, b) from the dot product and the two squared norms: clamped to <= 1, 0 for a zero norm.
+__device__ inline float cosine_from(float dot, float na2, float nb2) {
+  if (na2 == 0.f || nb2 == 0.f) return 0.f;
+  float v = dot / (sqrtf(na2) * sqrtf(nb2));
+  return v > 1.f ? 1.f : v;
+}
+
+// Monotone map float -> uint32 (order preserving for all non-NaN values).
+__device__ inline uint32_t float_key(float v) {
+  uint32_t u = __float_as_uint(v);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ inline float key_float(uint32_t k) {
+  uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+  return __uint_as_float(u);
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Orders LDS traffic between the lanes of one wavefront (no cross-wave synchronisation).
+__device__ inline void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
+struct Workspace;  // see sttm_api.hip
+
+void launch_pyramid_stats(const Geo& g, const void* feats, float* part, hipStream_t s);
+void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m, float* sc,
+                             hipStream_t s);
+void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
+                           uint8_t* node_level, hipStream_t s);
+void launch_select_spatial(const Geo& g, const float* sc, const int* target, float* tau, hipStream_t s);
+void launch_select_temporal(const Geo& g, const int32_t* node_map, const float* e, const int* target,
+                            float* tau, hipStream_t s);
+void launch_temporal_dots(const Geo& g, const void* feats, const int32_t* node_map, const uint8_t* node_level,
+                          float* pd_part, hipStream_t s);
+void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
+                             const float* pd_part, const float* nrm2, float* sig, float* e, hipStream_t s);
+void launch_temporal_parent(const Geo& g, const int32_t* node_map, const uint8_t* node_level, const float* sig,
+                            const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s);
+void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* node_map, int32_t* cluster_ids,
+                  hipStream_t s);
+void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_level, hipStream_t s);
+
+struct ReduceBuffers {
+  int32_t* rank;      // [N]   exclusive scan of root flags
+  int32_t* blocksum;  // scan scratch
+  int32_t* key_a;     // [N] sort ping
+  int32_t* val_a;     // [N]
+  int32_t* key_b;     // [N] sort pong
+  int32_t* val_b;     // [N]
+  int32_t* hist;      // radix histogram table
+  int32_t* seg;       // [N+1] first sorted position of every output row
+  int32_t* kdev;      // [1] number of clusters
+};
+void launch_reduce(const Geo& g, const void* feats, const int32_t* cluster_ids, int out_dtype, int64_t capacity,
+                   void* merged, int32_t* counts, int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
+                   hipStream_t s);
+size_t reduce_hist_entries(int N);
+size_t scan_blocks(int n);
+
+}  // namespace sttm

@@ -1,0 +1,322 @@
+// Reduce stage (Sec. 3.1 / 3.3 / 3.4): one output token per cluster = mean of its member tokens, rows in
+// ascending cluster id. Integer plumbing: rank of every root (prefix sum), member lists (stable radix
+// sort of the cells by cluster id), then the one feature pass that gathers and averages.
+#include "sttm_dev.h"
+
+namespace sttm {
+
+// ---- exclusive prefix sum over int32 -------------------------------------------------------------------
+constexpr int kScanBlock = 256;
+constexpr int kScanPer = 8;
+constexpr int kScanTile = kScanBlock * kScanPer;  // 2048 elements per workgroup
+
+size_t scan_blocks(int n) { return (size_t)(n + kScanTile - 1) / kScanTile; }
+
+// MODE 0: input = in[i]; MODE 1: input = (in[i] == i) (root flags of a cluster map)
+template <int MODE> __device__ inline int scan_input(const int32_t* in, int i) {
+  return MODE == 0 ? in[i] : (in[i] == i ? 1 : 0);
+}
+
+__device__ inline int block_exclusive_scan(int v, int* total) {
+  // 256 threads; returns the exclusive prefix of v within the workgroup
+  __shared__ int wsum[kScanBlock / kWave];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kScanBlock / kWave; ++w) {
+    if (w < wave) base += wsum[w];
+    tot += wsum[w];
+  }
+  __syncthreads();
+  *total = tot;
+  return base + inc - v;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kScanBlock) void k_scan_local(int n, const int32_t* in, int32_t* out,
+                                                           int32_t* __restrict__ blocksum) {
+  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanPer;
+  int v[kScanPer], s = 0;
+#pragma unroll
+  for (int j = 0; j < kScanPer; ++j) {
+    v[j] = (base + j < n) ? scan_input<MODE>(in, base + j) : 0;
+    s += v[j];
+  }
+  int total;
+  int ex = block_exclusive_scan(s, &total);
+#pragma unroll
+  for (int j = 0; j < kScanPer; ++j) {
+    if (base + j < n) out[base + j] = ex;
+    ex += v[j];
+  }
+  if (threadIdx.x == 0) blocksum[blockIdx.x] = total;
+}
+
+// One workgroup scans the per-block totals in place (exclusive), sequentially over tiles.
+__global__ __launch_bounds__(kScanBlock) void k_scan_tops(int nb, int32_t* __restrict__ blocksum,
+                                                          int32_t* __restrict__ grand_total) {
+  int carry = 0;
+  for (int t0 = 0; t0 < nb; t0 += kScanBlock) {
+    const int i = t0 + threadIdx.x;
+    const int v = i < nb ? blocksum[i] : 0;
+    int total;
+    const int ex = block_exclusive_scan(v, &total);
+    if (i < nb) blocksum[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0 && grand_total) *grand_total = carry;
+}
+
+__global__ __launch_bounds__(kScanBlock) void k_scan_add(int n, int32_t* __restrict__ out,
+                                                         const int32_t* __restrict__ blocksum) {
+  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanPer;
+  const int add = blocksum[blockIdx.x];
+#pragma unroll
+  for (int j = 0; j < kScanPer; ++j)
+    if (base + j < n) out[base + j] += add;
+}
+
+template <int MODE>
+static void exclusive_scan(int n, const int32_t* in, int32_t* out, int32_t* blocksum, int32_t* total,
+                           hipStream_t s) {
+  const int nb = (int)scan_blocks(n);
+  hipLaunchKernelGGL(k_scan_local<MODE>, dim3(nb), dim3(kScanBlock), 0, s, n, in, out, blocksum);
+  hipLaunchKernelGGL(k_scan_tops, dim3(1), dim3(kScanBlock), 0, s, nb, blocksum, total);
+  hipLaunchKernelGGL(k_scan_add, dim3(nb), dim3(kScanBlock), 0, s, n, out, blocksum);
+}
+
+// ---- stable LSD radix sort of (key, value) pairs, 8-bit digits --------------------------------------
+// A workgroup is one wavefront that owns kSortTile consecutive elements; it handles them 64 at a time in
+// index order, so ranks inside the tile are stable without any cross-wave ordering.
+constexpr int kSortTile = 2048;
+constexpr int kRadix = 256;
+
+size_t reduce_hist_entries(int N) { return (size_t)kRadix * ((N + kSortTile - 1) / kSortTile); }
+
+__global__ __launch_bounds__(64) void k_sort_hist(int n, int shift, const int32_t* __restrict__ keys,
+                                                  int32_t* __restrict__ hist, int nblocks) {
+  __shared__ int cnt[kRadix];
+  for (int j = threadIdx.x; j < kRadix; j += 64) cnt[j] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * kSortTile;
+  for (int o = threadIdx.x; o < kSortTile; o += 64) {
+    const int i = base + o;
+    if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & (kRadix - 1)], 1);
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < kRadix; j += 64) hist[j * nblocks + blockIdx.x] = cnt[j];
+}
+
+__global__ __launch_bounds__(64) void k_sort_scatter(int n, int shift, const int32_t* __restrict__ keys,
+                                                     const int32_t* __restrict__ vals,
+                                                     int32_t* __restrict__ keys_out,
+                                                     int32_t* __restrict__ vals_out,
+                                                     const int32_t* __restrict__ hist, int nblocks,
+                                                     int first_pass) {
+  __shared__ int cur[kRadix];
+  const int lane = threadIdx.x;
+  for (int j = lane; j < kRadix; j += 64) cur[j] = hist[j * nblocks + blockIdx.x];
+  __syncthreads();
+  const int base = blockIdx.x * kSortTile;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  for (int o = 0; o < kSortTile; o += 64) {
+    const int i = base + o + lane;
+    const bool ok = i < n;
+    const int key = ok ? keys[i] : 0;
+    const int val = ok ? (first_pass ? i : vals[i]) : 0;
+    const int digit = (key >> shift) & (kRadix - 1);
+    // lanes holding the same digit
+    unsigned long long same = __ballot(ok);
+#pragma unroll
+    for (int bit = 0; bit < 8; ++bit) {
+      const unsigned long long m = __ballot((digit >> bit) & 1);
+      same &= ((digit >> bit) & 1) ? m : ~m;
+    }
+    if (ok) {
+      const int rank = __popcll(same & below);
+      const int dst = cur[digit] + rank;
+      keys_out[dst] = key;
+      vals_out[dst] = val;
+    }
+    __syncthreads();
+    if (ok && (same >> lane) >> 1 == 0)  // highest lane of its digit group advances the cursor
+      cur[digit] += __popcll(same);
+    __syncthreads();
+  }
+}
+
+// ---- ranks, segment starts, bookkeeping outputs ------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fill_i32(int n, int32_t* __restrict__ p, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// out_ids, per-video offsets and the cluster count from the exclusive scan of the root flags.
+__global__ __launch_bounds__(256) void k_root_outputs(Geo g, const int32_t* __restrict__ cluster_ids,
+                                                      const int32_t* __restrict__ rank,
+                                                      const int32_t* __restrict__ kdev, int64_t capacity,
+                                                      int32_t* __restrict__ out_ids,
+                                                      int64_t* __restrict__ offsets) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= g.N) return;
+  if (cluster_ids[i] == i && out_ids && rank[i] < capacity) out_ids[rank[i]] = i;
+  const int per_video = g.T * g.HW;
+  if (i % per_video == 0) offsets[i / per_video] = rank[i];
+  if (i == 0) offsets[g.B] = *kdev;
+}
+
+// seg[k] = first sorted position of output row k, seg[K] = N; counts from consecutive starts.
+__global__ __launch_bounds__(256) void k_segments(int n, const int32_t* __restrict__ skey,
+                                                  const int32_t* __restrict__ rank,
+                                                  const int32_t* __restrict__ kdev, int32_t* __restrict__ seg) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= n) return;
+  const int key = skey[p];
+  if (p == 0 || skey[p - 1] != key) seg[rank[key]] = p;
+  if (p == n - 1) seg[*kdev] = n;
+}
+
+__global__ __launch_bounds__(256) void k_counts(const int32_t* __restrict__ kdev, const int32_t* __restrict__ seg,
+                                                int64_t capacity, int32_t* __restrict__ counts) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < *kdev && k < capacity) counts[k] = seg[k + 1] - seg[k];
+}
+
+// ------------------------------------------------------------------------------------------------
+// k_reduce: the gather/average pass. Work item j = the clusters whose member list starts at a sorted
+// position in [j*kItem, (j+1)*kItem). One wavefront per (item, chunk of the row); a lane owns VEC
+// channels, sums the member rows in list order (ascending flat index) in fp32 and stores the mean.
+// ------------------------------------------------------------------------------------------------
+constexpr int kItem = 16;
+
+template <int DT, int ODT>
+__global__ __launch_bounds__(1024) void k_reduce(Geo g, const void* __restrict__ feats_v,
+                                                 const int32_t* __restrict__ skey,
+                                                 const int32_t* __restrict__ order,
+                                                 const int32_t* __restrict__ rank,
+                                                 const int32_t* __restrict__ seg, int64_t capacity,
+                                                 void* __restrict__ merged_v) {
+  typedef Row<DT> R;
+  constexpr int VEC = R::VEC;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  const int p0 = blockIdx.x * kItem, p1 = min(p0 + kItem, g.N);
+  const typename R::Elem* fb = reinterpret_cast<const typename R::Elem*>(feats_v);
+  for (int chunk = wave; chunk < g.nC; chunk += nw) {
+    const int ch0 = chunk * g.cch + lane * VEC;
+    const bool act = ch0 < g.D;
+    int p = p0;
+    // skip the tail of a cluster that started in an earlier item
+    if (p > 0) {
+      const int prev = skey[p - 1];
+      while (p < p1 && skey[p] == prev) ++p;
+    }
+    while (p < p1) {
+      const int k = rank[skey[p]];
+      const int end = seg[k + 1];
+      float acc[VEC];
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+      const int cnt = end - p;
+      int q = p;
+      for (; q + 4 <= end; q += 4) {
+        typename R::Raw r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          r[j] = R::zero();
+          if (act) r[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q + j] * g.D + ch0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float t[VEC];
+          R::unpack(r[j], t);
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[v] += t[v];
+        }
+      }
+      for (; q < end; ++q) {
+        typename R::Raw r = R::zero();
+        if (act) r = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q] * g.D + ch0);
+        float t[VEC];
+        R::unpack(r, t);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += t[v];
+      }
+      if (act && k < capacity) {
+        const float inv = 1.f / (float)cnt;
+        if (ODT == 0) {
+          float* o = reinterpret_cast<float*>(merged_v) + (size_t)k * g.D + ch0;
+#pragma unroll
+          for (int v = 0; v < VEC; v += 4)
+            *reinterpret_cast<float4*>(o + v) =
+                make_float4(acc[v] * inv, acc[v + 1] * inv, acc[v + 2] * inv, acc[v + 3] * inv);
+        } else {
+          uint16_t* o = reinterpret_cast<uint16_t*>(merged_v) + (size_t)k * g.D + ch0;
+          uint32_t w[VEC / 2];
+#pragma unroll
+          for (int v = 0; v < VEC; v += 2)
+            w[v / 2] = f32_to_bf16_rne(acc[v] * inv) | (f32_to_bf16_rne(acc[v + 1] * inv) << 16);
+          if (VEC == 8)
+            *reinterpret_cast<uint4*>(o) = make_uint4(w[0], w[1], w[2 % (VEC / 2)], w[3 % (VEC / 2)]);
+          else
+            *reinterpret_cast<uint2*>(o) = make_uint2(w[0], w[1]);
+        }
+      }
+      p = end;
+    }
+  }
+}
+
+void launch_reduce(const Geo& g, const void* feats, const int32_t* cluster_ids, int out_dtype, int64_t capacity,
+                   void* merged, int32_t* counts, int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
+                   hipStream_t s) {
+  const int N = g.N;
+  const dim3 b256(256), gN((N + 255) / 256);
+  // ranks of the roots, K, per-video offsets, out_ids
+  exclusive_scan<1>(N, cluster_ids, rb.rank, rb.blocksum, rb.kdev, s);
+  hipLaunchKernelGGL(k_root_outputs, gN, b256, 0, s, g, cluster_ids, rb.rank, rb.kdev, capacity, out_ids,
+                     offsets);
+  // member lists: stable sort of the cells by cluster id
+  int bits = 1;
+  while ((1ll << bits) < (long long)N) ++bits;
+  const int nblocks = (N + kSortTile - 1) / kSortTile;
+  const int32_t* kin = cluster_ids;
+  const int32_t* vin = nullptr;
+  int32_t* kout = rb.key_a;
+  int32_t* vout = rb.val_a;
+  int pass = 0;
+  for (int shift = 0; shift < bits; shift += 8, ++pass) {
+    hipLaunchKernelGGL(k_sort_hist, dim3(nblocks), dim3(64), 0, s, N, shift, kin, rb.hist, nblocks);
+    exclusive_scan<0>(kRadix * nblocks, rb.hist, rb.hist, rb.blocksum, (int32_t*)nullptr, s);
+    hipLaunchKernelGGL(k_sort_scatter, dim3(nblocks), dim3(64), 0, s, N, shift, kin, vin, kout, vout, rb.hist,
+                       nblocks, pass == 0 ? 1 : 0);
+    kin = kout;
+    vin = vout;
+    if (kout == rb.key_a) { kout = rb.key_b; vout = rb.val_b; } else { kout = rb.key_a; vout = rb.val_a; }
+  }
+  const int32_t* skey = kin;
+  const int32_t* order = vin;
+  hipLaunchKernelGGL(k_segments, gN, b256, 0, s, N, skey, rb.rank, rb.kdev, rb.seg);
+  if (counts) hipLaunchKernelGGL(k_counts, gN, b256, 0, s, rb.kdev, rb.seg, capacity, counts);
+  // the feature pass
+  const int nitems = (N + kItem - 1) / kItem;
+  const int nw = g.nC < 16 ? g.nC : 16;
+  dim3 grid(nitems), block(64 * nw);
+#define STTM_REDUCE(DT, ODT) \
+  hipLaunchKernelGGL((k_reduce<DT, ODT>), grid, block, 0, s, g, feats, skey, order, rb.rank, rb.seg, capacity, merged)
+  if (g.dtype == 1) {
+    if (out_dtype == 1) STTM_REDUCE(1, 1); else STTM_REDUCE(1, 0);
+  } else {
+    if (out_dtype == 1) STTM_REDUCE(0, 1); else STTM_REDUCE(0, 0);
+  }
+#undef STTM_REDUCE
+}
+
+}  // namespace sttm

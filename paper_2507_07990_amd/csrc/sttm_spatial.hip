@@ -1,0 +1,538 @@
+// Spatial stage (Sec. 3.2): pyramid sums, squared norms, parent-child cosine similarities, the
+// coarse-to-fine decision, and the budget-driven threshold for it.
+#include "sttm_dev.h"
+
+namespace sttm {
+
+// ------------------------------------------------------------------------------------------------
+// k_pyramid_stats: the one pass over the features of the spatial stage.
+//
+// Grid (chunk, frame); a workgroup is 4 wavefronts. A lane owns VEC consecutive channels of one chunk
+// of the token rows, so all pyramid sums are private to the lane and only the scalars (squared norms,
+// parent-child dot products) are reduced across lanes: each wavefront stages its per-lane partial
+// scalars in LDS as [scalar][lane] and then lets lane r add up row r.
+// A wavefront walks "units" = 8x8 cell blocks (level 3) quadrant by quadrant: 4 tiles (4x4, level 2)
+// of 4 level-1 blocks of 4 cells. Levels above 3 are finished by the whole workgroup from the
+// per-channel level-3 sums kept in LDS.
+// Output: part[f][chunk][0][node] = partial squared norm of the node's sum over this chunk's channels,
+//         part[f][chunk][1][node] = partial dot product of the node's sum with its parent's sum.
+// ------------------------------------------------------------------------------------------------
+constexpr int kTileRows = 40;    // 16 n0 + 16 d0 + 4 n1 + 4 d1
+constexpr int kRowStride = 68;   // 64 lanes + pad, keeps 16-byte alignment of every row
+constexpr int kStatsWaves = 4;
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
+                                                       float* __restrict__ part) {
+  typedef Row<DT> R;
+  constexpr int VEC = R::VEC;
+  extern __shared__ float smem[];
+  const int chunk = blockIdx.x, f = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ch0 = chunk * g.cch + lane * VEC;
+  const bool act = ch0 < g.D;
+  const int H = g.H, W = g.W, P = g.P, L = g.L;
+  float* tb = smem + wave * (kTileRows * kRowStride);
+  float* s3buf = smem + kStatsWaves * (kTileRows * kRowStride);
+  float* pn = part + (size_t)(f * g.nC + chunk) * 2 * g.NN;
+  float* pd = pn + g.NN;
+  const typename R::Elem* fbase =
+      reinterpret_cast<const typename R::Elem*>(feats_v) + (size_t)f * g.HW * g.D + (act ? ch0 : 0);
+  const int U = P >= 8 ? (P >> 3) : 1;
+
+  for (int u = wave; u < U * U; u += kStatsWaves) {
+    const int y3 = (u / U) * 8, x3 = (u % U) * 8;
+    float S3[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) S3[v] = 0.f;
+    if (y3 < H && x3 < W) {
+      float S2[4][VEC];
+#pragma unroll
+      for (int q2 = 0; q2 < 4; ++q2) {
+        const int ty = y3 + (q2 >> 1) * 4, tx = x3 + (q2 & 1) * 4;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) S2[q2][v] = 0.f;
+        if (ty >= H || tx >= W) continue;  // wave-uniform
+        typename R::Raw raw[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int q1 = i >> 2, k = i & 3;
+          const int y = ty + (q1 >> 1) * 2 + (k >> 1), x = tx + (q1 & 1) * 2 + (k & 1);
+          raw[i] = R::zero();
+          if (y < H && x < W && act)
+            raw[i] = *reinterpret_cast<const typename R::Raw*>(fbase + (size_t)(y * W + x) * g.D);
+        }
+        float S1[4][VEC];
+#pragma unroll
+        for (int q1 = 0; q1 < 4; ++q1) {
+          float x[4][VEC];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) R::unpack(raw[q1 * 4 + k], x[k]);
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) S1[q1][v] = (x[0][v] + x[1][v]) + (x[2][v] + x[3][v]);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            float n0 = 0.f, d0 = 0.f;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+              n0 = fmaf(x[k][v], x[k][v], n0);
+              d0 = fmaf(x[k][v], S1[q1][v], d0);
+            }
+            tb[(q1 * 4 + k) * kRowStride + lane] = n0;
+            tb[(16 + q1 * 4 + k) * kRowStride + lane] = d0;
+          }
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) S2[q2][v] += S1[q1][v];
+        }
+#pragma unroll
+        for (int q1 = 0; q1 < 4; ++q1) {
+          float n1 = 0.f, d1 = 0.f;
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) {
+            n1 = fmaf(S1[q1][v], S1[q1][v], n1);
+            d1 = fmaf(S1[q1][v], S2[q2][v], d1);
+          }
+          tb[(32 + q1) * kRowStride + lane] = n1;
+          tb[(36 + q1) * kRowStride + lane] = d1;
+        }
+        wave_lds_fence();
+        if (lane < kTileRows) {
+          const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
+          float acc = 0.f;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            float4 q = row[j];
+            acc += (q.x + q.y) + (q.z + q.w);
+          }
+          // which node / table does row `lane` belong to
+          int r = lane, lvl, by, bx;
+          bool is_dot;
+          if (r < 32) {
+            is_dot = r >= 16;
+            const int q1 = (r & 15) >> 2, k = r & 3;
+            lvl = 0;
+            by = ty + (q1 >> 1) * 2 + (k >> 1);
+            bx = tx + (q1 & 1) * 2 + (k & 1);
+          } else {
+            is_dot = r >= 36;
+            const int q1 = (r - 32) & 3;
+            lvl = 1;
+            by = (ty >> 1) + (q1 >> 1);
+            bx = (tx >> 1) + (q1 & 1);
+          }
+          const int side = P >> lvl;
+          if (lvl <= L && by < side && bx < side && !(is_dot && lvl >= L))
+            (is_dot ? pd : pn)[node_index(g, lvl, by, bx)] = acc;
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) S3[v] += S2[q2][v];
+      }
+      // level-2 scalars of the four tiles and the level-3 norm of the unit
+#pragma unroll
+      for (int q2 = 0; q2 < 4; ++q2) {
+        float n2 = 0.f, d2 = 0.f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          n2 = fmaf(S2[q2][v], S2[q2][v], n2);
+          d2 = fmaf(S2[q2][v], S3[v], d2);
+        }
+        tb[q2 * kRowStride + lane] = n2;
+        tb[(4 + q2) * kRowStride + lane] = d2;
+      }
+      {
+        float n3 = 0.f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) n3 = fmaf(S3[v], S3[v], n3);
+        tb[8 * kRowStride + lane] = n3;
+      }
+      wave_lds_fence();
+      if (lane < 9) {
+        const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          float4 q = row[j];
+          acc += (q.x + q.y) + (q.z + q.w);
+        }
+        int lvl, by, bx;
+        bool is_dot = false;
+        if (lane < 8) {
+          const int q2 = lane & 3;
+          is_dot = lane >= 4;
+          lvl = 2;
+          by = (y3 >> 2) + (q2 >> 1);
+          bx = (x3 >> 2) + (q2 & 1);
+        } else {
+          lvl = 3;
+          by = y3 >> 3;
+          bx = x3 >> 3;
+        }
+        const int side = P >> lvl;
+        if (lvl <= L && by < side && bx < side && !(is_dot && lvl >= L))
+          (is_dot ? pd : pn)[node_index(g, lvl, by, bx)] = acc;
+      }
+      wave_lds_fence();
+    }
+    if (L > 3) {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) s3buf[u * g.cch + lane * VEC + v] = S3[v];
+    }
+  }
+
+  if (L > 3) {
+    // Levels 4..L from the per-channel level-3 sums: thread t owns channels t, t+256, ...
+    __shared__ float red[kStatsWaves][5];
+    __syncthreads();
+    float* child = s3buf;
+    float* cur = s3buf + U * U * g.cch;
+    for (int lvl = 4; lvl <= L; ++lvl) {
+      const int G = P >> lvl, Gc = G * 2;
+      for (int nd = 0; nd < G * G; ++nd) {
+        const int by = nd / G, bx = nd % G;
+        float tot[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int c = threadIdx.x; c < g.cch; c += 256) {
+          float a[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+            a[k] = child[((2 * by + (k >> 1)) * Gc + 2 * bx + (k & 1)) * g.cch + c];
+          const float S = (a[0] + a[1]) + (a[2] + a[3]);
+          cur[nd * g.cch + c] = S;
+          tot[0] = fmaf(S, S, tot[0]);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) tot[1 + k] = fmaf(a[k], S, tot[1 + k]);
+        }
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+          const float r = wave_sum(tot[j]);
+          if (lane == 0) red[wave][j] = r;
+        }
+        __syncthreads();
+        if (threadIdx.x < 5) {
+          const int j = threadIdx.x;
+          const float r = (red[0][j] + red[1][j]) + (red[2][j] + red[3][j]);
+          if (j == 0) {
+            pn[node_index(g, lvl, by, bx)] = r;
+          } else {
+            const int k = j - 1;
+            pd[node_index(g, lvl - 1, 2 * by + (k >> 1), 2 * bx + (k & 1))] = r;
+          }
+        }
+        __syncthreads();
+      }
+      child = cur;
+      cur = cur + G * G * g.cch;
+    }
+  }
+}
+
+static size_t stats_lds_bytes(const Geo& g) {
+  size_t fl = (size_t)kStatsWaves * kTileRows * kRowStride;
+  if (g.L > 3) {
+    int U = g.P >> 3;
+    size_t nodes = (size_t)U * U;
+    for (int lvl = 4; lvl <= g.L; ++lvl) nodes += (size_t)(g.P >> lvl) * (g.P >> lvl);
+    fl += nodes * g.cch;
+  }
+  return fl * sizeof(float);
+}
+
+void launch_pyramid_stats(const Geo& g, const void* feats, float* part, hipStream_t s) {
+  dim3 grid(g.nC, g.F), block(256);
+  size_t lds = stats_lds_bytes(g);
+  if (g.dtype == 1)
+    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, lds, s, g, feats, part);
+  else
+    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, lds, s, g, feats, part);
+}
+
+// ------------------------------------------------------------------------------------------------
+// k_spatial_finalize: one workgroup per frame. Sums the per-chunk partials in chunk order, turns
+// them into sigma(parent, child) (Sec. 3.2: cosine between a level's nodes and their children),
+// m_n = min over existing children, and the split score s_n = max of m along the path from the root.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __restrict__ part,
+                                                          float* __restrict__ nrm2, float* __restrict__ sim,
+                                                          float* __restrict__ m, float* __restrict__ sc) {
+  extern __shared__ float sm[];
+  float* s_n = sm;
+  float* s_sim = sm + g.NN;
+  float* s_m = sm + 2 * g.NN;
+  const int f = blockIdx.x;
+  const size_t fo = (size_t)f * g.NN;
+  for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
+    int lvl, by, bx;
+    node_decode(g, idx, lvl, by, bx);
+    float n = 0.f, d = 0.f;
+    if (node_exists(g, lvl, by, bx)) {
+      for (int c = 0; c < g.nC; ++c) {
+        const float* p = part + (size_t)(f * g.nC + c) * 2 * g.NN;
+        n += p[idx];
+        if (lvl < g.L) d += p[g.NN + idx];
+      }
+    }
+    s_n[idx] = n;
+    s_sim[idx] = d;  // dot for now
+    nrm2[fo + idx] = n;
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
+    int lvl, by, bx;
+    node_decode(g, idx, lvl, by, bx);
+    float v = 0.f;
+    if (lvl < g.L && node_exists(g, lvl, by, bx))
+      v = cosine_from(s_sim[idx], s_n[idx], s_n[node_index(g, lvl + 1, by >> 1, bx >> 1)]);
+    sim[fo + idx] = v;
+    s_m[idx] = v;  // reuse as sim storage until the next phase reads it
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
+    int lvl, by, bx;
+    node_decode(g, idx, lvl, by, bx);
+    float mv = 2.f;
+    if (lvl >= 1 && node_exists(g, lvl, by, bx)) {
+      bool nan = false;
+      for (int k = 0; k < 4; ++k) {
+        const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
+        if (!node_exists(g, lvl - 1, cy, cx)) continue;
+        const float v = s_m[node_index(g, lvl - 1, cy, cx)];
+        if (v != v) nan = true;
+        mv = fminf(mv, v);
+      }
+      if (nan) mv = __uint_as_float(0x7fc00000u);
+    }
+    s_sim[idx] = mv;  // m in LDS
+    m[fo + idx] = mv;
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
+    int lvl, by, bx;
+    node_decode(g, idx, lvl, by, bx);
+    float s = -2.f;
+    if (lvl >= 1 && node_exists(g, lvl, by, bx)) {
+      int l = lvl, y = by, x = bx;
+      while (true) {
+        const float v = s_sim[node_index(g, l, y, x)];
+        s = fmaxf(s, (v != v) ? -2.f : v);  // NaN always splits
+        if (l == g.L) break;
+        ++l; y >>= 1; x >>= 1;
+      }
+    }
+    sc[fo + idx] = s;
+  }
+}
+
+void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m, float* sc,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(256), 3 * g.NN * sizeof(float), s, g, part, nrm2, sim,
+                     m, sc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// k_spatial_decide: coarse-to-fine search (Sec. 3.2). One thread per cell walks down from its root:
+// the first node on the path whose smallest child similarity exceeds tau_S is kept.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_spatial_decide(Geo g, const float* __restrict__ m,
+                                                        const float* __restrict__ tau,
+                                                        int32_t* __restrict__ node_map,
+                                                        uint8_t* __restrict__ node_level) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= g.N) return;
+  const int f = i / g.HW, c = i - f * g.HW;
+  const int y = c / g.W, x = c - y * g.W;
+  const float t = tau[f / g.T];
+  const float* mf = m + (size_t)f * g.NN;
+  int lvl = g.L;
+  for (; lvl >= 1; --lvl)
+    if (mf[node_index(g, lvl, y >> lvl, x >> lvl)] > t) break;
+  const int y0 = (y >> lvl) << lvl, x0 = (x >> lvl) << lvl;
+  node_map[i] = f * g.HW + y0 * g.W + x0;
+  if (node_level) node_level[i] = (uint8_t)lvl;
+}
+
+void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
+                           uint8_t* node_level, hipStream_t s) {
+  hipLaunchKernelGGL(k_spatial_decide, dim3((g.N + 255) / 256), dim3(256), 0, s, g, m, tau, node_map,
+                     node_level);
+}
+
+// Recovers node levels from a node map (callers may pass node_level == NULL to the temporal stage).
+__global__ __launch_bounds__(256) void k_node_levels(Geo g, const int32_t* __restrict__ node_map,
+                                                     uint8_t* __restrict__ node_level) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= g.N) return;
+  const int f = i / g.HW, c = i - f * g.HW;
+  const int y = c / g.W, x = c - y * g.W;
+  const int r = node_map[i] - f * g.HW;
+  const int y0 = r / g.W, x0 = r - y0 * g.W;
+  // smallest level whose block at (y0, x0) contains (y, x) and is aligned; the partition's block is
+  // the largest aligned block rooted at (y0,x0) in which every valid cell maps to it -- found by growing.
+  int lvl = 0;
+  while (lvl < g.L) {
+    const int s2 = 2 << lvl;
+    if ((y0 & (s2 - 1)) || (x0 & (s2 - 1))) break;
+    // the candidate block [y0, y0+s2) x [x0, x0+s2): its bottom-right valid corner must map to r as well
+    const int yy = min(y0 + s2 - 1, g.H - 1), xx = min(x0 + s2 - 1, g.W - 1);
+    if (node_map[f * g.HW + yy * g.W + xx] - f * g.HW != r) break;
+    ++lvl;
+  }
+  (void)y; (void)x;
+  node_level[i] = (uint8_t)lvl;
+}
+
+void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_level, hipStream_t s) {
+  hipLaunchKernelGGL(k_node_levels, dim3((g.N + 255) / 256), dim3(256), 0, s, g, node_map, node_level);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Budget-driven thresholds. Token count as a function of the threshold is the step function
+// K(tau) = base + sum_j w_j [v_j <= tau]; one workgroup per video finds, by a 4-pass MSB-first radix
+// select over the order-preserving integer image of v, the smallest value whose cumulative weight
+// exceeds target - base, then the largest value below it, and takes the midpoint of the two.
+// ------------------------------------------------------------------------------------------------
+struct SpatialElems {
+  Geo g;
+  const float* sc;
+  __device__ int count() const { return g.T * g.NN; }
+  __device__ bool get(int b, int j, float& v, uint32_t& w) const {
+    const int t = j / g.NN, idx = j - t * g.NN;
+    if (idx < g.lvl_base[1]) return false;
+    int lvl, by, bx;
+    node_decode(g, idx, lvl, by, bx);
+    if (!node_exists(g, lvl, by, bx)) return false;
+    int kids = 0;
+    for (int k = 0; k < 4; ++k) kids += node_exists(g, lvl - 1, 2 * by + (k >> 1), 2 * bx + (k & 1));
+    if (kids < 2) return false;
+    w = kids - 1;
+    v = sc[(size_t)(b * g.T + t) * g.NN + idx];
+    return true;
+  }
+  __device__ int base(int) const {
+    int roots = 0;
+    for (int ry = 0; ry < g.R; ++ry)
+      for (int rx = 0; rx < g.R; ++rx) roots += node_exists(g, g.L, ry, rx);
+    return roots * g.T;
+  }
+};
+
+struct TemporalElems {
+  Geo g;
+  const int32_t* node_map;
+  const float* e;
+  __device__ int count() const { return g.T * g.HW; }
+  __device__ bool get(int b, int j, float& v, uint32_t& w) const {
+    if (j < g.HW) return false;  // frame 0 has no candidates
+    const int i = b * g.T * g.HW + j;
+    if (node_map[i] != i) return false;
+    w = 1;
+    v = e[i];
+    if (v != v) v = -2.f;  // NaN never passes
+    return true;
+  }
+  __device__ int base(int b) const {  // nodes of frame 0 (counted by the caller loop)
+    return -1;
+  }
+};
+
+template <class E>
+__global__ __launch_bounds__(1024) void k_budget_select(E el, const int* __restrict__ target,
+                                                        float* __restrict__ tau) {
+  __shared__ unsigned hist[256];
+  __shared__ unsigned s_prefix, s_acc, s_lo;
+  __shared__ int s_state;  // 0 searching, 1 = everything fits (tau = 1)
+  __shared__ int s_base;
+  const int b = blockIdx.x, tid = threadIdx.x, n = el.count();
+  if (tid == 0) { s_prefix = 0; s_acc = 0; s_lo = 0; s_state = 0; s_base = 0; }
+  __syncthreads();
+  int base = el.base(b);
+  if (base < 0) {  // temporal: count the kept nodes of frame 0
+    int c = 0;
+    for (int j = tid; j < el.g.HW; j += blockDim.x) {
+      const int i = b * el.g.T * el.g.HW + j;
+      c += (el.node_map_ptr()[i] == i);
+    }
+    atomicAdd(&s_base, c);
+    __syncthreads();
+    base = s_base;
+  }
+  const long long budget = (long long)target[b] - base;
+  if (budget < 0) {
+    if (tid == 0) tau[b] = -2.f;
+    return;
+  }
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    for (int j = tid; j < 256; j += blockDim.x) hist[j] = 0;
+    __syncthreads();
+    const unsigned prefix = s_prefix;
+    for (int j = tid; j < n; j += blockDim.x) {
+      float v; uint32_t w;
+      if (!el.get(b, j, v, w)) continue;
+      const uint32_t key = float_key(v);
+      if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255u], w);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long run = s_acc;
+      int d = 0;
+      for (; d < 256; ++d) {
+        if (run + hist[d] > (unsigned long long)budget) break;
+        run += hist[d];
+      }
+      if (d == 256) {
+        s_state = 1;  // only reachable in pass 0: the whole weight fits
+      } else {
+        s_prefix = (prefix << 8) | (unsigned)d;
+        s_acc = (unsigned)run;
+      }
+    }
+    __syncthreads();
+    if (s_state == 1) {
+      if (tid == 0) tau[b] = 1.f;
+      return;
+    }
+  }
+  const unsigned over = s_prefix;  // smallest value at which K exceeds the target
+  unsigned lo = 0;                 // key 0 is below every real value (keys of finite floats are > 0)
+  for (int j = tid; j < n; j += blockDim.x) {
+    float v; uint32_t w;
+    if (!el.get(b, j, v, w)) continue;
+    const uint32_t key = float_key(v);
+    if (key < over && key > lo) lo = key;
+  }
+  atomicMax(&s_lo, lo);
+  __syncthreads();
+  if (tid == 0) {
+    const float hi = key_float(over);
+    const float lof = s_lo ? key_float(s_lo) : -2.f;
+    float mid = 0.5f * (lof + hi);
+    if (!(mid < hi)) mid = lof;
+    tau[b] = mid;
+  }
+}
+
+// node_map accessor used by the temporal flavour only
+struct TemporalElemsImpl : TemporalElems {
+  __device__ const int32_t* node_map_ptr() const { return node_map; }
+};
+struct SpatialElemsImpl : SpatialElems {
+  __device__ const int32_t* node_map_ptr() const { return nullptr; }
+};
+
+void launch_select_spatial(const Geo& g, const float* sc, const int* target, float* tau, hipStream_t s) {
+  SpatialElemsImpl el;
+  el.g = g;
+  el.sc = sc;
+  hipLaunchKernelGGL(k_budget_select<SpatialElemsImpl>, dim3(g.B), dim3(1024), 0, s, el, target, tau);
+}
+
+void launch_select_temporal(const Geo& g, const int32_t* node_map, const float* e, const int* target,
+                            float* tau, hipStream_t s) {
+  TemporalElemsImpl el;
+  el.g = g;
+  el.node_map = node_map;
+  el.e = e;
+  hipLaunchKernelGGL(k_budget_select<TemporalElemsImpl>, dim3(g.B), dim3(1024), 0, s, el, target, tau);
+}
+
+}  // namespace sttm

@@ -1,0 +1,221 @@
+"""Helpers shared by the GPU parity tests, smoke() and bench.py's checks.
+
+run_gpu()      drives the HIP library through its C ABI (via the ctypes binding) on cuda:0.
+check_parity() compares every stage with the CPU oracle.
+
+Near-threshold protocol.  Cluster maps must be bit-identical to the oracle's, except that a decision
+whose fp64 similarity lies within BAND = 1e-5 of the threshold may fall either way (the GPU accumulates
+in fp32).  The oracle is authoritative outside the band; inside it, and only there, it is told which way
+the GPU decided (a hook it consults only when |sigma64 - tau| <= BAND), and the number of such decisions
+is reported.  All other oracle inputs are the seeded synthetic features and thresholds.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional
+
+import numpy as np
+
+from oracle import sttm_oracle as O
+
+BAND = O.BAND
+SIM_TOL = 1e-5          # |sigma_gpu(fp32) - sigma_oracle(fp64)|
+TOL_F32 = 1e-3          # merged features, fp32 in / fp32 out
+TOL_BF16 = 2e-2         # bf16 in, fp32 accumulate
+
+
+class GpuResult:
+    pass
+
+
+def _to_dev(feats: np.ndarray):
+    import torch
+    if feats.dtype == np.uint16:
+        return torch.from_numpy(feats.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(feats).cuda()
+
+
+def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_grid: int = 1,
+            out_dtype: Optional[int] = None, node_map_override=None, ctx=None, feats_dev=None) -> GpuResult:
+    """Whole path through the C ABI. Fixed thresholds, or `keep` (budget mode)."""
+    import torch
+    B, T, H, W, D = feats.shape
+    dt = lib.STTM_BF16 if feats.dtype == np.uint16 else lib.STTM_F32
+    if out_dtype is None:
+        out_dtype = dt
+    x = _to_dev(feats) if feats_dev is None else feats_dev
+    s = ctx or lib.Sttm(0)
+    s.ensure_workspace(B, T, H, W, D, dt, root_grid)
+    N = B * T * H * W
+    NN = lib.sttm_nodes_per_frame(H, W, root_grid)
+    dev = "cuda:0"
+    r = GpuResult()
+    node_map = torch.empty(N, dtype=torch.int32, device=dev)
+    node_level = torch.empty(N, dtype=torch.uint8, device=dev)
+    cluster = torch.empty(N, dtype=torch.int32, device=dev)
+    r.tau_s = r.tau_t = None
+    if tau_s is None:
+        s.sttm_spatial_stats(x, dt, B, T, H, W, D, root_grid)
+        r.tau_s = s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, keep)
+        s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, root_grid, None, node_map, node_level)
+    else:
+        s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, root_grid, tau_s, node_map, node_level)
+    tbl = torch.empty(B * T * NN, dtype=torch.float32, device=dev)
+    s.sttm_export(lib.STTM_TBL_CHILD_SIM, tbl)
+    r.child_sim = tbl.cpu().numpy().reshape(B * T, NN)
+    s.sttm_export(lib.STTM_TBL_MIN_SIM, tbl)
+    r.min_sim = tbl.cpu().numpy().reshape(B * T, NN)
+    r.node_map = node_map.cpu().numpy().reshape(B, T, H, W)
+    r.node_level = node_level.cpu().numpy().reshape(B, T, H, W)
+    if node_map_override is not None:
+        node_map.copy_(torch.from_numpy(node_map_override[0].reshape(-1)).cuda())
+        node_level.copy_(torch.from_numpy(node_map_override[1].reshape(-1)).cuda())
+    if tau_t is None:
+        s.sttm_temporal_stats(x, node_map, node_level)
+        r.tau_t = s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, keep)
+        s.sttm_temporal_merge(x, node_map, node_level, None, cluster)
+    else:
+        s.sttm_temporal_merge(x, node_map, node_level, tau_t, cluster)
+    t32 = torch.empty(N, dtype=torch.float32, device=dev)
+    s.sttm_export(lib.STTM_TBL_PAIR_SIM, t32)
+    r.pair_sim = t32.cpu().numpy()
+    s.sttm_export(lib.STTM_TBL_BEST_SIM, t32)
+    r.best_sim = t32.cpu().numpy()
+    ti = torch.empty(N, dtype=torch.int32, device=dev)
+    s.sttm_export(lib.STTM_TBL_PARENT, ti)
+    r.parent = ti.cpu().numpy().reshape(B, T, H, W)
+    r.cluster_ids = cluster.cpu().numpy().reshape(B, T, H, W)
+    odt = torch.bfloat16 if out_dtype == lib.STTM_BF16 else torch.float32
+    merged = torch.zeros(N, D, dtype=odt, device=dev)
+    counts = torch.zeros(N, dtype=torch.int32, device=dev)
+    out_ids = torch.zeros(N, dtype=torch.int32, device=dev)
+    offsets = torch.zeros(B + 1, dtype=torch.int64, device=dev)
+    K = s.sttm_reduce(x, cluster, out_dtype, N, merged, counts, out_ids, offsets)
+    r.K = K
+    r.merged = merged[:K].float().cpu().numpy()
+    r.counts = counts[:K].cpu().numpy()
+    r.out_ids = out_ids[:K].cpu().numpy()
+    r.offsets = offsets.cpu().numpy()
+    r.ctx = s
+    r.feats_dev = x
+    return r
+
+
+def check_spatial(lib, feats, r: GpuResult, tau_s, root_grid=1, stats=None):
+    """Similarity tables within SIM_TOL, node map identical under the near-threshold protocol."""
+    B, T, H, W, D = feats.shape
+    HW = H * W
+    stats = stats or O.spatial_stats(feats, root_grid, keep_means=False)
+    grid = stats[0]
+    worst = 0.0
+    for f, (_, cnt, sims, m) in enumerate(stats[1]):
+        for lvl in range(1, grid.L + 1):
+            g = grid.side(lvl)
+            for by in range(g):
+                for bx in range(g):
+                    if cnt[lvl][by, bx] == 0:
+                        continue
+                    for k in range(4):
+                        cy, cx = 2 * by + (k >> 1), 2 * bx + (k & 1)
+                        if cnt[lvl - 1][cy, cx] == 0:
+                            continue
+                        got = r.child_sim[f, lib.sttm_node_index(H, W, root_grid, lvl - 1, cy, cx)]
+                        worst = max(worst, abs(float(got) - sims[lvl][by, bx, k]))
+                    gm = r.min_sim[f, lib.sttm_node_index(H, W, root_grid, lvl, by, bx)]
+                    worst = max(worst, abs(float(gm) - m[lvl][by, bx]))
+    assert worst <= SIM_TOL, f"spatial similarity error {worst}"
+
+    def decide(b, t, lvl, by, bx, val):
+        y0, x0 = by << lvl, bx << lvl
+        return bool(r.node_level[b, t, y0, x0] == lvl and r.node_map[b, t, y0, x0] == (b * T + t) * HW + y0 * W + x0)
+
+    sp = O.spatial_quadtree(feats, tau_s, root_grid, stats=stats, decide=decide)
+    assert (sp.node_map == r.node_map).all(), "node_map differs from the oracle outside the threshold band"
+    # levels may differ only for nodes with a single existing child chain (same cells either way)
+    assert (sp.node_level == r.node_level).all()
+    return sp, worst
+
+
+def check_temporal(lib, feats, r: GpuResult, sp, tau_t, cands=None):
+    B, T, H, W, D = feats.shape
+    if cands is None:
+        cands, _ = O.temporal_candidates(feats, sp.node_map, sp.node_level)
+    HW = H * W
+    worst = 0.0
+    lvl_flat = sp.node_level.reshape(-1)
+    for n, lst in cands.items():
+        f = n // HW
+        for d, sig in lst:
+            # slot = top-left cell of the finer node, in frame f's table
+            q = n if lvl_flat[n] <= lvl_flat[d] else d + HW
+            worst = max(worst, abs(float(r.pair_sim[q]) - sig))
+        worst = max(worst, abs(float(r.best_sim[n]) - max(s for _, s in lst)))
+    assert worst <= SIM_TOL, f"temporal similarity error {worst}"
+    gpar = r.parent.reshape(-1)
+
+    def decide(n, d, sig):
+        p = int(gpar[n])
+        if d == p:
+            return True
+        if p < 0 or d < p:
+            return False
+        return None
+
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, tau_t, cands=cands, decide=decide)
+    nodes = np.unique(sp.node_map)
+    assert (tm.parent.reshape(-1)[nodes] == gpar[nodes]).all(), "parent differs outside the threshold band"
+    assert (tm.cluster_ids == r.cluster_ids).all(), "cluster_ids differ"
+    return tm, worst
+
+
+def check_reduce(feats, r: GpuResult, tm, out_is_bf16: bool):
+    rd = O.reduce_clusters(feats, tm.cluster_ids)
+    assert r.K == len(rd.counts)
+    assert (r.counts == rd.counts).all() and (r.out_ids == rd.out_ids).all()
+    assert (r.offsets == rd.offsets).all()
+    assert int(r.counts.sum()) == feats.shape[0] * feats.shape[1] * feats.shape[2] * feats.shape[3]
+    tol = TOL_BF16 if (feats.dtype == np.uint16 or out_is_bf16) else TOL_F32
+    err = float(np.abs(r.merged.astype(np.float64) - rd.merged).max()) if r.K else 0.0
+    assert err <= tol, f"merged feature error {err} > {tol}"
+    return rd, err
+
+
+def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None, root_grid=1,
+                 out_is_bf16=None):
+    """Full comparison; returns a dict with the error figures and near-threshold counts."""
+    B, T, H, W, D = feats.shape
+    if out_is_bf16 is None:
+        out_is_bf16 = feats.dtype == np.uint16
+    stats = O.spatial_stats(feats, root_grid, keep_means=False)
+    info = {}
+    ts = tau_s
+    if tau_s is None:
+        ts = r.tau_s.astype(np.float64)
+        N1 = T * H * W
+        for b, (vals, wts, base) in enumerate(O.spatial_budget_inputs(stats, B, T)):
+            keep_b = float(np.broadcast_to(np.asarray(keep, dtype=np.float64), (B,))[b])
+            target = int(math.floor(math.sqrt(keep_b) * N1))
+            tau, lo, hi, K = O.budget_threshold(vals, wts, base, target)
+            assert lo - BAND <= ts[b] <= hi + BAND or ts[b] == tau, \
+                f"tau_s {ts[b]} outside the oracle's interval [{lo}, {hi})"
+            assert len(np.unique(r.node_map[b])) <= target or base > target
+        info["tau_s"] = ts
+    sp, e1 = check_spatial(lib, feats, r, ts, root_grid, stats)
+    cands, _ = O.temporal_candidates(feats, sp.node_map, sp.node_level)
+    tt = tau_t
+    if tau_t is None:
+        tt = r.tau_t.astype(np.float64)
+        N1 = T * H * W
+        for b, (vals, wts, base) in enumerate(O.temporal_budget_inputs(cands, sp.node_map)):
+            keep_b = float(np.broadcast_to(np.asarray(keep, dtype=np.float64), (B,))[b])
+            target = int(math.floor(keep_b * N1))
+            tau, lo, hi, K = O.budget_threshold(vals, wts, base, target)
+            assert lo - BAND <= tt[b] <= hi + BAND or tt[b] == tau, \
+                f"tau_t {tt[b]} outside the oracle's interval [{lo}, {hi})"
+            assert len(np.unique(r.cluster_ids[b])) <= target or base > target
+        info["tau_t"] = tt
+    tm, e2 = check_temporal(lib, feats, r, sp, tt, cands)
+    rd, e3 = check_reduce(feats, r, tm, out_is_bf16)
+    info.update(spatial_sim_err=e1, temporal_sim_err=e2, merged_err=e3, near_spatial=sp.near,
+                near_temporal=tm.near, K=r.K, N=B * T * H * W, n_spatial=len(np.unique(sp.node_map)))
+    return info
