@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the merge path on one MI355X.
+
+A step = one pass of the whole hot path (pyramid statistics -> spatial threshold from the budget ->
+quadtree decision -> temporal similarities -> temporal threshold -> edges + roots -> gather/average)
+over one synthetic video batch already resident in HBM.  No host synchronisation happens inside a step.
+
+Prints ONE JSON line: whole-path throughput in input tokens/s, the roofline figure of the dominant
+feature kernel (HIP events recorded by the library on its stream during the timed steps), and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="index into the workload table (default: long video)")
+    ap.add_argument("--keep", type=float, default=None, help="token budget (default: the config's first)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-frames", type=int, default=192, help="frames of the workload the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path's sharding is described in DESIGN.md); "
+              "rerun with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2507_07990_amd import binding as lib
+    from paper_2507_07990_amd import workloads as wl
+
+    cfg = wl.CONFIGS[args.config]
+    budget_mode = cfg.tau_s is None
+    keep = args.keep if args.keep is not None else (cfg.budgets[0] if budget_mode else None)
+    t0 = time.time()
+    feats = wl.generate(cfg)
+    gen_s = time.time() - t0
+    B, T, H, W, D = feats.shape
+    N = B * T * H * W
+    dt = lib.STTM_BF16 if feats.dtype == np.uint16 else lib.STTM_F32
+    esz = 2 if dt == lib.STTM_BF16 else 4
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    if feats.dtype == np.uint16:
+        x = torch.from_numpy(feats.view(np.int16)).to(dev).view(torch.bfloat16)
+    else:
+        x = torch.from_numpy(feats).to(dev)
+
+    s = lib.Sttm(0)
+    s.ensure_workspace(B, T, H, W, D, dt, 1)
+    node_map = torch.empty(N, dtype=torch.int32, device=dev)
+    node_level = torch.empty(N, dtype=torch.uint8, device=dev)
+    cluster = torch.empty(N, dtype=torch.int32, device=dev)
+    merged = torch.empty(N, D, dtype=x.dtype, device=dev)
+    counts = torch.empty(N, dtype=torch.int32, device=dev)
+    out_ids = torch.empty(N, dtype=torch.int32, device=dev)
+    offsets = torch.zeros(B + 1, dtype=torch.int64, device=dev)
+
+    def step():
+        if budget_mode:
+            s.sttm_spatial_stats(x, dt, B, T, H, W, D, 1)
+            s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, keep, want_tau=False)
+            s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, 1, None, node_map, node_level)
+            s.sttm_temporal_stats(x, node_map, node_level)
+            s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, keep, want_tau=False)
+            s.sttm_temporal_merge(x, node_map, node_level, None, cluster)
+        else:
+            s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, 1, [cfg.tau_s], node_map, node_level)
+            s.sttm_temporal_merge(x, node_map, node_level, [cfg.tau_t], cluster)
+        s.sttm_reduce(x, cluster, dt, N, merged, counts, out_ids, offsets, want_n=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    s.sttm_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = {k: s.sttm_profile_read(k) for k in (lib.STTM_KERNEL_PYRAMID_STATS, lib.STTM_KERNEL_TEMPORAL_DOTS,
+                                               lib.STTM_KERNEL_REDUCE_GATHER)}
+    s.sttm_profile_enable(False)
+    ms_per_step = elapsed / args.steps * 1e3
+    K = int(offsets[B].item())
+    assert int(counts[:K].sum().item()) == N, "member counts do not add up to the number of input tokens"
+    rho = K / N
+
+    # Algorithmic bytes per launch of each feature kernel: every input element it must see read once,
+    # every output element written once (design notes: data layout / kernels).
+    alg = {
+        lib.STTM_KERNEL_PYRAMID_STATS: ("k_pyramid_stats", N * D * esz),
+        lib.STTM_KERNEL_TEMPORAL_DOTS: ("k_temporal_dots", N * D * esz),
+        lib.STTM_KERNEL_REDUCE_GATHER: ("k_reduce", N * D * esz + K * D * esz),
+    }
+    kernels = {}
+    for k, (ms, n) in prof.items():
+        name, nbytes = alg[k]
+        avg_ms = ms / max(n, 1)
+        kernels[name] = {"avg_ms": avg_ms, "launches": n, "alg_bytes": nbytes,
+                         "GBps": nbytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else None}
+    dom = max(kernels, key=lambda kk: kernels[kk]["avg_ms"])
+    achieved = kernels[dom]["GBps"]
+    path_bytes = N * D * esz + K * D * esz + 9 * N + 8 * K
+    out = {
+        "metric": "input visual tokens merged/sec (Mtok/s) at D=3584 bf16; achieved HBM GB/s vs peak",
+        "value": N / (elapsed / args.steps) / 1e6,
+        "unit": "Mtok/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if dt == lib.STTM_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {cfg.name}: B={B} T={T} grid={H}x{W} D={D} "
+                               f"{cfg.dtype}, " + (f"budget keep={keep}" if budget_mode else
+                                                   f"tau_s={cfg.tau_s} tau_t={cfg.tau_t}"),
+                   "tokens": N, "kept_tokens": K, "kept_fraction": rho, "generate_s": gen_s},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": None,
+                     "alg_bytes_per_launch": kernels[dom]["alg_bytes"], "kernels": kernels},
+        "path": {"alg_bytes_per_step": path_bytes,
+                 "whole_path_GBps": path_bytes / (elapsed / args.steps) / 1e9,
+                 "whole_path_frac_of_peak": path_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS},
+        "paper_context": "end-to-end prefill speed-up reported by the paper on 1xA100 80G (LLaVA-Video-7B): "
+                         "about 2x at a 50% budget, about 3x at 30%; the merge path alone is not timed there",
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import sttm_oracle as O
+        try:
+            from threadpoolctl import threadpool_limits
+            limiter = threadpool_limits(limits=1)
+        except Exception:  # pragma: no cover
+            limiter = None
+        nf = min(T, args.cpu_frames)
+        sample = feats[:1, :nf]
+        t0 = time.perf_counter()
+        if budget_mode:
+            O.sttm(sample, keep=keep)
+        else:
+            O.sttm(sample, tau_s=cfg.tau_s, tau_t=cfg.tau_t)
+        cpu_s = time.perf_counter() - t0
+        if limiter is not None:
+            limiter.restore_original_limits()
+        out["cpu_baseline"] = {"value": nf * H * W / cpu_s / 1e6, "unit": "Mtok/s", "cores": 1, "kind": "oracle",
+                               "sample": f"video 0, first {nf} of {T} frames of the same workload "
+                                         f"({nf * H * W} tokens, {cpu_s:.1f} s, fp64 numpy, 1 thread)"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -150,6 +150,20 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
 /* Copies an internal table (device to device, asynchronous) into dst_dev; bytes must equal the table's size. */
 int sttm_export(sttm_ctx* ctx, int table, void* dst_dev, size_t bytes);
 
+/* The three kernels that read the features (one per stage); everything else touches O(1) scalars per token. */
+typedef enum {
+  STTM_KERNEL_PYRAMID_STATS = 0, /* stage 1: block sums, norms, parent-child dot products */
+  STTM_KERNEL_TEMPORAL_DOTS = 1, /* stage 2: dot products of overlapping nodes of consecutive frames */
+  STTM_KERNEL_REDUCE_GATHER = 2, /* stage 3: gather and average the member rows */
+  STTM_KERNEL_COUNT = 3
+} sttm_kernel;
+
+/* Benchmark aid: when on, every launch of the three feature kernels is bracketed by HIP events on the context's
+ * stream (turning it on or off resets the record). sttm_profile_read synchronises the stream and returns the summed
+ * device time in milliseconds and the number of launches recorded for one kernel. */
+int sttm_profile_enable(sttm_ctx* ctx, int on);
+int sttm_profile_read(sttm_ctx* ctx, int kernel, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

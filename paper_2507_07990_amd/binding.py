@@ -28,7 +28,9 @@ EXPORTS = [
     "sttm_create", "sttm_destroy", "sttm_last_error", "sttm_nodes_per_frame", "sttm_node_index",
     "sttm_workspace_bytes", "sttm_set_workspace", "sttm_spatial_stats", "sttm_spatial_quadtree",
     "sttm_temporal_stats", "sttm_temporal_merge", "sttm_budget_threshold", "sttm_reduce", "sttm_export",
+    "sttm_profile_enable", "sttm_profile_read",
 ]
+STTM_KERNEL_PYRAMID_STATS, STTM_KERNEL_TEMPORAL_DOTS, STTM_KERNEL_REDUCE_GATHER = 0, 1, 2
 
 
 def _load() -> C.CDLL:
@@ -54,6 +56,8 @@ def _load() -> C.CDLL:
     lib.sttm_budget_threshold.argtypes = [vp, i, C.POINTER(C.c_double), C.POINTER(C.c_float)]
     lib.sttm_reduce.argtypes = [vp, vp, vp, i, i64, vp, vp, vp, vp, C.POINTER(i64)]
     lib.sttm_export.argtypes = [vp, i, vp, sz]
+    lib.sttm_profile_enable.argtypes = [vp, i]
+    lib.sttm_profile_read.argtypes = [vp, i, C.POINTER(C.c_double), C.POINTER(i64)]
     return lib
 
 
@@ -167,3 +171,11 @@ class Sttm:
 
     def sttm_export(self, table, dst):
         self._check(_lib.sttm_export(self._h, table, _ptr(dst), dst.numel() * dst.element_size()))
+
+    def sttm_profile_enable(self, on: bool):
+        self._check(_lib.sttm_profile_enable(self._h, 1 if on else 0))
+
+    def sttm_profile_read(self, kernel: int):
+        ms, n = C.c_double(0.0), C.c_int64(0)
+        self._check(_lib.sttm_profile_read(self._h, kernel, C.byref(ms), C.byref(n)))
+        return float(ms.value), int(n.value)

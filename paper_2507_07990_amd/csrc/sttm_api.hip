@@ -99,6 +99,11 @@ struct sttm_ctx {
   std::vector<float> h_tau;                    // host staging that outlives the asynchronous uploads
   std::vector<int> h_target;
   std::string err;
+  // optional per-kernel timing of the three feature passes (HIP events on the context's stream)
+  bool profiling = false;
+  struct EvPair { hipEvent_t a, b; };
+  std::vector<EvPair> ev[STTM_KERNEL_COUNT];
+  size_t ev_used[STTM_KERNEL_COUNT] = {0, 0, 0};
 };
 
 namespace {
@@ -153,10 +158,33 @@ int upload_tau(sttm_ctx* c, const float* host, float* dev) {
   return STTM_OK;
 }
 
+// Brackets one feature kernel with two events when profiling is on.
+struct Timed {
+  sttm_ctx* c;
+  int kid;
+  sttm_ctx::EvPair* p = nullptr;
+  Timed(sttm_ctx* c_, int kid_) : c(c_), kid(kid_) {
+    if (!c->profiling) return;
+    if (c->ev_used[kid] == c->ev[kid].size()) {
+      sttm_ctx::EvPair n;
+      if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
+      c->ev[kid].push_back(n);
+    }
+    p = &c->ev[kid][c->ev_used[kid]++];
+    (void)hipEventRecord(p->a, c->stream);
+  }
+  ~Timed() {
+    if (p) (void)hipEventRecord(p->b, c->stream);
+  }
+};
+
 int after_launch(sttm_ctx* c) { return hip_check(c, hipGetLastError(), "kernel launch"); }
 
 int run_spatial_stats(sttm_ctx* c, const void* feats) {
-  launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), c->stream);
+  {
+    Timed t(c, STTM_KERNEL_PYRAMID_STATS);
+    launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), c->stream);
+  }
   launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nrm2), at<float>(c, c->lay.sim),
                           at<float>(c, c->lay.m), at<float>(c, c->lay.sc), c->stream);
   int rc = after_launch(c);
@@ -169,7 +197,10 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
 }
 
 int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, const uint8_t* node_level) {
-  launch_temporal_dots(c->g, feats, node_map, node_level, at<float>(c, c->lay.pd_part), c->stream);
+  {
+    Timed t(c, STTM_KERNEL_TEMPORAL_DOTS);
+    launch_temporal_dots(c->g, feats, node_map, node_level, at<float>(c, c->lay.pd_part), c->stream);
+  }
   launch_temporal_resolve(c->g, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
                           at<float>(c, c->lay.sig), at<float>(c, c->lay.e), c->stream);
   int rc = after_launch(c);
@@ -204,6 +235,9 @@ int sttm_create(sttm_ctx** out, int device, void* hip_stream) {
 }
 
 int sttm_destroy(sttm_ctx* ctx) {
+  if (ctx)
+    for (auto& v : ctx->ev)
+      for (auto& p : v) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   delete ctx;
   return STTM_OK;
 }
@@ -399,8 +433,14 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
   rb.hist = at<int32_t>(ctx, ctx->lay.hist);
   rb.seg = at<int32_t>(ctx, ctx->lay.seg);
   rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
-  launch_reduce(ctx->g, feats_dev, cluster_ids_dev, out_dtype, capacity, merged_dev, counts_dev, out_ids_dev,
-                offsets_dev, rb, ctx->stream);
+  const int32_t* skey = nullptr;
+  const int32_t* order = nullptr;
+  launch_reduce_prepare(ctx->g, cluster_ids_dev, capacity, counts_dev, out_ids_dev, offsets_dev, rb, &skey, &order,
+                        ctx->stream);
+  {
+    Timed t(ctx, STTM_KERNEL_REDUCE_GATHER);
+    launch_reduce_gather(ctx->g, feats_dev, out_dtype, capacity, merged_dev, rb, skey, order, ctx->stream);
+  }
   rc = after_launch(ctx);
   if (rc) return rc;
   if (n_out_host) {
@@ -437,6 +477,29 @@ int sttm_export(sttm_ctx* ctx, int table, void* dst_dev, size_t bytes) {
   if (bytes != want) return fail(ctx, STTM_ERR_ARG, "byte count does not match the table size");
   STTM_HIP(ctx, hipSetDevice(ctx->device));
   STTM_HIP(ctx, hipMemcpyAsync(dst_dev, ctx->ws + off, want, hipMemcpyDeviceToDevice, ctx->stream));
+  return STTM_OK;
+}
+
+int sttm_profile_enable(sttm_ctx* ctx, int on) {
+  if (!ctx) return STTM_ERR_NULL;
+  ctx->profiling = on != 0;
+  for (auto& u : ctx->ev_used) u = 0;
+  return STTM_OK;
+}
+
+int sttm_profile_read(sttm_ctx* ctx, int kernel, double* total_ms, int64_t* launches) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!total_ms || !launches) return fail(ctx, STTM_ERR_NULL, "total_ms and launches are required");
+  if (kernel < 0 || kernel >= STTM_KERNEL_COUNT) return fail(ctx, STTM_ERR_ARG, "unknown kernel id");
+  STTM_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  double tot = 0.0;
+  for (size_t i = 0; i < ctx->ev_used[kernel]; ++i) {
+    float ms = 0.f;
+    STTM_HIP(ctx, hipEventElapsedTime(&ms, ctx->ev[kernel][i].a, ctx->ev[kernel][i].b));
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = (int64_t)ctx->ev_used[kernel];
   return STTM_OK;
 }
 

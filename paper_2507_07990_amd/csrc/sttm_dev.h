@@ -137,9 +137,11 @@ struct ReduceBuffers {
   int32_t* seg;       // [N+1] first sorted position of every output row
   int32_t* kdev;      // [1] number of clusters
 };
-void launch_reduce(const Geo& g, const void* feats, const int32_t* cluster_ids, int out_dtype, int64_t capacity,
-                   void* merged, int32_t* counts, int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
-                   hipStream_t s);
+void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t capacity, int32_t* counts,
+                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb, const int32_t** skey_out,
+                           const int32_t** order_out, hipStream_t s);
+void launch_reduce_gather(const Geo& g, const void* feats, int out_dtype, int64_t capacity, void* merged,
+                          const ReduceBuffers& rb, const int32_t* skey, const int32_t* order, hipStream_t s);
 size_t reduce_hist_entries(int N);
 size_t scan_blocks(int n);
 

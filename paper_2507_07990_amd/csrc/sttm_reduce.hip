@@ -274,9 +274,10 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, const void* __restrict__
   }
 }
 
-void launch_reduce(const Geo& g, const void* feats, const int32_t* cluster_ids, int out_dtype, int64_t capacity,
-                   void* merged, int32_t* counts, int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
-                   hipStream_t s) {
+// Integer plumbing of the reduce stage; returns the sorted member lists through `skey` / `order`.
+void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t capacity, int32_t* counts,
+                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb, const int32_t** skey_out,
+                           const int32_t** order_out, hipStream_t s) {
   const int N = g.N;
   const dim3 b256(256), gN((N + 255) / 256);
   // ranks of the roots, K, per-video offsets, out_ids
@@ -301,12 +302,16 @@ void launch_reduce(const Geo& g, const void* feats, const int32_t* cluster_ids, 
     vin = vout;
     if (kout == rb.key_a) { kout = rb.key_b; vout = rb.val_b; } else { kout = rb.key_a; vout = rb.val_a; }
   }
-  const int32_t* skey = kin;
-  const int32_t* order = vin;
-  hipLaunchKernelGGL(k_segments, gN, b256, 0, s, N, skey, rb.rank, rb.kdev, rb.seg);
+  hipLaunchKernelGGL(k_segments, gN, b256, 0, s, N, kin, rb.rank, rb.kdev, rb.seg);
   if (counts) hipLaunchKernelGGL(k_counts, gN, b256, 0, s, rb.kdev, rb.seg, capacity, counts);
-  // the feature pass
-  const int nitems = (N + kItem - 1) / kItem;
+  *skey_out = kin;
+  *order_out = vin;
+}
+
+// The feature pass of the reduce stage.
+void launch_reduce_gather(const Geo& g, const void* feats, int out_dtype, int64_t capacity, void* merged,
+                          const ReduceBuffers& rb, const int32_t* skey, const int32_t* order, hipStream_t s) {
+  const int nitems = (g.N + kItem - 1) / kItem;
   const int nw = g.nC < 16 ? g.nC : 16;
   dim3 grid(nitems), block(64 * nw);
 #define STTM_REDUCE(DT, ODT) \

@@ -183,3 +183,54 @@ def test_error_paths(lib):
     assert e.value.code == lib.STTM_ERR_CAPACITY and int(off[1].item()) == 128
     torch.cuda.synchronize()
     np.testing.assert_array_equal(merged.cpu().numpy(), x.view(128, 16)[:4].cpu().numpy())
+
+
+# ---- the five configurations at full size, in the launch configuration bench.py times ------------------
+def test_config1_short_clip_budget(lib):
+    cfg = wl.CONFIGS[1]
+    _run_and_check(lib, cfg, keep=cfg.budgets[0])
+
+
+def test_config2_encoder_width_budget(lib):
+    cfg = wl.CONFIGS[2]
+    _run_and_check(lib, cfg, keep=cfg.budgets[0])
+
+
+@pytest.mark.parametrize("keep", [0.5, 0.3])
+def test_config3_long_video_budget(lib, keep):
+    cfg = wl.CONFIGS[3]
+    _run_and_check(lib, cfg, keep=keep)
+
+
+def test_config4_batched_fixed_thresholds_sampled_videos(lib):
+    """All 32 videos run on the GPU; the oracle checks four of them one by one (videos are independent,
+    so a video's slice of every output equals the single-video result shifted by its token offset)."""
+    cfg = wl.CONFIGS[4]
+    feats = wl.generate(cfg)
+    B, T, H, W, D = feats.shape
+    print(f"case {cfg.name} shape={feats.shape}", flush=True)
+    r = P.run_gpu(lib, feats, tau_s=cfg.tau_s, tau_t=cfg.tau_t)
+    assert int(r.counts.sum()) == cfg.n_tokens and r.offsets[-1] == r.K
+    per = T * H * W
+    for b in (0, 11, 22, 31):
+        sub = P.GpuResult()
+        lo, hi = int(r.offsets[b]), int(r.offsets[b + 1])
+        NN = r.child_sim.shape[1]
+        sub.child_sim = r.child_sim[b * T:(b + 1) * T]
+        sub.min_sim = r.min_sim[b * T:(b + 1) * T]
+        sub.node_map = r.node_map[b:b + 1] - b * per
+        sub.node_level = r.node_level[b:b + 1]
+        sub.pair_sim = r.pair_sim[b * per:(b + 1) * per]
+        sub.best_sim = r.best_sim[b * per:(b + 1) * per]
+        par = r.parent[b:b + 1].copy()
+        par[par >= 0] -= b * per
+        sub.parent = par
+        sub.cluster_ids = r.cluster_ids[b:b + 1] - b * per
+        sub.K = hi - lo
+        sub.merged = r.merged[lo:hi]
+        sub.counts = r.counts[lo:hi]
+        sub.out_ids = r.out_ids[lo:hi] - b * per
+        sub.offsets = np.array([0, hi - lo])
+        info = P.check_parity(lib, feats[b:b + 1], sub, tau_s=cfg.tau_s, tau_t=cfg.tau_t)
+        print(f"   video {b}:", {k: (float(v) if isinstance(v, (float, np.floating)) else v)
+                                 for k, v in info.items()}, flush=True)
