@@ -17,8 +17,8 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t part, nrm2, sim, m, sc, tau_s, tau_t, target, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
-  size_t rank, blocksum, key_a, val_a, key_b, val_b, hist, seg, kdev;
+  size_t part, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
+  size_t rank, blocksum, key_a, val_a, key_b, val_b, hist, seg, kdev, bigpart;
   size_t total;
 };
 
@@ -57,7 +57,9 @@ Layout make_layout(const Geo& g) {
   l.nrm2 = take(F * NN * sizeof(float));
   l.sim = take(F * NN * sizeof(float));
   l.m = take(F * NN * sizeof(float));
-  l.sc = take(F * NN * sizeof(float));
+  l.sel_key_s = take(F * (NN - g.lvl_base[1]) * sizeof(uint32_t) + 4);
+  l.sel_w_s = take(F * (NN - g.lvl_base[1]) + 4);
+  l.sel_key_t = take(N * sizeof(uint32_t));
   l.tau_s = take(g.B * sizeof(float));
   l.tau_t = take(g.B * sizeof(float));
   l.target = take(g.B * sizeof(int));
@@ -79,6 +81,7 @@ Layout make_layout(const Geo& g) {
   l.hist = take(hist * sizeof(int32_t));
   l.seg = take((N + 1) * sizeof(int32_t));
   l.kdev = take(sizeof(int32_t));
+  l.bigpart = take(reduce_bigpart_floats(g) * sizeof(float));
   l.total = off;
   return l;
 }
@@ -186,7 +189,8 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
     launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), c->stream);
   }
   launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nrm2), at<float>(c, c->lay.sim),
-                          at<float>(c, c->lay.m), at<float>(c, c->lay.sc), c->stream);
+                          at<float>(c, c->lay.m), at<uint32_t>(c, c->lay.sel_key_s), at<uint8_t>(c, c->lay.sel_w_s),
+                          c->stream);
   int rc = after_launch(c);
   if (rc == STTM_OK) {
     c->have_spatial = true;
@@ -202,7 +206,8 @@ int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, 
     launch_temporal_dots(c->g, feats, node_map, node_level, at<float>(c, c->lay.pd_part), c->stream);
   }
   launch_temporal_resolve(c->g, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
-                          at<float>(c, c->lay.sig), at<float>(c, c->lay.e), c->stream);
+                          at<float>(c, c->lay.sig), at<float>(c, c->lay.e), at<uint32_t>(c, c->lay.sel_key_t),
+                          c->stream);
   int rc = after_launch(c);
   if (rc == STTM_OK) {
     c->have_temporal = true;
@@ -396,10 +401,11 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
                                hipMemcpyHostToDevice, ctx->stream));
   float* tau_dev = at<float>(ctx, stage == STTM_STAGE_SPATIAL ? ctx->lay.tau_s : ctx->lay.tau_t);
   if (stage == STTM_STAGE_SPATIAL)
-    launch_select_spatial(g, at<float>(ctx, ctx->lay.sc), at<int>(ctx, ctx->lay.target), tau_dev, ctx->stream);
+    launch_select_spatial(g, at<uint32_t>(ctx, ctx->lay.sel_key_s), at<uint8_t>(ctx, ctx->lay.sel_w_s),
+                          at<int>(ctx, ctx->lay.target), tau_dev, ctx->stream);
   else
-    launch_select_temporal(g, ctx->node_map_temporal, at<float>(ctx, ctx->lay.e), at<int>(ctx, ctx->lay.target),
-                           tau_dev, ctx->stream);
+    launch_select_temporal(g, ctx->node_map_temporal, at<uint32_t>(ctx, ctx->lay.sel_key_t),
+                           at<int>(ctx, ctx->lay.target), tau_dev, ctx->stream);
   rc = after_launch(ctx);
   if (rc) return rc;
   if (stage == STTM_STAGE_SPATIAL) ctx->have_tau_s = true; else ctx->have_tau_t = true;
@@ -433,13 +439,15 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
   rb.hist = at<int32_t>(ctx, ctx->lay.hist);
   rb.seg = at<int32_t>(ctx, ctx->lay.seg);
   rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
-  const int32_t* skey = nullptr;
+  rb.bigpart = at<float>(ctx, ctx->lay.bigpart);
+  const int32_t* orow = nullptr;
+  rb.orow_out = &orow;
   const int32_t* order = nullptr;
-  launch_reduce_prepare(ctx->g, cluster_ids_dev, capacity, counts_dev, out_ids_dev, offsets_dev, rb, &skey, &order,
+  launch_reduce_prepare(ctx->g, cluster_ids_dev, capacity, counts_dev, out_ids_dev, offsets_dev, rb, &order,
                         ctx->stream);
   {
     Timed t(ctx, STTM_KERNEL_REDUCE_GATHER);
-    launch_reduce_gather(ctx->g, feats_dev, out_dtype, capacity, merged_dev, rb, skey, order, ctx->stream);
+    launch_reduce_gather(ctx->g, feats_dev, out_dtype, capacity, merged_dev, rb, order, ctx->stream);
   }
   rc = after_launch(ctx);
   if (rc) return rc;

@@ -109,17 +109,19 @@ __device__ inline void wave_lds_fence() {
 struct Workspace;  // see sttm_api.hip
 
 void launch_pyramid_stats(const Geo& g, const void* feats, float* part, hipStream_t s);
-void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m, float* sc,
-                             hipStream_t s);
+void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
+                             uint32_t* sel_key, uint8_t* sel_w, hipStream_t s);
 void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
                            uint8_t* node_level, hipStream_t s);
-void launch_select_spatial(const Geo& g, const float* sc, const int* target, float* tau, hipStream_t s);
-void launch_select_temporal(const Geo& g, const int32_t* node_map, const float* e, const int* target,
+void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
+                           float* tau, hipStream_t s);
+void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
                             float* tau, hipStream_t s);
 void launch_temporal_dots(const Geo& g, const void* feats, const int32_t* node_map, const uint8_t* node_level,
                           float* pd_part, hipStream_t s);
 void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
-                             const float* pd_part, const float* nrm2, float* sig, float* e, hipStream_t s);
+                             const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
+                             hipStream_t s);
 void launch_temporal_parent(const Geo& g, const int32_t* node_map, const uint8_t* node_level, const float* sig,
                             const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s);
 void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* node_map, int32_t* cluster_ids,
@@ -136,12 +138,15 @@ struct ReduceBuffers {
   int32_t* hist;      // radix histogram table
   int32_t* seg;       // [N+1] first sorted position of every output row
   int32_t* kdev;      // [1] number of clusters
+  float* bigpart;     // window partial sums of clusters with more than 64 members
+  const int32_t** orow_out;  // host slot: where launch_reduce_prepare left the row-of-position array
 };
 void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t capacity, int32_t* counts,
-                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb, const int32_t** skey_out,
+                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
                            const int32_t** order_out, hipStream_t s);
 void launch_reduce_gather(const Geo& g, const void* feats, int out_dtype, int64_t capacity, void* merged,
-                          const ReduceBuffers& rb, const int32_t* skey, const int32_t* order, hipStream_t s);
+                          const ReduceBuffers& rb, const int32_t* order, hipStream_t s);
+size_t reduce_bigpart_floats(const Geo& g);
 size_t reduce_hist_entries(int N);
 size_t scan_blocks(int n);
 

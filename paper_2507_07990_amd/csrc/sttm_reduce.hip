@@ -173,14 +173,17 @@ __global__ __launch_bounds__(256) void k_root_outputs(Geo g, const int32_t* __re
   if (i == 0) offsets[g.B] = *kdev;
 }
 
-// seg[k] = first sorted position of output row k, seg[K] = N; counts from consecutive starts.
+// seg[k] = first sorted position of output row k, seg[K] = N; orow[p] = output row of sorted position p.
 __global__ __launch_bounds__(256) void k_segments(int n, const int32_t* __restrict__ skey,
                                                   const int32_t* __restrict__ rank,
-                                                  const int32_t* __restrict__ kdev, int32_t* __restrict__ seg) {
+                                                  const int32_t* __restrict__ kdev, int32_t* __restrict__ seg,
+                                                  int32_t* __restrict__ orow) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= n) return;
   const int key = skey[p];
-  if (p == 0 || skey[p - 1] != key) seg[rank[key]] = p;
+  const int k = rank[key];
+  orow[p] = k;
+  if (p == 0 || skey[p - 1] != key) seg[k] = p;
   if (p == n - 1) seg[*kdev] = n;
 }
 
@@ -191,17 +194,50 @@ __global__ __launch_bounds__(256) void k_counts(const int32_t* __restrict__ kdev
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_reduce: the gather/average pass. Work item j = the clusters whose member list starts at a sorted
-// position in [j*kItem, (j+1)*kItem). One wavefront per (item, chunk of the row); a lane owns VEC
-// channels, sums the member rows in list order (ascending flat index) in fp32 and stores the mean.
+// The gather/average pass. The sorted member list is cut into items of kItem consecutive positions;
+// an item owns the clusters whose list starts inside it. One wavefront per (item, chunk of the row):
+// a lane owns VEC channels. All index look-ups of the item are done lane-parallel first, then all row
+// loads are issued, then the rows are summed in list order (ascending flat index, fp32) with the
+// cluster boundaries handled as wave-uniform control flow.
+// Clusters with more than kBig members are left to the two kernels below, which cut them at fixed
+// kBig-aligned list positions so that the summation order does not depend on scheduling.
 // ------------------------------------------------------------------------------------------------
 constexpr int kItem = 16;
+constexpr int kBig = 64;
+
+template <int DT> __device__ inline void acc_row(const typename Row<DT>::Raw& r, float (&acc)[Row<DT>::VEC]) {
+  float t[Row<DT>::VEC];
+  Row<DT>::unpack(r, t);
+#pragma unroll
+  for (int v = 0; v < Row<DT>::VEC; ++v) acc[v] += t[v];
+}
+
+template <int DT, int ODT>
+__device__ inline void store_mean(void* merged_v, size_t elem_off, const float (&acc)[Row<DT>::VEC], float inv) {
+  constexpr int VEC = Row<DT>::VEC;
+  if (ODT == 0) {
+    float* o = reinterpret_cast<float*>(merged_v) + elem_off;
+#pragma unroll
+    for (int v = 0; v < VEC; v += 4)
+      *reinterpret_cast<float4*>(o + v) =
+          make_float4(acc[v] * inv, acc[v + 1] * inv, acc[v + 2] * inv, acc[v + 3] * inv);
+  } else {
+    uint16_t* o = reinterpret_cast<uint16_t*>(merged_v) + elem_off;
+    uint32_t w[VEC / 2];
+#pragma unroll
+    for (int v = 0; v < VEC; v += 2)
+      w[v / 2] = f32_to_bf16_rne(acc[v] * inv) | (f32_to_bf16_rne(acc[v + 1] * inv) << 16);
+    if (VEC == 8)
+      *reinterpret_cast<uint4*>(o) = make_uint4(w[0], w[1], w[2 % (VEC / 2)], w[3 % (VEC / 2)]);
+    else
+      *reinterpret_cast<uint2*>(o) = make_uint2(w[0], w[1]);
+  }
+}
 
 template <int DT, int ODT>
 __global__ __launch_bounds__(1024) void k_reduce(Geo g, const void* __restrict__ feats_v,
-                                                 const int32_t* __restrict__ skey,
                                                  const int32_t* __restrict__ order,
-                                                 const int32_t* __restrict__ rank,
+                                                 const int32_t* __restrict__ orow,
                                                  const int32_t* __restrict__ seg, int64_t capacity,
                                                  void* __restrict__ merged_v) {
   typedef Row<DT> R;
@@ -209,74 +245,154 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, const void* __restrict__
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
   const int p0 = blockIdx.x * kItem, p1 = min(p0 + kItem, g.N);
   const typename R::Elem* fb = reinterpret_cast<const typename R::Elem*>(feats_v);
+  // lane j < kItem describes sorted position p0 + j
+  int cell_v = 0, row_v = -1, beg_v = 0, end_v = 0;
+  if (lane < kItem && p0 + lane < p1) {
+    cell_v = order[p0 + lane];
+    row_v = orow[p0 + lane];
+    beg_v = seg[row_v];
+    end_v = seg[row_v + 1];
+  }
   for (int chunk = wave; chunk < g.nC; chunk += nw) {
     const int ch0 = chunk * g.cch + lane * VEC;
     const bool act = ch0 < g.D;
-    int p = p0;
-    // skip the tail of a cluster that started in an earlier item
-    if (p > 0) {
-      const int prev = skey[p - 1];
-      while (p < p1 && skey[p] == prev) ++p;
+    // issue every row load of the item that this item owns
+    typename R::Raw raw[kItem];
+#pragma unroll
+    for (int j = 0; j < kItem; ++j) {
+      const int beg = __shfl(beg_v, j, 64), end = __shfl(end_v, j, 64), cell = __shfl(cell_v, j, 64);
+      raw[j] = R::zero();
+      const bool use = p0 + j < p1 && beg >= p0 && end - beg <= kBig;  // wave-uniform
+      if (use && act) raw[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)cell * g.D + ch0);
     }
-    while (p < p1) {
-      const int k = rank[skey[p]];
-      const int end = seg[k + 1];
-      float acc[VEC];
+    float acc[VEC];
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-      const int cnt = end - p;
-      int q = p;
-      for (; q + 4 <= end; q += 4) {
-        typename R::Raw r[4];
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          r[j] = R::zero();
-          if (act) r[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q + j] * g.D + ch0);
+    for (int j = 0; j < kItem; ++j) {
+      const int beg = __shfl(beg_v, j, 64), end = __shfl(end_v, j, 64), row = __shfl(row_v, j, 64);
+      const bool use = p0 + j < p1 && beg >= p0 && end - beg <= kBig;
+      if (!use) continue;
+      acc_row<DT>(raw[j], acc);
+      const int p = p0 + j;
+      if (p + 1 == end || j == kItem - 1 || p + 1 == p1) {
+        // the cluster either ends here, or runs past the item: finish it from the list
+        for (int q = p + 1; q < end; ++q) {
+          typename R::Raw r = R::zero();
+          if (act) r = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q] * g.D + ch0);
+          acc_row<DT>(r, acc);
         }
+        if (act && row < capacity)
+          store_mean<DT, ODT>(merged_v, (size_t)row * g.D + ch0, acc, 1.f / (float)(end - beg));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float t[VEC];
-          R::unpack(r[j], t);
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) acc[v] += t[v];
-        }
+        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
       }
-      for (; q < end; ++q) {
-        typename R::Raw r = R::zero();
-        if (act) r = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q] * g.D + ch0);
-        float t[VEC];
-        R::unpack(r, t);
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[v] += t[v];
-      }
-      if (act && k < capacity) {
-        const float inv = 1.f / (float)cnt;
-        if (ODT == 0) {
-          float* o = reinterpret_cast<float*>(merged_v) + (size_t)k * g.D + ch0;
-#pragma unroll
-          for (int v = 0; v < VEC; v += 4)
-            *reinterpret_cast<float4*>(o + v) =
-                make_float4(acc[v] * inv, acc[v + 1] * inv, acc[v + 2] * inv, acc[v + 3] * inv);
-        } else {
-          uint16_t* o = reinterpret_cast<uint16_t*>(merged_v) + (size_t)k * g.D + ch0;
-          uint32_t w[VEC / 2];
-#pragma unroll
-          for (int v = 0; v < VEC; v += 2)
-            w[v / 2] = f32_to_bf16_rne(acc[v] * inv) | (f32_to_bf16_rne(acc[v + 1] * inv) << 16);
-          if (VEC == 8)
-            *reinterpret_cast<uint4*>(o) = make_uint4(w[0], w[1], w[2 % (VEC / 2)], w[3 % (VEC / 2)]);
-          else
-            *reinterpret_cast<uint2*>(o) = make_uint2(w[0], w[1]);
-        }
-      }
-      p = end;
     }
   }
 }
 
-// Integer plumbing of the reduce stage; returns the sorted member lists through `skey` / `order`.
+// Partial sums of the big clusters over fixed windows of kBig list positions: slot 0 = the big cluster
+// running into the window from the left, slot 1 = the big cluster starting inside it (at most one each).
+template <int DT>
+__global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, const void* __restrict__ feats_v,
+                                                             const int32_t* __restrict__ order,
+                                                             const int32_t* __restrict__ orow,
+                                                             const int32_t* __restrict__ seg,
+                                                             float* __restrict__ bigpart) {
+  typedef Row<DT> R;
+  constexpr int VEC = R::VEC;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, g.N);
+  int beg = -1, end = -1;
+  if (w0 + lane < w1) {
+    const int row = orow[w0 + lane];
+    beg = seg[row];
+    end = seg[row + 1];
+  }
+  const bool big = end - beg > kBig;
+  const int beg0 = __shfl(beg, 0, 64), end0 = __shfl(end, 0, 64);
+  const bool has_left = (end0 - beg0 > kBig) && beg0 < w0;
+  const unsigned long long starts = __ballot(big && beg == w0 + lane);
+  if (!has_left && starts == 0) return;
+  const typename R::Elem* fb = reinterpret_cast<const typename R::Elem*>(feats_v);
+  for (int slot = 0; slot < 2; ++slot) {
+    int a, b;
+    if (slot == 0) {
+      if (!has_left) continue;
+      a = w0;
+      b = min(end0, w1);
+    } else {
+      if (starts == 0) continue;
+      const int l = __ffsll((long long)starts) - 1;
+      a = w0 + l;
+      b = min(__shfl(end, l, 64), w1);
+    }
+    for (int chunk = wave; chunk < g.nC; chunk += nw) {
+      const int ch0 = chunk * g.cch + lane * VEC;
+      if (ch0 >= g.D) continue;
+      float acc[VEC];
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+      int q = a;
+      for (; q + 4 <= b; q += 4) {
+        typename R::Raw r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          r[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q + j] * g.D + ch0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc_row<DT>(r[j], acc);
+      }
+      for (; q < b; ++q)
+        acc_row<DT>(*reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q] * g.D + ch0), acc);
+      float* o = bigpart + ((size_t)blockIdx.x * 2 + slot) * g.D + ch0;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) o[v] = acc[v];
+    }
+  }
+}
+
+// The window in which a big cluster starts adds up its window partials in window order and stores the mean.
+template <int DT, int ODT>
+__global__ __launch_bounds__(1024) void k_reduce_big_combine(Geo g, const int32_t* __restrict__ orow,
+                                                             const int32_t* __restrict__ seg,
+                                                             const float* __restrict__ bigpart, int64_t capacity,
+                                                             void* __restrict__ merged_v) {
+  constexpr int VEC = Row<DT>::VEC;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, g.N);
+  int beg = -1, end = -1, row = -1;
+  if (w0 + lane < w1) {
+    row = orow[w0 + lane];
+    beg = seg[row];
+    end = seg[row + 1];
+  }
+  const unsigned long long starts = __ballot(end - beg > kBig && beg == w0 + lane);
+  if (starts == 0) return;
+  const int l = __ffsll((long long)starts) - 1;
+  const int b = __shfl(beg, l, 64), e = __shfl(end, l, 64), k = __shfl(row, l, 64);
+  if (k >= capacity) return;
+  const int wlast = (e - 1) / kBig;
+  for (int chunk = wave; chunk < g.nC; chunk += nw) {
+    const int ch0 = chunk * g.cch + lane * VEC;
+    if (ch0 >= g.D) continue;
+    float acc[VEC];
+    const float* pp = bigpart + ((size_t)blockIdx.x * 2 + 1) * g.D + ch0;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = pp[v];
+    for (int w = blockIdx.x + 1; w <= wlast; ++w) {
+      const float* q = bigpart + ((size_t)w * 2) * g.D + ch0;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) acc[v] += q[v];
+    }
+    store_mean<DT, ODT>(merged_v, (size_t)k * g.D + ch0, acc, 1.f / (float)(e - b));
+  }
+}
+
+size_t reduce_bigpart_floats(const Geo& g) { return (size_t)((g.N + kBig - 1) / kBig) * 2 * g.D; }
+
+// Integer plumbing of the reduce stage; leaves the sorted member list in `*order_out`.
 void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t capacity, int32_t* counts,
-                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb, const int32_t** skey_out,
+                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
                            const int32_t** order_out, hipStream_t s) {
   const int N = g.N;
   const dim3 b256(256), gN((N + 255) / 256);
@@ -302,20 +418,29 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t cap
     vin = vout;
     if (kout == rb.key_a) { kout = rb.key_b; vout = rb.val_b; } else { kout = rb.key_a; vout = rb.val_a; }
   }
-  hipLaunchKernelGGL(k_segments, gN, b256, 0, s, N, kin, rb.rank, rb.kdev, rb.seg);
+  // kout is now the free key buffer: it receives the output row of every sorted position
+  hipLaunchKernelGGL(k_segments, gN, b256, 0, s, N, kin, rb.rank, rb.kdev, rb.seg, kout);
   if (counts) hipLaunchKernelGGL(k_counts, gN, b256, 0, s, rb.kdev, rb.seg, capacity, counts);
-  *skey_out = kin;
   *order_out = vin;
+  rb.orow_out[0] = kout;
 }
 
-// The feature pass of the reduce stage.
+// The feature pass of the reduce stage (three kernels; the two for big clusters exit at once when there are none).
 void launch_reduce_gather(const Geo& g, const void* feats, int out_dtype, int64_t capacity, void* merged,
-                          const ReduceBuffers& rb, const int32_t* skey, const int32_t* order, hipStream_t s) {
+                          const ReduceBuffers& rb, const int32_t* order, hipStream_t s) {
+  const int32_t* orow = rb.orow_out[0];
   const int nitems = (g.N + kItem - 1) / kItem;
+  const int nwin = (g.N + kBig - 1) / kBig;
   const int nw = g.nC < 16 ? g.nC : 16;
-  dim3 grid(nitems), block(64 * nw);
-#define STTM_REDUCE(DT, ODT) \
-  hipLaunchKernelGGL((k_reduce<DT, ODT>), grid, block, 0, s, g, feats, skey, order, rb.rank, rb.seg, capacity, merged)
+  dim3 grid(nitems), gridw(nwin), block(64 * nw);
+#define STTM_REDUCE(DT, ODT)                                                                                     \
+  do {                                                                                                           \
+    hipLaunchKernelGGL((k_reduce<DT, ODT>), grid, block, 0, s, g, feats, order, orow, rb.seg, capacity, merged); \
+    hipLaunchKernelGGL((k_reduce_big_partial<DT>), gridw, block, 0, s, g, feats, order, orow, rb.seg,            \
+                       rb.bigpart);                                                                              \
+    hipLaunchKernelGGL((k_reduce_big_combine<DT, ODT>), gridw, block, 0, s, g, orow, rb.seg, rb.bigpart,         \
+                       capacity, merged);                                                                        \
+  } while (0)
   if (g.dtype == 1) {
     if (out_dtype == 1) STTM_REDUCE(1, 1); else STTM_REDUCE(1, 0);
   } else {

@@ -253,7 +253,8 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, hipStrea
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __restrict__ part,
                                                           float* __restrict__ nrm2, float* __restrict__ sim,
-                                                          float* __restrict__ m, float* __restrict__ sc) {
+                                                          float* __restrict__ m, uint32_t* __restrict__ sel_key,
+                                                          uint8_t* __restrict__ sel_w) {
   extern __shared__ float sm[];
   float* s_n = sm;
   float* s_sim = sm + g.NN;
@@ -318,14 +319,22 @@ __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __
         ++l; y >>= 1; x >>= 1;
       }
     }
-    sc[fo + idx] = s;
+    // compact (value, weight) element of the budget search: upper-level nodes with >= 2 children
+    if (lvl >= 1) {
+      int kids = 0;
+      if (node_exists(g, lvl, by, bx))
+        for (int k = 0; k < 4; ++k) kids += node_exists(g, lvl - 1, 2 * by + (k >> 1), 2 * bx + (k & 1));
+      const size_t o = (size_t)f * (g.NN - g.lvl_base[1]) + (idx - g.lvl_base[1]);
+      sel_key[o] = kids >= 2 ? float_key(s) : 0u;
+      sel_w[o] = kids >= 2 ? (uint8_t)(kids - 1) : 0;
+    }
   }
 }
 
-void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m, float* sc,
-                             hipStream_t s) {
+void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
+                             uint32_t* sel_key, uint8_t* sel_w, hipStream_t s) {
   hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(256), 3 * g.NN * sizeof(float), s, g, part, nrm2, sim,
-                     m, sc);
+                     m, sel_key, sel_w);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -386,70 +395,48 @@ void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_lev
 
 // ------------------------------------------------------------------------------------------------
 // Budget-driven thresholds. Token count as a function of the threshold is the step function
-// K(tau) = base + sum_j w_j [v_j <= tau]; one workgroup per video finds, by a 4-pass MSB-first radix
-// select over the order-preserving integer image of v, the smallest value whose cumulative weight
-// exceeds target - base, then the largest value below it, and takes the midpoint of the two.
+// K(tau) = base + sum_j w_j [v_j <= tau]. One workgroup per video finds, by an MSB-first radix select
+// (11 + 11 + 10 bits) over the order-preserving integer image of v, the smallest value whose cumulative
+// weight exceeds target - base, then the largest value below it, and takes the midpoint of the two.
+// Input: keys[video][per_video] (0 = not an element), weights (NULL = 1 for every element).
 // ------------------------------------------------------------------------------------------------
-struct SpatialElems {
-  Geo g;
-  const float* sc;
-  __device__ int count() const { return g.T * g.NN; }
-  __device__ bool get(int b, int j, float& v, uint32_t& w) const {
-    const int t = j / g.NN, idx = j - t * g.NN;
-    if (idx < g.lvl_base[1]) return false;
-    int lvl, by, bx;
-    node_decode(g, idx, lvl, by, bx);
-    if (!node_exists(g, lvl, by, bx)) return false;
-    int kids = 0;
-    for (int k = 0; k < 4; ++k) kids += node_exists(g, lvl - 1, 2 * by + (k >> 1), 2 * bx + (k & 1));
-    if (kids < 2) return false;
-    w = kids - 1;
-    v = sc[(size_t)(b * g.T + t) * g.NN + idx];
-    return true;
-  }
-  __device__ int base(int) const {
-    int roots = 0;
-    for (int ry = 0; ry < g.R; ++ry)
-      for (int rx = 0; rx < g.R; ++rx) roots += node_exists(g, g.L, ry, rx);
-    return roots * g.T;
-  }
-};
+constexpr int kSelBins = 2048;
 
-struct TemporalElems {
-  Geo g;
-  const int32_t* node_map;
-  const float* e;
-  __device__ int count() const { return g.T * g.HW; }
-  __device__ bool get(int b, int j, float& v, uint32_t& w) const {
-    if (j < g.HW) return false;  // frame 0 has no candidates
-    const int i = b * g.T * g.HW + j;
-    if (node_map[i] != i) return false;
-    w = 1;
-    v = e[i];
-    if (v != v) v = -2.f;  // NaN never passes
-    return true;
+// Adds w to hist[digit] for the lanes with valid set; lanes sharing a digit are combined first, so the
+// tightly clustered similarities of real data do not serialise on one LDS word.
+__device__ inline void wave_hist_add(unsigned* hist, bool valid, unsigned digit, unsigned w) {
+  unsigned long long todo = __ballot(valid);
+  while (todo) {
+    const int leader = __ffsll((long long)todo) - 1;
+    const unsigned d = __shfl(digit, leader, 64);
+    const bool mine = valid && digit == d;
+    const unsigned long long m = __ballot(mine);
+    const unsigned sum = __popcll(__ballot(mine && (w & 1))) + 2u * __popcll(__ballot(mine && (w & 2)));
+    if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d], sum);
+    todo &= ~m;
   }
-  __device__ int base(int b) const {  // nodes of frame 0 (counted by the caller loop)
-    return -1;
-  }
-};
+}
 
-template <class E>
-__global__ __launch_bounds__(1024) void k_budget_select(E el, const int* __restrict__ target,
+__global__ __launch_bounds__(1024) void k_budget_select(Geo g, const uint32_t* __restrict__ keys,
+                                                        const uint8_t* __restrict__ weights, int per_video,
+                                                        const int* __restrict__ target, int base_const,
+                                                        const int32_t* __restrict__ node_map,
                                                         float* __restrict__ tau) {
-  __shared__ unsigned hist[256];
+  __shared__ unsigned hist[kSelBins];
+  __shared__ unsigned wsum[16];
   __shared__ unsigned s_prefix, s_acc, s_lo;
-  __shared__ int s_state;  // 0 searching, 1 = everything fits (tau = 1)
-  __shared__ int s_base;
-  const int b = blockIdx.x, tid = threadIdx.x, n = el.count();
-  if (tid == 0) { s_prefix = 0; s_acc = 0; s_lo = 0; s_state = 0; s_base = 0; }
+  __shared__ int s_found, s_base;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint32_t* kv = keys + (size_t)b * per_video;
+  const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
+  if (tid == 0) { s_prefix = 0; s_acc = 0; s_lo = 0; s_base = 0; }
   __syncthreads();
-  int base = el.base(b);
-  if (base < 0) {  // temporal: count the kept nodes of frame 0
+  int base = base_const;
+  if (node_map) {  // temporal flavour: base = kept nodes of the video's first frame
     int c = 0;
-    for (int j = tid; j < el.g.HW; j += blockDim.x) {
-      const int i = b * el.g.T * el.g.HW + j;
-      c += (el.node_map_ptr()[i] == i);
+    for (int j = tid; j < g.HW; j += blockDim.x) {
+      const int i = b * g.T * g.HW + j;
+      c += (node_map[i] == i);
     }
     atomicAdd(&s_base, c);
     __syncthreads();
@@ -460,47 +447,56 @@ __global__ __launch_bounds__(1024) void k_budget_select(E el, const int* __restr
     if (tid == 0) tau[b] = -2.f;
     return;
   }
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    for (int j = tid; j < 256; j += blockDim.x) hist[j] = 0;
+  const int shifts[3] = {21, 10, 0};
+  const int widths[3] = {11, 11, 10};
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = shifts[pass], width = widths[pass];
+    for (int j = tid; j < kSelBins; j += blockDim.x) hist[j] = 0;
+    if (tid == 0) s_found = 0;
     __syncthreads();
-    const unsigned prefix = s_prefix;
-    for (int j = tid; j < n; j += blockDim.x) {
-      float v; uint32_t w;
-      if (!el.get(b, j, v, w)) continue;
-      const uint32_t key = float_key(v);
-      if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255u], w);
+    const unsigned prefix = s_prefix, acc0 = s_acc;
+    for (int j0 = 0; j0 < per_video; j0 += blockDim.x) {
+      const int j = j0 + tid;
+      const uint32_t key = j < per_video ? kv[j] : 0u;
+      const unsigned w = key ? (wv ? wv[j] : 1u) : 0u;
+      const bool valid = w != 0 && (pass == 0 || (key >> (shift + width)) == prefix);
+      wave_hist_add(hist, valid, (key >> shift) & ((1u << width) - 1u), w);
     }
     __syncthreads();
-    if (tid == 0) {
-      unsigned long long run = s_acc;
-      int d = 0;
-      for (; d < 256; ++d) {
-        if (run + hist[d] > (unsigned long long)budget) break;
-        run += hist[d];
-      }
-      if (d == 256) {
-        s_state = 1;  // only reachable in pass 0: the whole weight fits
-      } else {
-        s_prefix = (prefix << 8) | (unsigned)d;
-        s_acc = (unsigned)run;
-      }
+    // first bin at which the running weight exceeds the budget (2 bins per thread + block scan)
+    const unsigned h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+    unsigned inc = h0 + h1;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned t = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += t;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    unsigned long long ex = acc0;
+    for (int w = 0; w < wave; ++w) ex += wsum[w];
+    ex += inc - (h0 + h1);
+    const unsigned long long bud = (unsigned long long)budget;
+    if (ex <= bud && ex + h0 > bud) {
+      s_found = 1; s_prefix = (prefix << width) | (unsigned)(2 * tid); s_acc = (unsigned)ex;
+    } else if (ex + h0 <= bud && ex + h0 + h1 > bud) {
+      s_found = 1; s_prefix = (prefix << width) | (unsigned)(2 * tid + 1); s_acc = (unsigned)(ex + h0);
     }
     __syncthreads();
-    if (s_state == 1) {
+    if (!s_found) {  // only possible in the first pass: the whole weight fits
       if (tid == 0) tau[b] = 1.f;
       return;
     }
   }
   const unsigned over = s_prefix;  // smallest value at which K exceeds the target
-  unsigned lo = 0;                 // key 0 is below every real value (keys of finite floats are > 0)
-  for (int j = tid; j < n; j += blockDim.x) {
-    float v; uint32_t w;
-    if (!el.get(b, j, v, w)) continue;
-    const uint32_t key = float_key(v);
-    if (key < over && key > lo) lo = key;
+  unsigned lo = 0;                 // key 0 is below every real value
+  for (int j = tid; j < per_video; j += blockDim.x) {
+    const uint32_t key = kv[j];
+    if (key && (!wv || wv[j]) && key < over && key > lo) lo = key;
   }
-  atomicMax(&s_lo, lo);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) lo = max(lo, (unsigned)__shfl_xor((int)lo, o, 64));
+  if (lane == 0) atomicMax(&s_lo, lo);
   __syncthreads();
   if (tid == 0) {
     const float hi = key_float(over);
@@ -511,28 +507,20 @@ __global__ __launch_bounds__(1024) void k_budget_select(E el, const int* __restr
   }
 }
 
-// node_map accessor used by the temporal flavour only
-struct TemporalElemsImpl : TemporalElems {
-  __device__ const int32_t* node_map_ptr() const { return node_map; }
-};
-struct SpatialElemsImpl : SpatialElems {
-  __device__ const int32_t* node_map_ptr() const { return nullptr; }
-};
-
-void launch_select_spatial(const Geo& g, const float* sc, const int* target, float* tau, hipStream_t s) {
-  SpatialElemsImpl el;
-  el.g = g;
-  el.sc = sc;
-  hipLaunchKernelGGL(k_budget_select<SpatialElemsImpl>, dim3(g.B), dim3(1024), 0, s, el, target, tau);
+void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
+                           float* tau, hipStream_t s) {
+  int roots = 0;
+  for (int ry = 0; ry < g.R; ++ry)
+    for (int rx = 0; rx < g.R; ++rx) roots += node_exists(g, g.L, ry, rx);
+  const int per_video = g.T * (g.NN - g.lvl_base[1]);
+  hipLaunchKernelGGL(k_budget_select, dim3(g.B), dim3(1024), 0, s, g, keys, weights, per_video, target,
+                     roots * g.T, (const int32_t*)nullptr, tau);
 }
 
-void launch_select_temporal(const Geo& g, const int32_t* node_map, const float* e, const int* target,
+void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
                             float* tau, hipStream_t s) {
-  TemporalElemsImpl el;
-  el.g = g;
-  el.node_map = node_map;
-  el.e = e;
-  hipLaunchKernelGGL(k_budget_select<TemporalElemsImpl>, dim3(g.B), dim3(1024), 0, s, el, target, tau);
+  hipLaunchKernelGGL(k_budget_select, dim3(g.B), dim3(1024), 0, s, g, keys, (const uint8_t*)nullptr,
+                     g.T * g.HW, target, 0, node_map, tau);
 }
 
 }  // namespace sttm

@@ -143,99 +143,119 @@ __device__ inline int node_idx_of(const Geo& g, int lvl, int y0, int x0) {
   return node_index(g, lvl, y0 >> lvl, x0 >> lvl);
 }
 
+// Per-frame view of the two partitions in LDS, shared by the two kernels below.
+struct PairFrame {
+  uint8_t lvl_t[1024], lvl_p[1024];
+  int16_t rep_t[1024], rep_p[1024];
+};
+
+__device__ inline void load_pair_frame(const Geo& g, int f, const int32_t* node_map, const uint8_t* node_level,
+                                       PairFrame& pf) {
+  const int HW = g.HW;
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) {
+    pf.lvl_t[c] = node_level[(size_t)f * HW + c];
+    pf.lvl_p[c] = node_level[(size_t)(f - 1) * HW + c];
+    pf.rep_t[c] = (int16_t)(node_map[(size_t)f * HW + c] - f * HW);
+    pf.rep_p[c] = (int16_t)(node_map[(size_t)(f - 1) * HW + c] - (f - 1) * HW);
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
-// k_temporal_resolve: one thread per kept node n of a frame t >= 1 (at its top-left cell). Sums the
-// per-chunk partial dots in chunk order, divides by the norms from the spatial stage, stores the
-// similarity of every (n, d) pair at the pair's slot and e_n = max over n's destinations.
+// k_temporal_resolve: one workgroup per frame. Every overlapping (source n in frame t, destination d in
+// frame t-1) pair lives at the top-left cell of the finer of the two nodes: the thread of that cell sums
+// the per-chunk partial dots in chunk order, divides by the norms from the spatial stage and stores the
+// similarity; e_n = max over n's destinations is collected with an integer max in LDS (order-free).
+// Also writes the order-preserving integer image of e_n for the budget search (0 = not a candidate).
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* __restrict__ node_map,
                                                           const uint8_t* __restrict__ node_level,
                                                           const float* __restrict__ pd_part,
                                                           const float* __restrict__ nrm2,
-                                                          float* __restrict__ sig, float* __restrict__ e) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= g.N) return;
-  const int f = i / g.HW, c = i - f * g.HW;
-  if (f % g.T == 0 || node_map[i] != i) return;
-  const int W = g.W, H = g.H, HW = g.HW;
-  const int y0 = c / W, x0 = c - y0 * W;
-  const int a = node_level[i];
-  const float nn = nrm2[(size_t)f * g.NN + node_idx_of(g, a, y0, x0)];
-  const size_t fp = (size_t)(f - 1) * HW;
-  const int bb = node_level[fp + c];
-  float best = -2.f;
-  bool any_nan = false;
-  auto pair_sim = [&](int q, int dl, int dy0, int dx0) {
-    float d = 0.f;
-    for (int k = 0; k < g.nC; ++k) d += pd_part[(size_t)(f * g.nC + k) * HW + q];
-    const float nd = nrm2[(size_t)(f - 1) * g.NN + node_idx_of(g, dl, dy0, dx0)];
-    const float v = cosine_from(d, nn, nd);
-    sig[(size_t)f * HW + q] = v;
-    if (v != v) any_nan = true; else best = fmaxf(best, v);
-  };
-  if (bb >= a) {
-    // destination is the same block or a coarser one: a single pair, stored at n's own cell
-    const int r = node_map[fp + c] - (f - 1) * HW;
-    pair_sim(c, bb, r / W, r % W);
-  } else {
-    // n is coarser: every kept node of frame t-1 inside n's block is a destination
-    const int s = 1 << a;
-    for (int y = y0; y < min(y0 + s, H); ++y)
-      for (int x = x0; x < min(x0 + s, W); ++x) {
-        const int q = y * W + x;
-        if (node_map[fp + q] - (f - 1) * HW == q) pair_sim(q, node_level[fp + q], y, x);
-      }
+                                                          float* __restrict__ sig, float* __restrict__ e,
+                                                          uint32_t* __restrict__ sel_key) {
+  __shared__ PairFrame pf;
+  __shared__ unsigned ekey[1024];
+  const int f = blockIdx.x, HW = g.HW, W = g.W;
+  if (f % g.T == 0) {
+    for (int c = threadIdx.x; c < HW; c += blockDim.x) sel_key[(size_t)f * HW + c] = 0;
+    return;
   }
-  (void)any_nan;
-  e[i] = best;
+  load_pair_frame(g, f, node_map, node_level, pf);
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) ekey[c] = 0;
+  __syncthreads();
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) {
+    const int a = pf.lvl_t[c], b = pf.lvl_p[c];
+    const int n = pf.rep_t[c], d = pf.rep_p[c];
+    if ((a <= b ? n : d) != c) continue;  // not the top-left cell of the finer node
+    float dot = 0.f;
+    for (int k = 0; k < g.nC; ++k) dot += pd_part[(size_t)(f * g.nC + k) * HW + c];
+    const float nn = nrm2[(size_t)f * g.NN + node_idx_of(g, a, n / W, n % W)];
+    const float nd = nrm2[(size_t)(f - 1) * g.NN + node_idx_of(g, b, d / W, d % W)];
+    const float v = cosine_from(dot, nn, nd);
+    sig[(size_t)f * HW + c] = v;
+    if (v == v) atomicMax(&ekey[n], float_key(v));
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) {
+    const size_t i = (size_t)f * HW + c;
+    if (pf.rep_t[c] != c) { sel_key[i] = 0; continue; }
+    const unsigned k = ekey[c];                 // 0 only if every similarity was NaN
+    e[i] = k ? key_float(k) : -2.f;
+    sel_key[i] = k ? k : float_key(-2.f);
+  }
 }
 
 void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
-                             const float* pd_part, const float* nrm2, float* sig, float* e, hipStream_t s) {
-  hipLaunchKernelGGL(k_temporal_resolve, dim3((g.N + 255) / 256), dim3(256), 0, s, g, node_map, node_level,
-                     pd_part, nrm2, sig, e);
+                             const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(k_temporal_resolve, dim3(g.F), dim3(256), 0, s, g, node_map, node_level, pd_part, nrm2, sig,
+                     e, sel_key);
 }
 
 // ------------------------------------------------------------------------------------------------
 // k_temporal_parent: directed edge of every kept node (Sec. 3.3): among the destinations whose similarity
-// exceeds tau_T the one towards the top-left (raster order). Also seeds the pointer-jumping array.
+// exceeds tau_T the one towards the top-left (smallest raster index; integer min in LDS). Also seeds the
+// pointer-jumping array.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_temporal_parent(Geo g, const int32_t* __restrict__ node_map,
                                                          const uint8_t* __restrict__ node_level,
                                                          const float* __restrict__ sig,
                                                          const float* __restrict__ tau,
                                                          int32_t* __restrict__ parent, int32_t* __restrict__ ptr) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= g.N) return;
-  const int f = i / g.HW, c = i - f * g.HW;
-  int par = -1;
-  if (f % g.T != 0 && node_map[i] == i) {
-    const int W = g.W, H = g.H, HW = g.HW;
-    const float th = tau[f / g.T];
-    const size_t fp = (size_t)(f - 1) * HW;
-    const int a = node_level[i], bb = node_level[fp + c];
-    if (bb >= a) {
-      if (sig[(size_t)f * HW + c] > th) par = node_map[fp + c];
-    } else {
-      const int y0 = c / W, x0 = c - y0 * W, s = 1 << a;
-      for (int y = y0; y < min(y0 + s, H) && par < 0; ++y)
-        for (int x = x0; x < min(x0 + s, W); ++x) {
-          const int q = y * W + x;
-          if (node_map[fp + q] - (f - 1) * HW == q && sig[(size_t)f * HW + q] > th) {
-            par = (f - 1) * HW + q;
-            break;
-          }
-        }
+  __shared__ PairFrame pf;
+  __shared__ int par[1024];
+  const int f = blockIdx.x, HW = g.HW;
+  if (f % g.T == 0) {
+    for (int c = threadIdx.x; c < HW; c += blockDim.x) {
+      parent[(size_t)f * HW + c] = -1;
+      ptr[(size_t)f * HW + c] = f * HW + c;
     }
+    return;
   }
-  parent[i] = par;
-  ptr[i] = par >= 0 ? par : i;
+  load_pair_frame(g, f, node_map, node_level, pf);
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) par[c] = 0x7fffffff;
+  __syncthreads();
+  const float th = tau[f / g.T];
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) {
+    const int a = pf.lvl_t[c], b = pf.lvl_p[c];
+    const int n = pf.rep_t[c], d = pf.rep_p[c];
+    if ((a <= b ? n : d) != c) continue;
+    if (sig[(size_t)f * HW + c] > th) atomicMin(&par[n], d);
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) {
+    const int i = f * HW + c;
+    int p = -1;
+    if (pf.rep_t[c] == c && par[c] != 0x7fffffff) p = (f - 1) * HW + par[c];
+    parent[i] = p;
+    ptr[i] = p >= 0 ? p : i;
+  }
 }
 
 void launch_temporal_parent(const Geo& g, const int32_t* node_map, const uint8_t* node_level, const float* sig,
                             const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s) {
-  hipLaunchKernelGGL(k_temporal_parent, dim3((g.N + 255) / 256), dim3(256), 0, s, g, node_map, node_level, sig,
-                     tau, parent, ptr);
+  hipLaunchKernelGGL(k_temporal_parent, dim3(g.F), dim3(256), 0, s, g, node_map, node_level, sig, tau, parent,
+                     ptr);
 }
 
 // ------------------------------------------------------------------------------------------------
