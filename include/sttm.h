@@ -24,7 +24,7 @@
  *     hand a value back through a host pointer (documented per call), in which case they synchronise the stream.
  *   - feats is contiguous [B, T, H, W, D] (D fastest), B independent videos; tokens are addressed by the
  *     flat cell index i = ((b*T + t)*H + y)*W + x.  Requirements: 1 <= H, W <= 32; D % 8 == 0;
- *     B*T*H*W < 2^31; root_grid a power of two <= P, P = smallest power of two >= max(H, W).
+ *     B*T <= 65535 frames; B*T*H*W < 2^31; root_grid a power of two <= P, P = smallest power of two >= max(H, W).
  *   - a grid that is not a power of two is embedded top-left in the P x P grid; padded cells take no part.
  *   - quadtree level 0 is the finest (single cells), level log2(P/root_grid) holds the roots.
  *   - similarities are clamped to <= 1 and compared strictly (">"): a threshold >= 1 merges nothing.

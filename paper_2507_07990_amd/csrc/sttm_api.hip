@@ -17,7 +17,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t part, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
+  size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
   size_t rank, blocksum, key_a, val_a, key_b, val_b, hist, seg, kdev, bigpart;
   size_t total;
 };
@@ -27,6 +27,7 @@ bool make_geo(int B, int T, int H, int W, int D, int dtype, int root_grid, Geo* 
   if (dtype != STTM_F32 && dtype != STTM_BF16) return false;
   long long n = (long long)B * T * H * W;
   if (n >= (1ll << 31) - 1) return false;
+  if ((long long)B * T > 65535) return false;  // frames index a grid dimension
   int P = 1;
   while (P < (H > W ? H : W)) P *= 2;
   if (root_grid < 1 || (root_grid & (root_grid - 1)) || root_grid > P) return false;
@@ -54,6 +55,7 @@ Layout make_layout(const Geo& g) {
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   const size_t F = g.F, NN = g.NN, N = g.N;
   l.part = take(F * g.nC * 2 * NN * sizeof(float));
+  l.nsum = take(F * nsum_nodes(g) * g.D * sizeof(float));
   l.nrm2 = take(F * NN * sizeof(float));
   l.sim = take(F * NN * sizeof(float));
   l.m = take(F * NN * sizeof(float));
@@ -62,7 +64,8 @@ Layout make_layout(const Geo& g) {
   l.sel_key_t = take(N * sizeof(uint32_t));
   l.tau_s = take(g.B * sizeof(float));
   l.tau_t = take(g.B * sizeof(float));
-  l.target = take(g.B * sizeof(int));
+  l.target_s = take(g.B * sizeof(int));
+  l.target_t = take(g.B * sizeof(int));
   l.lvl = take(N);
   l.pd_part = take(F * g.nC * g.HW * sizeof(float));
   l.sig = take(N * sizeof(float));
@@ -99,8 +102,8 @@ struct sttm_ctx {
   bool have_spatial = false, have_tau_s = false, have_temporal = false, have_tau_t = false;
   const void* feats_spatial = nullptr;
   const int32_t* node_map_temporal = nullptr;  // caller's node map of the last temporal statistics pass
-  std::vector<float> h_tau;                    // host staging that outlives the asynchronous uploads
-  std::vector<int> h_target;
+  std::vector<float> h_tau_s, h_tau_t;         // host staging that outlives the asynchronous uploads
+  std::vector<int> h_target_s, h_target_t;
   std::string err;
   // optional per-kernel timing of the three feature passes (HIP events on the context's stream)
   bool profiling = false;
@@ -134,7 +137,7 @@ int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int ro
   Geo g;
   if (!make_geo(B, T, H, W, D, dtype, root_grid, &g))
     return fail(c, STTM_ERR_SHAPE,
-                "need B,T >= 1, 1 <= H,W <= 32, D % 8 == 0, B*T*H*W < 2^31, root_grid a power of two <= P");
+                "need B,T >= 1, B*T <= 65535, 1 <= H,W <= 32, D % 8 == 0, B*T*H*W < 2^31, root_grid a power of two <= P");
   Layout l = make_layout(g);
   if (!c->ws) return fail(c, STTM_ERR_WORKSPACE, "no workspace set (sttm_set_workspace)");
   if (c->ws_bytes < l.total) {
@@ -153,11 +156,11 @@ bool same_shape(const Geo& g, int dtype, int B, int T, int H, int W, int D, int 
   return g.dtype == dtype && g.B == B && g.T == T && g.H == H && g.W == W && g.D == D && g.R == root_grid;
 }
 
-int upload_tau(sttm_ctx* c, const float* host, float* dev) {
+int upload_tau(sttm_ctx* c, const float* host, float* dev, std::vector<float>* staging) {
   for (int b = 0; b < c->g.B; ++b)
     if (host[b] != host[b]) return fail(c, STTM_ERR_ARG, "threshold is NaN");
-  c->h_tau.assign(host, host + c->g.B);
-  STTM_HIP(c, hipMemcpyAsync(dev, c->h_tau.data(), c->g.B * sizeof(float), hipMemcpyHostToDevice, c->stream));
+  staging->assign(host, host + c->g.B);
+  STTM_HIP(c, hipMemcpyAsync(dev, staging->data(), c->g.B * sizeof(float), hipMemcpyHostToDevice, c->stream));
   return STTM_OK;
 }
 
@@ -186,7 +189,7 @@ int after_launch(sttm_ctx* c) { return hip_check(c, hipGetLastError(), "kernel l
 int run_spatial_stats(sttm_ctx* c, const void* feats) {
   {
     Timed t(c, STTM_KERNEL_PYRAMID_STATS);
-    launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), c->stream);
+    launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum), c->stream);
   }
   launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nrm2), at<float>(c, c->lay.sim),
                           at<float>(c, c->lay.m), at<uint32_t>(c, c->lay.sel_key_s), at<uint8_t>(c, c->lay.sel_w_s),
@@ -203,7 +206,8 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
 int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, const uint8_t* node_level) {
   {
     Timed t(c, STTM_KERNEL_TEMPORAL_DOTS);
-    launch_temporal_dots(c->g, feats, node_map, node_level, at<float>(c, c->lay.pd_part), c->stream);
+    launch_temporal_dots(c->g, feats, node_level, at<float>(c, c->lay.nsum), at<float>(c, c->lay.pd_part),
+                         c->stream);
   }
   launch_temporal_resolve(c->g, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
                           at<float>(c, c->lay.sig), at<float>(c, c->lay.e), at<uint32_t>(c, c->lay.sel_key_t),
@@ -308,7 +312,7 @@ int sttm_spatial_quadtree(sttm_ctx* ctx, const void* feats_dev, int dtype, int B
     if (rc) return rc;
     rc = bind_shape(ctx, dtype, B, T, H, W, D, root_grid);
     if (rc) return rc;
-    rc = upload_tau(ctx, tau_s_host, at<float>(ctx, ctx->lay.tau_s));
+    rc = upload_tau(ctx, tau_s_host, at<float>(ctx, ctx->lay.tau_s), &ctx->h_tau_s);
     if (rc) return rc;
     ctx->have_tau_s = true;
     rc = run_spatial_stats(ctx, feats_dev);
@@ -357,7 +361,7 @@ int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* nod
   int rc = temporal_prepare(ctx, feats_dev, node_map_dev, &node_level_dev);
   if (rc) return rc;
   if (tau_t_host) {
-    rc = upload_tau(ctx, tau_t_host, at<float>(ctx, ctx->lay.tau_t));
+    rc = upload_tau(ctx, tau_t_host, at<float>(ctx, ctx->lay.tau_t), &ctx->h_tau_t);
     if (rc) return rc;
     ctx->have_tau_t = true;
     rc = run_temporal_stats(ctx, feats_dev, node_map_dev, node_level_dev);
@@ -391,21 +395,23 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
     const double k = target_keep_host[b];
     if (!(k > 0.0 && k <= 1.0)) return fail(ctx, STTM_ERR_ARG, "target_keep must be in (0, 1]");
   }
-  ctx->h_target.resize(g.B);
+  std::vector<int>& h_target = stage == STTM_STAGE_SPATIAL ? ctx->h_target_s : ctx->h_target_t;
+  h_target.resize(g.B);
   for (int b = 0; b < g.B; ++b) {
     const double k = target_keep_host[b];
-    ctx->h_target[b] = (int)std::floor((stage == STTM_STAGE_SPATIAL ? std::sqrt(k) : k) * thw);
+    h_target[b] = (int)std::floor((stage == STTM_STAGE_SPATIAL ? std::sqrt(k) : k) * thw);
   }
   int rc;
-  STTM_HIP(ctx, hipMemcpyAsync(at<int>(ctx, ctx->lay.target), ctx->h_target.data(), g.B * sizeof(int),
-                               hipMemcpyHostToDevice, ctx->stream));
+  int* target_dev = at<int>(ctx, stage == STTM_STAGE_SPATIAL ? ctx->lay.target_s : ctx->lay.target_t);
+  STTM_HIP(ctx, hipMemcpyAsync(target_dev, h_target.data(), g.B * sizeof(int), hipMemcpyHostToDevice,
+                               ctx->stream));
   float* tau_dev = at<float>(ctx, stage == STTM_STAGE_SPATIAL ? ctx->lay.tau_s : ctx->lay.tau_t);
   if (stage == STTM_STAGE_SPATIAL)
     launch_select_spatial(g, at<uint32_t>(ctx, ctx->lay.sel_key_s), at<uint8_t>(ctx, ctx->lay.sel_w_s),
-                          at<int>(ctx, ctx->lay.target), tau_dev, ctx->stream);
+                          target_dev, tau_dev, ctx->stream);
   else
-    launch_select_temporal(g, ctx->node_map_temporal, at<uint32_t>(ctx, ctx->lay.sel_key_t),
-                           at<int>(ctx, ctx->lay.target), tau_dev, ctx->stream);
+    launch_select_temporal(g, ctx->node_map_temporal, at<uint32_t>(ctx, ctx->lay.sel_key_t), target_dev, tau_dev,
+                           ctx->stream);
   rc = after_launch(ctx);
   if (rc) return rc;
   if (stage == STTM_STAGE_SPATIAL) ctx->have_tau_s = true; else ctx->have_tau_t = true;

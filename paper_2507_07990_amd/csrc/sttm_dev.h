@@ -3,6 +3,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Dynamic LDS of a kernel. (The second form serves the host-thread build used by the CPU tests.)
+#ifndef STTM_HOST_EMULATION
+#define STTM_DYNAMIC_LDS(T, name) extern __shared__ T name[]
+#else
+#define STTM_DYNAMIC_LDS(T, name) T* name = reinterpret_cast<T*>(hip_emul::g_dynamic_lds)
+#endif
+
 namespace sttm {
 
 constexpr int kWave = 64;
@@ -108,7 +115,7 @@ __device__ inline void wave_lds_fence() {
 // ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
 struct Workspace;  // see sttm_api.hip
 
-void launch_pyramid_stats(const Geo& g, const void* feats, float* part, hipStream_t s);
+void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, hipStream_t s);
 void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
                              uint32_t* sel_key, uint8_t* sel_w, hipStream_t s);
 void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
@@ -117,8 +124,10 @@ void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* we
                            float* tau, hipStream_t s);
 void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
                             float* tau, hipStream_t s);
-void launch_temporal_dots(const Geo& g, const void* feats, const int32_t* node_map, const uint8_t* node_level,
+void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
                           float* pd_part, hipStream_t s);
+// fp32 sums of the pyramid nodes at levels >= 3: [F][nsum_nodes][D]
+inline size_t nsum_nodes(const Geo& g) { return g.L >= 3 ? (size_t)(g.NN - g.lvl_base[3]) : 0; }
 void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
                              const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
                              hipStream_t s);

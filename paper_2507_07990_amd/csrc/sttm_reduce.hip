@@ -93,11 +93,12 @@ static void exclusive_scan(int n, const int32_t* in, int32_t* out, int32_t* bloc
   hipLaunchKernelGGL(k_scan_add, dim3(nb), dim3(kScanBlock), 0, s, n, out, blocksum);
 }
 
-// ---- stable LSD radix sort of (key, value) pairs, 8-bit digits --------------------------------------
+// ---- stable LSD radix sort of (key, value) pairs, 11-bit digits --------------------------------------
 // A workgroup is one wavefront that owns kSortTile consecutive elements; it handles them 64 at a time in
 // index order, so ranks inside the tile are stable without any cross-wave ordering.
-constexpr int kSortTile = 2048;
-constexpr int kRadix = 256;
+constexpr int kSortTile = 1024;
+constexpr int kRadixBits = 11;
+constexpr int kRadix = 1 << kRadixBits;
 
 size_t reduce_hist_entries(int N) { return (size_t)kRadix * ((N + kSortTile - 1) / kSortTile); }
 
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(64) void k_sort_scatter(int n, int shift, const int
     // lanes holding the same digit
     unsigned long long same = __ballot(ok);
 #pragma unroll
-    for (int bit = 0; bit < 8; ++bit) {
+    for (int bit = 0; bit < kRadixBits; ++bit) {
       const unsigned long long m = __ballot((digit >> bit) & 1);
       same &= ((digit >> bit) & 1) ? m : ~m;
     }
@@ -303,11 +304,12 @@ __global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, const void* 
   constexpr int VEC = R::VEC;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
   const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, g.N);
-  int beg = -1, end = -1;
+  int beg = -1, end = -1, cell_v = 0;
   if (w0 + lane < w1) {
     const int row = orow[w0 + lane];
     beg = seg[row];
     end = seg[row + 1];
+    cell_v = order[w0 + lane];
   }
   const bool big = end - beg > kBig;
   const int beg0 = __shfl(beg, 0, 64), end0 = __shfl(end, 0, 64);
@@ -329,21 +331,24 @@ __global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, const void* 
     }
     for (int chunk = wave; chunk < g.nC; chunk += nw) {
       const int ch0 = chunk * g.cch + lane * VEC;
-      if (ch0 >= g.D) continue;
+      const bool act = ch0 < g.D;
       float acc[VEC];
 #pragma unroll
       for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-      int q = a;
-      for (; q + 4 <= b; q += 4) {
-        typename R::Raw r[4];
+      // rows a..b-1 of the window, eight loads in flight; the cell of list position w0 + l sits in lane l
+      for (int q = a; q < b; q += 8) {
+        typename R::Raw r[8];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          r[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q + j] * g.D + ch0);
+        for (int j = 0; j < 8; ++j) {
+          const int cell = __shfl(cell_v, min(q + j, w1 - 1) - w0, 64);
+          r[j] = R::zero();
+          if (q + j < b && act) r[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)cell * g.D + ch0);
+        }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc_row<DT>(r[j], acc);
+        for (int j = 0; j < 8; ++j)
+          if (q + j < b) acc_row<DT>(r[j], acc);
       }
-      for (; q < b; ++q)
-        acc_row<DT>(*reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q] * g.D + ch0), acc);
+      if (!act) continue;
       float* o = bigpart + ((size_t)blockIdx.x * 2 + slot) * g.D + ch0;
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = acc[v];
@@ -409,7 +414,7 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t cap
   int32_t* kout = rb.key_a;
   int32_t* vout = rb.val_a;
   int pass = 0;
-  for (int shift = 0; shift < bits; shift += 8, ++pass) {
+  for (int shift = 0; shift < bits; shift += kRadixBits, ++pass) {
     hipLaunchKernelGGL(k_sort_hist, dim3(nblocks), dim3(64), 0, s, N, shift, kin, rb.hist, nblocks);
     exclusive_scan<0>(kRadix * nblocks, rb.hist, rb.hist, rb.blocksum, (int32_t*)nullptr, s);
     hipLaunchKernelGGL(k_sort_scatter, dim3(nblocks), dim3(64), 0, s, N, shift, kin, vin, kout, vout, rb.hist,

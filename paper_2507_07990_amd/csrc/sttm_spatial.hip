@@ -15,7 +15,9 @@ namespace sttm {
 // of 4 level-1 blocks of 4 cells. Levels above 3 are finished by the whole workgroup from the
 // per-channel level-3 sums kept in LDS.
 // Output: part[f][chunk][0][node] = partial squared norm of the node's sum over this chunk's channels,
-//         part[f][chunk][1][node] = partial dot product of the node's sum with its parent's sum.
+//         part[f][chunk][1][node] = partial dot product of the node's sum with its parent's sum,
+//         nsum[f][node - first level-3 node][D] = the per-channel sums of the nodes at levels >= 3 (fp32),
+//         which the later stages read instead of re-adding up to P*P token rows.
 // ------------------------------------------------------------------------------------------------
 constexpr int kTileRows = 40;    // 16 n0 + 16 d0 + 4 n1 + 4 d1
 constexpr int kRowStride = 68;   // 64 lanes + pad, keeps 16-byte alignment of every row
@@ -23,10 +25,10 @@ constexpr int kStatsWaves = 4;
 
 template <int DT>
 __global__ __launch_bounds__(256) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
-                                                       float* __restrict__ part) {
+                                                       float* __restrict__ part, float* __restrict__ nsum) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
-  extern __shared__ float smem[];
+  STTM_DYNAMIC_LDS(float, smem);
   const int chunk = blockIdx.x, f = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ch0 = chunk * g.cch + lane * VEC;
@@ -178,6 +180,12 @@ __global__ __launch_bounds__(256) void k_pyramid_stats(Geo g, const void* __rest
 #pragma unroll
       for (int v = 0; v < VEC; ++v) s3buf[u * g.cch + lane * VEC + v] = S3[v];
     }
+    if (L >= 3 && y3 < H && x3 < W && act) {
+      float* o = nsum + ((size_t)f * (g.NN - g.lvl_base[3]) + (y3 >> 3) * (P >> 3) + (x3 >> 3)) * g.D + ch0;
+#pragma unroll
+      for (int v = 0; v < VEC; v += 4)
+        *reinterpret_cast<float4*>(o + v) = make_float4(S3[v], S3[v + 1], S3[v + 2], S3[v + 3]);
+    }
   }
 
   if (L > 3) {
@@ -198,6 +206,9 @@ __global__ __launch_bounds__(256) void k_pyramid_stats(Geo g, const void* __rest
             a[k] = child[((2 * by + (k >> 1)) * Gc + 2 * bx + (k & 1)) * g.cch + c];
           const float S = (a[0] + a[1]) + (a[2] + a[3]);
           cur[nd * g.cch + c] = S;
+          if (chunk * g.cch + c < g.D)
+            nsum[((size_t)f * (g.NN - g.lvl_base[3]) + node_index(g, lvl, by, bx) - g.lvl_base[3]) * g.D +
+                 chunk * g.cch + c] = S;
           tot[0] = fmaf(S, S, tot[0]);
 #pragma unroll
           for (int k = 0; k < 4; ++k) tot[1 + k] = fmaf(a[k], S, tot[1 + k]);
@@ -237,13 +248,13 @@ static size_t stats_lds_bytes(const Geo& g) {
   return fl * sizeof(float);
 }
 
-void launch_pyramid_stats(const Geo& g, const void* feats, float* part, hipStream_t s) {
+void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, hipStream_t s) {
   dim3 grid(g.nC, g.F), block(256);
   size_t lds = stats_lds_bytes(g);
   if (g.dtype == 1)
-    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, lds, s, g, feats, part);
+    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, lds, s, g, feats, part, nsum);
   else
-    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, lds, s, g, feats, part);
+    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, lds, s, g, feats, part, nsum);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -255,7 +266,7 @@ __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __
                                                           float* __restrict__ nrm2, float* __restrict__ sim,
                                                           float* __restrict__ m, uint32_t* __restrict__ sel_key,
                                                           uint8_t* __restrict__ sel_w) {
-  extern __shared__ float sm[];
+  STTM_DYNAMIC_LDS(float, sm);
   float* s_n = sm;
   float* s_sim = sm + g.NN;
   float* s_m = sm + 2 * g.NN;
@@ -401,12 +412,14 @@ void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_lev
 // Input: keys[video][per_video] (0 = not an element), weights (NULL = 1 for every element).
 // ------------------------------------------------------------------------------------------------
 constexpr int kSelBins = 2048;
+constexpr int kSelBatch = 24;
 
-// Adds w to hist[digit] for the lanes with valid set; lanes sharing a digit are combined first, so the
-// tightly clustered similarities of real data do not serialise on one LDS word.
+// Adds w to hist[digit] for the lanes with valid set. The two most frequent leading digits of the wavefront
+// are combined before the atomic (real similarities sit in tight clusters, which would otherwise serialise
+// on one LDS word); whatever is left goes through plain LDS atomics.
 __device__ inline void wave_hist_add(unsigned* hist, bool valid, unsigned digit, unsigned w) {
   unsigned long long todo = __ballot(valid);
-  while (todo) {
+  for (int it = 0; it < 2 && todo; ++it) {
     const int leader = __ffsll((long long)todo) - 1;
     const unsigned d = __shfl(digit, leader, 64);
     const bool mine = valid && digit == d;
@@ -415,8 +428,12 @@ __device__ inline void wave_hist_add(unsigned* hist, bool valid, unsigned digit,
     if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d], sum);
     todo &= ~m;
   }
+  if ((todo >> (threadIdx.x & 63)) & 1ull) atomicAdd(&hist[digit], w);
 }
 
+// EPT > 0: every thread keeps its EPT elements in registers (one round of loads, then four passes without
+// touching memory); EPT == 0: elements are streamed from memory in every pass (any size).
+template <int EPT>
 __global__ __launch_bounds__(1024) void k_budget_select(Geo g, const uint32_t* __restrict__ keys,
                                                         const uint8_t* __restrict__ weights, int per_video,
                                                         const int* __restrict__ target, int base_const,
@@ -429,6 +446,23 @@ __global__ __launch_bounds__(1024) void k_budget_select(Geo g, const uint32_t* _
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const uint32_t* kv = keys + (size_t)b * per_video;
   const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
+  constexpr int NR = EPT > 0 ? EPT : 1;
+  uint32_t rkey[NR];          // key, 0 = no element
+  uint32_t rw[(NR + 15) / 16]; // 2-bit weights
+  if (EPT > 0) {
+#pragma unroll
+    for (int u = 0; u < (NR + 15) / 16; ++u) rw[u] = 0;
+#pragma unroll
+    for (int u = 0; u < NR; ++u) {
+      const int j = u * 1024 + tid;
+      uint32_t k = j < per_video ? kv[j] : 0u;
+      unsigned w = 1u;
+      if (wv) w = j < per_video ? wv[j] : 0u;
+      if (w == 0) k = 0;
+      rkey[u] = k;
+      rw[u / 16] |= (w & 3u) << (2 * (u % 16));
+    }
+  }
   if (tid == 0) { s_prefix = 0; s_acc = 0; s_lo = 0; s_base = 0; }
   __syncthreads();
   int base = base_const;
@@ -455,12 +489,32 @@ __global__ __launch_bounds__(1024) void k_budget_select(Geo g, const uint32_t* _
     if (tid == 0) s_found = 0;
     __syncthreads();
     const unsigned prefix = s_prefix, acc0 = s_acc;
-    for (int j0 = 0; j0 < per_video; j0 += blockDim.x) {
-      const int j = j0 + tid;
-      const uint32_t key = j < per_video ? kv[j] : 0u;
-      const unsigned w = key ? (wv ? wv[j] : 1u) : 0u;
-      const bool valid = w != 0 && (pass == 0 || (key >> (shift + width)) == prefix);
-      wave_hist_add(hist, valid, (key >> shift) & ((1u << width) - 1u), w);
+    if (EPT > 0) {
+#pragma unroll
+      for (int u = 0; u < NR; ++u) {
+        const uint32_t key = rkey[u];
+        const unsigned w = (rw[u / 16] >> (2 * (u % 16))) & 3u;
+        const bool valid = key != 0 && (pass == 0 || (key >> (shift + width)) == prefix);
+        wave_hist_add(hist, valid, (key >> shift) & ((1u << width) - 1u), w);
+      }
+    } else {
+      for (int j0 = 0; j0 < per_video; j0 += kSelBatch * blockDim.x) {
+        // kSelBatch independent loads per thread, then the (convergent) histogram updates
+        uint32_t key[kSelBatch];
+        unsigned w[kSelBatch];
+#pragma unroll
+        for (int u = 0; u < kSelBatch; ++u) {
+          const int j = j0 + u * blockDim.x + tid;
+          key[u] = j < per_video ? kv[j] : 0u;
+          w[u] = (wv && j < per_video) ? wv[j] : 1u;
+        }
+#pragma unroll
+        for (int u = 0; u < kSelBatch; ++u) {
+          const unsigned ww = key[u] ? w[u] : 0u;
+          const bool valid = ww != 0 && (pass == 0 || (key[u] >> (shift + width)) == prefix);
+          wave_hist_add(hist, valid, (key[u] >> shift) & ((1u << width) - 1u), ww);
+        }
+      }
     }
     __syncthreads();
     // first bin at which the running weight exceeds the budget (2 bins per thread + block scan)
@@ -490,9 +544,24 @@ __global__ __launch_bounds__(1024) void k_budget_select(Geo g, const uint32_t* _
   }
   const unsigned over = s_prefix;  // smallest value at which K exceeds the target
   unsigned lo = 0;                 // key 0 is below every real value
-  for (int j = tid; j < per_video; j += blockDim.x) {
-    const uint32_t key = kv[j];
-    if (key && (!wv || wv[j]) && key < over && key > lo) lo = key;
+  if (EPT > 0) {
+#pragma unroll
+    for (int u = 0; u < NR; ++u)
+      if (rkey[u] && rkey[u] < over && rkey[u] > lo) lo = rkey[u];
+  } else {
+    for (int j0 = 0; j0 < per_video; j0 += kSelBatch * blockDim.x) {
+      uint32_t key[kSelBatch];
+      unsigned w[kSelBatch];
+#pragma unroll
+      for (int u = 0; u < kSelBatch; ++u) {
+        const int j = j0 + u * blockDim.x + tid;
+        key[u] = j < per_video ? kv[j] : 0u;
+        w[u] = (wv && j < per_video) ? wv[j] : 1u;
+      }
+#pragma unroll
+      for (int u = 0; u < kSelBatch; ++u)
+        if (key[u] && w[u] && key[u] < over && key[u] > lo) lo = key[u];
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) lo = max(lo, (unsigned)__shfl_xor((int)lo, o, 64));
@@ -507,20 +576,28 @@ __global__ __launch_bounds__(1024) void k_budget_select(Geo g, const uint32_t* _
   }
 }
 
+static void launch_select(const Geo& g, const uint32_t* keys, const uint8_t* weights, int per_video,
+                          const int* target, int base_const, const int32_t* node_map, float* tau, hipStream_t s) {
+#define STTM_SELECT(EPT)                                                                                      \
+  hipLaunchKernelGGL(k_budget_select<EPT>, dim3(g.B), dim3(1024), 0, s, g, keys, weights, per_video, target, \
+                     base_const, node_map, tau)
+  if (per_video <= 24 * 1024) STTM_SELECT(24);
+  else STTM_SELECT(0);
+#undef STTM_SELECT
+}
+
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
                            float* tau, hipStream_t s) {
   int roots = 0;
   for (int ry = 0; ry < g.R; ++ry)
     for (int rx = 0; rx < g.R; ++rx) roots += node_exists(g, g.L, ry, rx);
   const int per_video = g.T * (g.NN - g.lvl_base[1]);
-  hipLaunchKernelGGL(k_budget_select, dim3(g.B), dim3(1024), 0, s, g, keys, weights, per_video, target,
-                     roots * g.T, (const int32_t*)nullptr, tau);
+  launch_select(g, keys, weights, per_video, target, roots * g.T, nullptr, tau, s);
 }
 
 void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
                             float* tau, hipStream_t s) {
-  hipLaunchKernelGGL(k_budget_select, dim3(g.B), dim3(1024), 0, s, g, keys, (const uint8_t*)nullptr,
-                     g.T * g.HW, target, 0, node_map, tau);
+  launch_select(g, keys, nullptr, g.T * g.HW, target, 0, node_map, tau, s);
 }
 
 }  // namespace sttm

@@ -51,29 +51,46 @@ __device__ inline void block_sum(const typename Row<DT>::Elem* fb, int D, int H,
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_temporal_dots: grid (chunk, frame pair). The two frames' partitions are both quadtree cuts, so any
-// two overlapping nodes are nested. The workgroup lists the "join" blocks (the coarser node of every
-// overlap); a wavefront takes one join block, sums it in the frame where it is a single node, then
-// walks the other frame's nodes inside it in Morton order, summing each and emitting the dot product.
-// Output: pd_part[f][chunk][q] for q = top-left cell of the finer node of each overlapping pair.
+// k_temporal_dots: grid (chunk, frame pair); the one pass over the features of the temporal stage.
+// The two frames' partitions are both quadtree cuts, so any two overlapping nodes are nested; a pair is
+// named by the top-left cell q of its finer node, and its "join" block is the coarser node. Work is
+// listed per workgroup by join level J:
+//  * J <= 1 ("fast"): aligned 2x2 regions in which both frames' nodes are single cells or the 2x2 block.
+//    A wavefront loads the 4+4 cells of two regions at once (16 rows in flight) and emits up to four dot
+//    products per region.
+//  * J == 2 ("mid"): a wavefront sums the 4x4 block in the frame where it is one node, then walks the
+//    other frame's nodes inside it in Morton order, summing each and emitting the dot product.
+//  * J >= 3 ("big"): the coarse sum is not recomputed: the spatial pass left the per-channel sums of all
+//    nodes at levels >= 3 in `nsum`; the workgroup stages the rows it needs in LDS. Pairs whose finer
+//    node is a single cell are handled 8 rows at a time, the others one by one (finer nodes at levels
+//    >= 3 also come from `nsum`).
+// Per-lane partial dot products are reduced across the wavefront through LDS ([scalar][lane] rows).
+// Frame pairs are visited last-to-first: the spatial pass before it reads frames first-to-last, so the
+// tail of the video may still sit in the memory-side cache.
+// Output: pd_part[f][chunk][q].
 // ------------------------------------------------------------------------------------------------
+constexpr int kFastRows = 16;
+
 template <int DT>
 __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __restrict__ feats_v,
-                                                       const int32_t* __restrict__ node_map,
                                                        const uint8_t* __restrict__ node_level,
+                                                       const float* __restrict__ nsum,
                                                        float* __restrict__ pd_part) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
+  STTM_DYNAMIC_LDS(float, bigS);  // [big join blocks][cch]
   __shared__ uint8_t lvl_t[1024], lvl_p[1024];
-  __shared__ int16_t heads[1024];
-  __shared__ int ntask, next;
+  __shared__ int16_t fast[256], mid[64], bighead[16], pairs0[1024], pairsX[512];
+  __shared__ int nfast, nmid, nbig, n0, nX;
+  __shared__ float tbuf[4][kFastRows * 68];
   const int chunk = blockIdx.x;
-  const int pair = blockIdx.y;  // frame pairs of all videos: (b, t) with t >= 1
+  const int pair = gridDim.y - 1 - blockIdx.y;  // frame pairs of all videos: (b, t) with t >= 1
   const int b = pair / (g.T - 1), t = pair - b * (g.T - 1) + 1;
   const int f = b * g.T + t;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int H = g.H, W = g.W, HW = g.HW;
-  if (threadIdx.x == 0) { ntask = 0; next = 0; }
+  const int NB = g.NN - g.lvl_base[3];
+  if (threadIdx.x == 0) { nfast = nmid = nbig = n0 = nX = 0; }
   for (int c = threadIdx.x; c < HW; c += blockDim.x) {
     lvl_t[c] = node_level[(size_t)f * HW + c];
     lvl_p[c] = node_level[(size_t)(f - 1) * HW + c];
@@ -81,9 +98,20 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
   __syncthreads();
   for (int c = threadIdx.x; c < HW; c += blockDim.x) {
     const int a = lvl_t[c], bb = lvl_p[c];
-    const int rep = (a >= bb ? node_map[(size_t)f * HW + c] - f * HW
-                             : node_map[(size_t)(f - 1) * HW + c] - (f - 1) * HW);
-    if (rep == c) heads[atomicAdd(&ntask, 1)] = (int16_t)c;
+    const int J = max(a, bb), lf = min(a, bb);
+    const int y = c / W, x = c - y * W;
+    const bool join_head = !(y & ((1 << J) - 1)) && !(x & ((1 << J) - 1));
+    if (J <= 1) {
+      if (!(y & 1) && !(x & 1)) fast[atomicAdd(&nfast, 1)] = (int16_t)c;
+    } else if (J == 2) {
+      if (join_head) mid[atomicAdd(&nmid, 1)] = (int16_t)c;
+    } else {
+      if (join_head) bighead[atomicAdd(&nbig, 1)] = (int16_t)c;
+      if (!(y & ((1 << lf) - 1)) && !(x & ((1 << lf) - 1))) {  // top-left cell of the finer node
+        if (lf == 0) pairs0[atomicAdd(&n0, 1)] = (int16_t)c;
+        else pairsX[atomicAdd(&nX, 1)] = (int16_t)c;
+      }
+    }
   }
   __syncthreads();
   const int ch0 = chunk * g.cch + lane * VEC;
@@ -92,30 +120,196 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
       reinterpret_cast<const typename R::Elem*>(feats_v) + (size_t)f * HW * g.D + (act ? ch0 : 0);
   const typename R::Elem* fp = ft - (size_t)HW * g.D;
   float* out = pd_part + (size_t)(f * g.nC + chunk) * HW;
-  const int nt = ntask;
-  while (true) {
-    int ti = 0;
-    if (lane == 0) ti = atomicAdd(&next, 1);
-    ti = __shfl(ti, 0, 64);
-    if (ti >= nt) break;
-    const int c = heads[ti];
+  float* tb = tbuf[wave];
+
+  // ---- stage the coarse sums of the big join blocks
+  const int nb = min(nbig, 16);
+  for (int s = 0; s < nb; ++s) {
+    const int c = bighead[s];
+    const int a = lvl_t[c], bb = lvl_p[c];
+    const int J = max(a, bb), y = c / W, x = c - y * W;
+    const int fc = a >= bb ? f : f - 1;  // frame in which the join block is one node
+    const float* row = nsum + ((size_t)fc * NB + node_index(g, J, y >> J, x >> J) - g.lvl_base[3]) * g.D;
+    for (int cc = threadIdx.x; cc < g.cch; cc += blockDim.x) {
+      const int ch = chunk * g.cch + cc;
+      bigS[s * g.cch + cc] = ch < g.D ? row[ch] : 0.f;
+    }
+  }
+  if (nb) __syncthreads();
+
+  // ---- fast regions: four per batch and wavefront, two at a time
+  const int nf = min(nfast, 256);
+  for (int base = wave * 4; base < nf; base += 16) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      typename R::Raw rt[2][4], rp[2][4];
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        const int ri = base + half * 2 + rr;
+        const int c0 = ri < nf ? fast[ri] : -1;
+        const int y0 = c0 / W, x0 = c0 - y0 * W;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int y = y0 + (k >> 1), x = x0 + (k & 1);
+          rt[rr][k] = R::zero();
+          rp[rr][k] = R::zero();
+          if (c0 >= 0 && y < H && x < W && act) {
+            rt[rr][k] = *reinterpret_cast<const typename R::Raw*>(ft + (size_t)(y * W + x) * g.D);
+            rp[rr][k] = *reinterpret_cast<const typename R::Raw*>(fp + (size_t)(y * W + x) * g.D);
+          }
+        }
+      }
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        const int ri = base + half * 2 + rr;
+        const int c0 = ri < nf ? fast[ri] : 0;
+        const bool t_block = lvl_t[c0] == 1, p_block = lvl_p[c0] == 1;  // wave-uniform
+        float xt[4][VEC], xp[4][VEC];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          R::unpack(rt[rr][k], xt[k]);
+          R::unpack(rp[rr][k], xp[k]);
+        }
+        if (t_block) {
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) {
+            const float sum = (xt[0][v] + xt[1][v]) + (xt[2][v] + xt[3][v]);
+            xt[0][v] = xt[1][v] = xt[2][v] = xt[3][v] = sum;
+          }
+        }
+        if (p_block) {
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) {
+            const float sum = (xp[0][v] + xp[1][v]) + (xp[2][v] + xp[3][v]);
+            xp[0][v] = xp[1][v] = xp[2][v] = xp[3][v] = sum;
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          float d = 0.f;
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) d = fmaf(xt[k][v], xp[k][v], d);
+          tb[((half * 2 + rr) * 4 + k) * 68 + lane] = d;
+        }
+      }
+    }
+    wave_lds_fence();
+    if (lane < kFastRows) {
+      const float4* row = reinterpret_cast<const float4*>(tb + lane * 68);
+      float acc = 0.f;
+#pragma unroll
+      for (int jj = 0; jj < 16; ++jj) {
+        const float4 q = row[jj];
+        acc += (q.x + q.y) + (q.z + q.w);
+      }
+      const int ri = base + (lane >> 2), k = lane & 3;
+      if (ri < nf) {
+        const int c0 = fast[ri];
+        const int y = c0 / W + (k >> 1), x = c0 % W + (k & 1);
+        const bool both_block = lvl_t[c0] == 1 && lvl_p[c0] == 1;
+        if (y < H && x < W && (k == 0 || !both_block)) out[y * W + x] = acc;
+      }
+    }
+    wave_lds_fence();
+  }
+
+  // ---- big pairs whose finer node is one cell: sixteen per batch and wavefront, eight rows at a time
+  const int np0 = min(n0, 1024);
+  for (int base = wave * 16; base < np0; base += 64) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      typename R::Raw r[8];
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
+        const int pi = base + half * 8 + jj;
+        r[jj] = R::zero();
+        if (pi < np0 && act) {
+          const int q = pairs0[pi];
+          const typename R::Elem* fine = lvl_t[q] < lvl_p[q] ? ft : fp;
+          r[jj] = *reinterpret_cast<const typename R::Raw*>(fine + (size_t)q * g.D);
+        }
+      }
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
+        const int pi = base + half * 8 + jj;
+        float d = 0.f;
+        if (pi < np0) {
+          const int q = pairs0[pi];
+          const int J = max(lvl_t[q], lvl_p[q]);
+          const int y = q / W, x = q - y * W;
+          const int cM = ((y >> J) << J) * W + ((x >> J) << J);
+          int slot = 0;
+          for (int s = 0; s < nb; ++s) slot = bighead[s] == cM ? s : slot;
+          float xv[VEC];
+          R::unpack(r[jj], xv);
+          const float* sm = bigS + slot * g.cch + lane * VEC;
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) d = fmaf(xv[v], sm[v], d);
+        }
+        tb[(half * 8 + jj) * 68 + lane] = d;
+      }
+    }
+    wave_lds_fence();
+    if (lane < 16) {
+      const float4* row = reinterpret_cast<const float4*>(tb + lane * 68);
+      float acc = 0.f;
+#pragma unroll
+      for (int jj = 0; jj < 16; ++jj) {
+        const float4 q = row[jj];
+        acc += (q.x + q.y) + (q.z + q.w);
+      }
+      if (base + lane < np0) out[pairs0[base + lane]] = acc;
+    }
+    wave_lds_fence();
+  }
+
+  // ---- big pairs with a finer node above the cell level, one at a time
+  const int npx = min(nX, 512);
+  for (int pi = wave; pi < npx; pi += 4) {
+    const int q = pairsX[pi];
+    const int a = lvl_t[q], bb = lvl_p[q];
+    const int J = max(a, bb), lf = min(a, bb);
+    const int y = q / W, x = q - y * W;
+    const int cM = ((y >> J) << J) * W + ((x >> J) << J);
+    int slot = 0;
+    for (int s = 0; s < nb; ++s) slot = bighead[s] == cM ? s : slot;
+    float SB[VEC];
+    if (lf >= 3) {
+      // when the levels are equal the join block is frame t's node (staged), the finer one is frame t-1's
+      const int ff = a < bb ? f : f - 1;
+      const float* row = nsum + ((size_t)ff * NB + node_index(g, lf, y >> lf, x >> lf) - g.lvl_base[3]) * g.D;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) SB[v] = act ? row[ch0 + v] : 0.f;
+    } else {
+      block_sum<DT>(a < bb ? ft : fp, g.D, H, W, y, x, 1 << lf, act, SB);
+    }
+    const float* sm = bigS + slot * g.cch + lane * VEC;
+    float d = 0.f;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) d = fmaf(SB[v], sm[v], d);
+    d = wave_sum(d);
+    if (lane == 0) out[q] = d;
+  }
+
+  // ---- mid join blocks (4x4)
+  const int nm = min(nmid, 64);
+  for (int ti = wave; ti < nm; ti += 4) {
+    const int c = mid[ti];
     const int a = lvl_t[c], bb = lvl_p[c];
     const bool coarse_is_t = a >= bb;
-    const int lM = coarse_is_t ? a : bb;
     const int y0 = c / W, x0 = c - y0 * W;
     float SA[VEC];
-    block_sum<DT>(coarse_is_t ? ft : fp, g.D, H, W, y0, x0, 1 << lM, act, SA);
+    block_sum<DT>(coarse_is_t ? ft : fp, g.D, H, W, y0, x0, 4, act, SA);
     const typename R::Elem* fine = coarse_is_t ? fp : ft;
     const uint8_t* fine_lvl = coarse_is_t ? lvl_p : lvl_t;
-    const int nz = 1 << (2 * lM);
     int z = 0;
-    while (z < nz) {
+    while (z < 16) {
       int dy, dx;
       morton_decode(z, dy, dx);
       const int y = y0 + dy, x = x0 + dx;
       if (y >= H || x >= W) { ++z; continue; }
       const int cb = y * W + x;
-      const int lf = fine_lvl[cb];
+      const int lf = min((int)fine_lvl[cb], 2);
       float SB[VEC];
       block_sum<DT>(fine, g.D, H, W, y, x, 1 << lf, act, SB);
       float d = 0.f;
@@ -126,17 +320,18 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
       z += 1 << (2 * lf);
     }
   }
-  (void)wave;
 }
 
-void launch_temporal_dots(const Geo& g, const void* feats, const int32_t* node_map, const uint8_t* node_level,
+void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
                           float* pd_part, hipStream_t s) {
   if (g.T < 2) return;
   dim3 grid(g.nC, g.B * (g.T - 1)), block(256);
+  const int U = g.P >= 8 ? g.P >> 3 : 1;
+  const size_t lds = g.L >= 3 ? (size_t)U * U * g.cch * sizeof(float) : 0;
   if (g.dtype == 1)
-    hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, 0, s, g, feats, node_map, node_level, pd_part);
+    hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, lds, s, g, feats, node_level, nsum, pd_part);
   else
-    hipLaunchKernelGGL(k_temporal_dots<0>, grid, block, 0, s, g, feats, node_map, node_level, pd_part);
+    hipLaunchKernelGGL(k_temporal_dots<0>, grid, block, lds, s, g, feats, node_level, nsum, pd_part);
 }
 
 __device__ inline int node_idx_of(const Geo& g, int lvl, int y0, int x0) {
@@ -260,12 +455,18 @@ void launch_temporal_parent(const Geo& g, const int32_t* node_map, const uint8_t
 
 // ------------------------------------------------------------------------------------------------
 // Common root by pointer jumping (Sec. 3.3, "union-find in a vectorized form"): every edge points one
-// frame back, so ceil(log2 T) doublings reach the root.
+// frame back, so a chain has at most T-1 edges; each launch multiplies the reach by kHops.
 // ------------------------------------------------------------------------------------------------
+// One launch follows kHops edges of the previous array, i.e. multiplies the reach by kHops.
+constexpr int kHops = 8;
 __global__ __launch_bounds__(256) void k_root_jump(int n, const int32_t* __restrict__ src,
                                                    int32_t* __restrict__ dst) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = src[src[i]];
+  if (i >= n) return;
+  int p = i;
+#pragma unroll
+  for (int h = 0; h < kHops; ++h) p = src[p];
+  dst[i] = p;
 }
 
 __global__ __launch_bounds__(256) void k_cluster_ids(int n, const int32_t* __restrict__ root,
@@ -278,7 +479,7 @@ __global__ __launch_bounds__(256) void k_cluster_ids(int n, const int32_t* __res
 void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* node_map, int32_t* cluster_ids,
                   hipStream_t s) {
   int rounds = 0;
-  while ((1 << rounds) < g.T) ++rounds;
+  for (long long reach = 1; reach < g.T; reach *= kHops) ++rounds;
   dim3 grid((g.N + 255) / 256), block(256);
   int32_t* src = ptr_a;
   int32_t* dst = ptr_b;

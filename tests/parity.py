@@ -28,6 +28,15 @@ class GpuResult:
     pass
 
 
+def _trace(msg):
+    """STTM_TRACE=1: synchronise and name every stage as it completes, so a hang or fault names its stage."""
+    import os
+    if os.environ.get("STTM_TRACE"):
+        import torch
+        torch.cuda.synchronize()
+        print(f"    [trace] {msg} done", flush=True)
+
+
 def _to_dev(feats: np.ndarray):
     import torch
     if feats.dtype == np.uint16:
@@ -56,10 +65,13 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     r.tau_s = r.tau_t = None
     if tau_s is None:
         s.sttm_spatial_stats(x, dt, B, T, H, W, D, root_grid)
+        _trace("spatial statistics")
         r.tau_s = s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, keep)
+        _trace("spatial budget")
         s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, root_grid, None, node_map, node_level)
     else:
         s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, root_grid, tau_s, node_map, node_level)
+    _trace("spatial stage")
     tbl = torch.empty(B * T * NN, dtype=torch.float32, device=dev)
     s.sttm_export(lib.STTM_TBL_CHILD_SIM, tbl)
     r.child_sim = tbl.cpu().numpy().reshape(B * T, NN)
@@ -72,10 +84,13 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
         node_level.copy_(torch.from_numpy(node_map_override[1].reshape(-1)).cuda())
     if tau_t is None:
         s.sttm_temporal_stats(x, node_map, node_level)
+        _trace("temporal statistics")
         r.tau_t = s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, keep)
+        _trace("temporal budget")
         s.sttm_temporal_merge(x, node_map, node_level, None, cluster)
     else:
         s.sttm_temporal_merge(x, node_map, node_level, tau_t, cluster)
+    _trace("temporal stage")
     t32 = torch.empty(N, dtype=torch.float32, device=dev)
     s.sttm_export(lib.STTM_TBL_PAIR_SIM, t32)
     r.pair_sim = t32.cpu().numpy()
@@ -91,6 +106,7 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     out_ids = torch.zeros(N, dtype=torch.int32, device=dev)
     offsets = torch.zeros(B + 1, dtype=torch.int64, device=dev)
     K = s.sttm_reduce(x, cluster, out_dtype, N, merged, counts, out_ids, offsets)
+    _trace("reduce stage")
     r.K = K
     r.merged = merged[:K].float().cpu().numpy()
     r.counts = counts[:K].cpu().numpy()
