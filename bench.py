@@ -33,7 +33,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="index into the workload table (default: long video)")
     ap.add_argument("--keep", type=float, default=None, help="token budget (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=192, help="frames of the workload the oracle is timed on")
+    ap.add_argument("--cpu-frames", type=int, default=512, help="frames of the workload the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path's sharding is described in DESIGN.md); "
