@@ -17,7 +17,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
+  size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_state, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
   size_t rank, blocksum, key_a, val_a, key_b, val_b, hist, seg, kdev, bigpart;
   size_t total;
 };
@@ -66,6 +66,7 @@ Layout make_layout(const Geo& g) {
   l.tau_t = take(g.B * sizeof(float));
   l.target_s = take(g.B * sizeof(int));
   l.target_t = take(g.B * sizeof(int));
+  l.sel_state = take(select_state_bytes(g.B));
   l.lvl = take(N);
   l.pd_part = take(F * g.nC * g.HW * sizeof(float));
   l.sig = take(N * sizeof(float));
@@ -408,10 +409,10 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
   float* tau_dev = at<float>(ctx, stage == STTM_STAGE_SPATIAL ? ctx->lay.tau_s : ctx->lay.tau_t);
   if (stage == STTM_STAGE_SPATIAL)
     launch_select_spatial(g, at<uint32_t>(ctx, ctx->lay.sel_key_s), at<uint8_t>(ctx, ctx->lay.sel_w_s),
-                          target_dev, tau_dev, ctx->stream);
+                          target_dev, at<char>(ctx, ctx->lay.sel_state), tau_dev, ctx->stream);
   else
-    launch_select_temporal(g, ctx->node_map_temporal, at<uint32_t>(ctx, ctx->lay.sel_key_t), target_dev, tau_dev,
-                           ctx->stream);
+    launch_select_temporal(g, ctx->node_map_temporal, at<uint32_t>(ctx, ctx->lay.sel_key_t), target_dev,
+                           at<char>(ctx, ctx->lay.sel_state), tau_dev, ctx->stream);
   rc = after_launch(ctx);
   if (rc) return rc;
   if (stage == STTM_STAGE_SPATIAL) ctx->have_tau_s = true; else ctx->have_tau_t = true;

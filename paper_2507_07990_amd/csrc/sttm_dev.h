@@ -121,9 +121,10 @@ void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float
 void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
                            uint8_t* node_level, hipStream_t s);
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
-                           float* tau, hipStream_t s);
+                           void* state, float* tau, hipStream_t s);
 void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
-                            float* tau, hipStream_t s);
+                            void* state, float* tau, hipStream_t s);
+size_t select_state_bytes(int B);
 void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
                           float* pd_part, hipStream_t s);
 // fp32 sums of the pyramid nodes at levels >= 3: [F][nsum_nodes][D]

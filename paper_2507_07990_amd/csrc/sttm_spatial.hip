@@ -412,7 +412,8 @@ void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_lev
 // Input: keys[video][per_video] (0 = not an element), weights (NULL = 1 for every element).
 // ------------------------------------------------------------------------------------------------
 constexpr int kSelBins = 2048;
-constexpr int kSelBatch = 24;
+constexpr int kSelPer = 8;   // elements per thread and pass
+constexpr int kSelThreads = 256;
 
 // Adds w to hist[digit] for the lanes with valid set. The two most frequent leading digits of the wavefront
 // are combined before the atomic (real similarities sit in tight clusters, which would otherwise serialise
@@ -431,173 +432,206 @@ __device__ inline void wave_hist_add(unsigned* hist, bool valid, unsigned digit,
   if ((todo >> (threadIdx.x & 63)) & 1ull) atomicAdd(&hist[digit], w);
 }
 
-// EPT > 0: every thread keeps its EPT elements in registers (one round of loads, then four passes without
-// touching memory); EPT == 0: elements are streamed from memory in every pass (any size).
-template <int EPT>
-__global__ __launch_bounds__(1024) void k_budget_select(Geo g, const uint32_t* __restrict__ keys,
-                                                        const uint8_t* __restrict__ weights, int per_video,
-                                                        const int* __restrict__ target, int base_const,
-                                                        const int32_t* __restrict__ node_map,
-                                                        float* __restrict__ tau) {
-  __shared__ unsigned hist[kSelBins];
-  __shared__ unsigned wsum[16];
-  __shared__ unsigned s_prefix, s_acc, s_lo;
-  __shared__ int s_found, s_base;
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const uint32_t* kv = keys + (size_t)b * per_video;
-  const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
-  constexpr int NR = EPT > 0 ? EPT : 1;
-  uint32_t rkey[NR];          // key, 0 = no element
-  uint32_t rw[(NR + 15) / 16]; // 2-bit weights
-  if (EPT > 0) {
+// Per-video state of one search in global memory: three pass histograms and the largest key below the result.
+struct SelState {
+  unsigned hist[3][kSelBins];
+  unsigned lo;
+  unsigned pad[3];
+};
+
+__device__ inline int sel_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ inline int sel_width(int pass) { return pass == 2 ? 10 : 11; }
+
+// Workgroup-wide (256 threads): the first bin of `hist` at which acc + running weight exceeds `budget`.
+// Returns false when the whole histogram fits. All threads get the same answer.
+__device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long long acc,
+                                unsigned long long budget, unsigned* digit, unsigned long long* acc_out) {
+  __shared__ unsigned long long wsum[kSelThreads / 64];
+  __shared__ unsigned s_digit;
+  __shared__ unsigned long long s_acc;
+  __shared__ int s_found;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned h[kSelBins / kSelThreads];
+  unsigned long long tot = 0;
 #pragma unroll
-    for (int u = 0; u < (NR + 15) / 16; ++u) rw[u] = 0;
-#pragma unroll
-    for (int u = 0; u < NR; ++u) {
-      const int j = u * 1024 + tid;
-      uint32_t k = j < per_video ? kv[j] : 0u;
-      unsigned w = 1u;
-      if (wv) w = j < per_video ? wv[j] : 0u;
-      if (w == 0) k = 0;
-      rkey[u] = k;
-      rw[u / 16] |= (w & 3u) << (2 * (u % 16));
-    }
+  for (int j = 0; j < kSelBins / kSelThreads; ++j) {
+    h[j] = hist[tid * (kSelBins / kSelThreads) + j];
+    tot += h[j];
   }
-  if (tid == 0) { s_prefix = 0; s_acc = 0; s_lo = 0; s_base = 0; }
+  unsigned long long inc = tot;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (tid == 0) s_found = 0;
+  if (lane == 63) wsum[wave] = inc;
   __syncthreads();
-  int base = base_const;
-  if (node_map) {  // temporal flavour: base = kept nodes of the video's first frame
-    int c = 0;
-    for (int j = tid; j < g.HW; j += blockDim.x) {
-      const int i = b * g.T * g.HW + j;
-      c += (node_map[i] == i);
+  unsigned long long ex = acc + inc - tot;
+  for (int w = 0; w < wave; ++w) ex += wsum[w];
+#pragma unroll
+  for (int j = 0; j < kSelBins / kSelThreads; ++j) {
+    if (ex <= budget && ex + h[j] > budget) {
+      s_found = 1;
+      s_digit = (unsigned)(tid * (kSelBins / kSelThreads) + j);
+      s_acc = ex;
     }
-    atomicAdd(&s_base, c);
-    __syncthreads();
-    base = s_base;
+    ex += h[j];
   }
-  const long long budget = (long long)target[b] - base;
-  if (budget < 0) {
-    if (tid == 0) tau[b] = -2.f;
-    return;
-  }
-  const int shifts[3] = {21, 10, 0};
-  const int widths[3] = {11, 11, 10};
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = shifts[pass], width = widths[pass];
-    for (int j = tid; j < kSelBins; j += blockDim.x) hist[j] = 0;
-    if (tid == 0) s_found = 0;
-    __syncthreads();
-    const unsigned prefix = s_prefix, acc0 = s_acc;
-    if (EPT > 0) {
-#pragma unroll
-      for (int u = 0; u < NR; ++u) {
-        const uint32_t key = rkey[u];
-        const unsigned w = (rw[u / 16] >> (2 * (u % 16))) & 3u;
-        const bool valid = key != 0 && (pass == 0 || (key >> (shift + width)) == prefix);
-        wave_hist_add(hist, valid, (key >> shift) & ((1u << width) - 1u), w);
-      }
-    } else {
-      for (int j0 = 0; j0 < per_video; j0 += kSelBatch * blockDim.x) {
-        // kSelBatch independent loads per thread, then the (convergent) histogram updates
-        uint32_t key[kSelBatch];
-        unsigned w[kSelBatch];
-#pragma unroll
-        for (int u = 0; u < kSelBatch; ++u) {
-          const int j = j0 + u * blockDim.x + tid;
-          key[u] = j < per_video ? kv[j] : 0u;
-          w[u] = (wv && j < per_video) ? wv[j] : 1u;
-        }
-#pragma unroll
-        for (int u = 0; u < kSelBatch; ++u) {
-          const unsigned ww = key[u] ? w[u] : 0u;
-          const bool valid = ww != 0 && (pass == 0 || (key[u] >> (shift + width)) == prefix);
-          wave_hist_add(hist, valid, (key[u] >> shift) & ((1u << width) - 1u), ww);
-        }
-      }
-    }
-    __syncthreads();
-    // first bin at which the running weight exceeds the budget (2 bins per thread + block scan)
-    const unsigned h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
-    unsigned inc = h0 + h1;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const unsigned t = __shfl_up(inc, o, 64);
-      if (lane >= o) inc += t;
-    }
-    if (lane == 63) wsum[wave] = inc;
-    __syncthreads();
-    unsigned long long ex = acc0;
-    for (int w = 0; w < wave; ++w) ex += wsum[w];
-    ex += inc - (h0 + h1);
-    const unsigned long long bud = (unsigned long long)budget;
-    if (ex <= bud && ex + h0 > bud) {
-      s_found = 1; s_prefix = (prefix << width) | (unsigned)(2 * tid); s_acc = (unsigned)ex;
-    } else if (ex + h0 <= bud && ex + h0 + h1 > bud) {
-      s_found = 1; s_prefix = (prefix << width) | (unsigned)(2 * tid + 1); s_acc = (unsigned)(ex + h0);
-    }
-    __syncthreads();
-    if (!s_found) {  // only possible in the first pass: the whole weight fits
-      if (tid == 0) tau[b] = 1.f;
-      return;
-    }
-  }
-  const unsigned over = s_prefix;  // smallest value at which K exceeds the target
-  unsigned lo = 0;                 // key 0 is below every real value
-  if (EPT > 0) {
-#pragma unroll
-    for (int u = 0; u < NR; ++u)
-      if (rkey[u] && rkey[u] < over && rkey[u] > lo) lo = rkey[u];
-  } else {
-    for (int j0 = 0; j0 < per_video; j0 += kSelBatch * blockDim.x) {
-      uint32_t key[kSelBatch];
-      unsigned w[kSelBatch];
-#pragma unroll
-      for (int u = 0; u < kSelBatch; ++u) {
-        const int j = j0 + u * blockDim.x + tid;
-        key[u] = j < per_video ? kv[j] : 0u;
-        w[u] = (wv && j < per_video) ? wv[j] : 1u;
-      }
-#pragma unroll
-      for (int u = 0; u < kSelBatch; ++u)
-        if (key[u] && w[u] && key[u] < over && key[u] > lo) lo = key[u];
-    }
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) lo = max(lo, (unsigned)__shfl_xor((int)lo, o, 64));
-  if (lane == 0) atomicMax(&s_lo, lo);
   __syncthreads();
-  if (tid == 0) {
-    const float hi = key_float(over);
-    const float lof = s_lo ? key_float(s_lo) : -2.f;
-    float mid = 0.5f * (lof + hi);
-    if (!(mid < hi)) mid = lof;
-    tau[b] = mid;
-  }
+  const bool found = s_found != 0;
+  *digit = s_digit;
+  *acc_out = s_acc;
+  __syncthreads();
+  return found;
 }
 
+// base of the step function: spatial = constant (roots * T), temporal = kept nodes of the video's first frame
+__device__ inline int sel_base(const Geo& g, int b, int base_const, const int32_t* node_map) {
+  if (!node_map) return base_const;
+  __shared__ int s_base;
+  if (threadIdx.x == 0) s_base = 0;
+  __syncthreads();
+  int c = 0;
+  for (int j = threadIdx.x; j < g.HW; j += blockDim.x) {
+    const int i = b * g.T * g.HW + j;
+    c += (node_map[i] == i);
+  }
+  if (c) atomicAdd(&s_base, c);
+  __syncthreads();
+  const int r = s_base;
+  __syncthreads();
+  return r;
+}
+
+// Resolves the passes before `upto`: prefix of the searched key and the weight below it.
+// Returns 0 = fine, 1 = everything fits (tau = 1), 2 = even the base exceeds the target (tau = -2).
+__device__ inline int sel_resolve(const Geo& g, const SelState* st, int b, int upto, const int* target,
+                                  int base_const, const int32_t* node_map, unsigned* prefix,
+                                  unsigned long long* budget_out) {
+  const long long budget = (long long)target[b] - sel_base(g, b, base_const, node_map);
+  *prefix = 0;
+  *budget_out = 0;
+  if (budget < 0) return 2;
+  *budget_out = (unsigned long long)budget;
+  unsigned long long acc = 0;
+  for (int p = 0; p < upto; ++p) {
+    unsigned d;
+    unsigned long long a2;
+    if (!sel_pick(st[b].hist[p], acc, (unsigned long long)budget, &d, &a2)) return 1;
+    *prefix = (*prefix << sel_width(p)) | d;
+    acc = a2;
+  }
+  return 0;
+}
+
+__global__ __launch_bounds__(256) void k_select_clear(SelState* st) {
+  unsigned* p = reinterpret_cast<unsigned*>(st + blockIdx.x);
+  for (int j = threadIdx.x; j < (int)(sizeof(SelState) / 4); j += blockDim.x) p[j] = 0;
+}
+
+// One pass: grid (slices, videos). Every workgroup re-derives the prefix found by the earlier passes from
+// their (complete) histograms, bins its slice in LDS and adds the non-empty bins to the video's histogram.
+// PASS == 3: instead of binning, the largest key below the searched one is collected.
+template <int PASS>
+__global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32_t* __restrict__ keys,
+                                                             const uint8_t* __restrict__ weights, int per_video,
+                                                             const int* __restrict__ target, int base_const,
+                                                             const int32_t* __restrict__ node_map,
+                                                             SelState* __restrict__ st) {
+  __shared__ unsigned hist[kSelBins];
+  const int b = blockIdx.y, tid = threadIdx.x;
+  unsigned prefix;
+  unsigned long long budget;
+  if (sel_resolve(g, st, b, PASS < 3 ? PASS : 3, target, base_const, node_map, &prefix, &budget) != 0) return;
+  const uint32_t* kv = keys + (size_t)b * per_video;
+  const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
+  const int j0 = blockIdx.x * (kSelThreads * kSelPer);
+  uint32_t key[kSelPer];
+  unsigned w[kSelPer];
+#pragma unroll
+  for (int u = 0; u < kSelPer; ++u) {
+    const int j = j0 + u * kSelThreads + tid;
+    key[u] = j < per_video ? kv[j] : 0u;
+    w[u] = 1u;
+    if (wv) w[u] = j < per_video ? wv[j] : 0u;
+    if (w[u] == 0) key[u] = 0;
+  }
+  if (PASS == 3) {
+    unsigned lo = 0;  // key 0 is below every real value
+#pragma unroll
+    for (int u = 0; u < kSelPer; ++u)
+      if (key[u] && key[u] < prefix && key[u] > lo) lo = key[u];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lo = max(lo, (unsigned)__shfl_xor((int)lo, o, 64));
+    if ((tid & 63) == 0 && lo) atomicMax(&st[b].lo, lo);
+    return;
+  }
+  constexpr int P = PASS < 3 ? PASS : 0;
+  const int shift = sel_shift(P), width = sel_width(P);
+  for (int j = tid; j < kSelBins; j += kSelThreads) hist[j] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kSelPer; ++u) {
+    const bool valid = key[u] != 0 && (P == 0 || (key[u] >> (shift + width)) == prefix);
+    wave_hist_add(hist, valid, (key[u] >> shift) & ((1u << width) - 1u), w[u]);
+  }
+  __syncthreads();
+  for (int j = tid; j < kSelBins; j += kSelThreads)
+    if (hist[j]) atomicAdd(&st[b].hist[P][j], hist[j]);
+}
+
+// tau = midpoint between the searched key and the largest key below it.
+__global__ __launch_bounds__(kSelThreads) void k_select_tau(Geo g, const int* __restrict__ target, int base_const,
+                                                            const int32_t* __restrict__ node_map,
+                                                            const SelState* __restrict__ st,
+                                                            float* __restrict__ tau) {
+  const int b = blockIdx.x;
+  unsigned over;
+  unsigned long long budget;
+  const int rc = sel_resolve(g, st, b, 3, target, base_const, node_map, &over, &budget);
+  if (threadIdx.x != 0) return;
+  if (rc == 2) { tau[b] = -2.f; return; }
+  if (rc == 1) { tau[b] = 1.f; return; }
+  const float hi = key_float(over);
+  const float lof = st[b].lo ? key_float(st[b].lo) : -2.f;
+  float mid = 0.5f * (lof + hi);
+  if (!(mid < hi)) mid = lof;
+  tau[b] = mid;
+}
+
+size_t select_state_bytes(int B) { return (size_t)B * sizeof(SelState); }
+
 static void launch_select(const Geo& g, const uint32_t* keys, const uint8_t* weights, int per_video,
-                          const int* target, int base_const, const int32_t* node_map, float* tau, hipStream_t s) {
-#define STTM_SELECT(EPT)                                                                                      \
-  hipLaunchKernelGGL(k_budget_select<EPT>, dim3(g.B), dim3(1024), 0, s, g, keys, weights, per_video, target, \
-                     base_const, node_map, tau)
-  if (per_video <= 24 * 1024) STTM_SELECT(24);
-  else STTM_SELECT(0);
-#undef STTM_SELECT
+                          const int* target, int base_const, const int32_t* node_map, void* state, float* tau,
+                          hipStream_t s) {
+  SelState* st = static_cast<SelState*>(state);
+  const int slices = (per_video + kSelThreads * kSelPer - 1) / (kSelThreads * kSelPer);
+  const dim3 grid(slices, g.B), block(kSelThreads);
+  hipLaunchKernelGGL(k_select_clear, dim3(g.B), block, 0, s, st);
+  hipLaunchKernelGGL(k_select_pass<0>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
+                     node_map, st);
+  hipLaunchKernelGGL(k_select_pass<1>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
+                     node_map, st);
+  hipLaunchKernelGGL(k_select_pass<2>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
+                     node_map, st);
+  hipLaunchKernelGGL(k_select_pass<3>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
+                     node_map, st);
+  hipLaunchKernelGGL(k_select_tau, dim3(g.B), block, 0, s, g, target, base_const, node_map, st, tau);
 }
 
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
-                           float* tau, hipStream_t s) {
+                           void* state, float* tau, hipStream_t s) {
   int roots = 0;
   for (int ry = 0; ry < g.R; ++ry)
     for (int rx = 0; rx < g.R; ++rx) roots += node_exists(g, g.L, ry, rx);
   const int per_video = g.T * (g.NN - g.lvl_base[1]);
-  launch_select(g, keys, weights, per_video, target, roots * g.T, nullptr, tau, s);
+  launch_select(g, keys, weights, per_video, target, roots * g.T, nullptr, state, tau, s);
 }
 
 void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
-                            float* tau, hipStream_t s) {
-  launch_select(g, keys, nullptr, g.T * g.HW, target, 0, node_map, tau, s);
+                            void* state, float* tau, hipStream_t s) {
+  launch_select(g, keys, nullptr, g.T * g.HW, target, 0, node_map, state, tau, s);
 }
 
 }  // namespace sttm
