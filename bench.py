@@ -34,6 +34,10 @@ def main() -> int:
     ap.add_argument("--keep", type=float, default=None, help="token budget (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=512, help="frames of the workload the oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed steps, run one plain device-to-device copy of the input tensor "
+                         "(known size: reads and writes N*D*esz bytes) so that a counter run can scale "
+                         "FETCH_SIZE / WRITE_SIZE by what they read for it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path's sharding is described in DESIGN.md); "
@@ -97,6 +101,9 @@ def main() -> int:
                                                lib.STTM_KERNEL_REDUCE_GATHER)}
     s.sttm_profile_enable(False)
     ms_per_step = elapsed / args.steps * 1e3
+    if args.calibrate_copy:
+        merged.view(-1)[:x.numel()].copy_(x.view(-1))
+        torch.cuda.synchronize()
     K = int(offsets[B].item())
     assert int(counts[:K].sum().item()) == N, "member counts do not add up to the number of input tokens"
     rho = K / N
