@@ -34,6 +34,8 @@ def main() -> int:
     ap.add_argument("--keep", type=float, default=None, help="token budget (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=512, help="frames of the workload the oracle is timed on")
+    ap.add_argument("--no-node-sums", action="store_true",
+                    help="reduce stage without the stage-1 partition: every cell is read again")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed steps, run one plain device-to-device copy of the input tensor "
                          "(known size: reads and writes N*D*esz bytes) so that a counter run can scale "
@@ -86,7 +88,8 @@ def main() -> int:
         else:
             s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, 1, [cfg.tau_s], node_map, node_level)
             s.sttm_temporal_merge(x, node_map, node_level, [cfg.tau_t], cluster)
-        s.sttm_reduce(x, cluster, dt, N, merged, counts, out_ids, offsets, want_n=False)
+        s.sttm_reduce(x, cluster, None if args.no_node_sums else node_map,
+                      None if args.no_node_sums else node_level, dt, N, merged, counts, out_ids, offsets, want_n=False)
 
     for _ in range(args.warmup):
         step()

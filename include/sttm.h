@@ -136,14 +136,20 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
 /* ---- stage 3: gather / average (Sec. 3.1, 3.3, 3.4) ---------------------------------------------------- */
 
 /* One output row per cluster, in ascending cluster id: merged [capacity, D] of out_dtype = mean of the member
- * cells' features (fp32 accumulation, members in ascending flat index); counts int32 [capacity] = members;
- * out_ids int32 [capacity] = cluster id; offsets int64 [B+1] = first row of each video, offsets[B] = K (all device,
- * counts/out_ids may be NULL). Rows beyond capacity are not written. n_out: host pointer or NULL; when non-NULL
- * the stream is synchronised, *n_out = K and STTM_ERR_CAPACITY is returned if K > capacity. Uses the shape bound by
- * stage 1; cluster_ids may be any labelling in which a cluster's id is its smallest member's flat index. */
-int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids_dev, int out_dtype,
-                int64_t capacity, void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev,
-                int64_t* offsets_dev, int64_t* n_out_host);
+ * cells' features (fp32 accumulation in a fixed order); counts int32 [capacity] = members; out_ids int32 [capacity]
+ * = cluster id; offsets int64 [B+1] = first row of each video, offsets[B] = K (all device, counts/out_ids may be
+ * NULL). Rows beyond capacity are not written. n_out: host pointer or NULL; when non-NULL the stream is
+ * synchronised, *n_out = K and STTM_ERR_CAPACITY is returned if K > capacity. Uses the shape bound by stage 1;
+ * cluster_ids may be any labelling in which a cluster's id is its smallest member's flat index.
+ * node_map / node_level (device, both or neither): the stage-1 partition the cluster ids were built on, as
+ * sttm_temporal_merge received it -- all cells of a node must carry the same cluster id, and the workspace must
+ * still hold the stage-1 statistics of these (unchanged) feats (STTM_ERR_STATE otherwise). Nodes at level >= 3 are
+ * then added from the per-node sums stage 1 left in the workspace instead of being read again cell by cell; the
+ * result differs from the NULL call only in the order of the fp32 additions. */
+int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids_dev,
+                const int32_t* node_map_dev, const uint8_t* node_level_dev, int out_dtype, int64_t capacity,
+                void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev, int64_t* offsets_dev,
+                int64_t* n_out_host);
 
 /* ---- inspection ---------------------------------------------------------------------------------------- */
 

@@ -54,7 +54,7 @@ def _load() -> C.CDLL:
     lib.sttm_temporal_stats.argtypes = [vp, vp, vp, vp]
     lib.sttm_temporal_merge.argtypes = [vp, vp, vp, vp, C.POINTER(C.c_float), vp]
     lib.sttm_budget_threshold.argtypes = [vp, i, C.POINTER(C.c_double), C.POINTER(C.c_float)]
-    lib.sttm_reduce.argtypes = [vp, vp, vp, i, i64, vp, vp, vp, vp, C.POINTER(i64)]
+    lib.sttm_reduce.argtypes = [vp, vp, vp, vp, vp, i, i64, vp, vp, vp, vp, C.POINTER(i64)]
     lib.sttm_export.argtypes = [vp, i, vp, sz]
     lib.sttm_profile_enable.argtypes = [vp, i]
     lib.sttm_profile_read.argtypes = [vp, i, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -162,10 +162,12 @@ class Sttm:
         self._check(_lib.sttm_budget_threshold(self._h, stage, karr, out))
         return np.array(list(out), dtype=np.float32) if want_tau else None
 
-    def sttm_reduce(self, feats, cluster_ids, out_dtype, capacity, merged, counts, out_ids, offsets, want_n=True):
+    def sttm_reduce(self, feats, cluster_ids, node_map, node_level, out_dtype, capacity, merged, counts, out_ids,
+                    offsets, want_n=True):
         n = C.c_int64(-1)
-        rc = _lib.sttm_reduce(self._h, _ptr(feats), _ptr(cluster_ids), out_dtype, capacity, _ptr(merged),
-                              _ptr(counts), _ptr(out_ids), _ptr(offsets), C.byref(n) if want_n else None)
+        rc = _lib.sttm_reduce(self._h, _ptr(feats), _ptr(cluster_ids), _ptr(node_map), _ptr(node_level), out_dtype,
+                              capacity, _ptr(merged), _ptr(counts), _ptr(out_ids), _ptr(offsets),
+                              C.byref(n) if want_n else None)
         self._check(rc)
         return int(n.value) if want_n else None
 

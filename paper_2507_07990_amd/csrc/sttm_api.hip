@@ -17,8 +17,10 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_state, lvl, pd_part, sig, e, parent, ptr_a, ptr_b;
-  size_t rank, blocksum, key_a, val_a, key_b, val_b, hist, seg, kdev, bigpart;
+  size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_s, sel_t, lvl,
+      pd_part, sig, e, parent, ptr_a, ptr_b;
+  size_t rank, key_a, val_a, key_b, val_b, order, orow, hist, tot, tile_roots, tile_live, seg, kdev,
+      bigpart, bigw;
   size_t total;
 };
 
@@ -66,7 +68,8 @@ Layout make_layout(const Geo& g) {
   l.tau_t = take(g.B * sizeof(float));
   l.target_s = take(g.B * sizeof(int));
   l.target_t = take(g.B * sizeof(int));
-  l.sel_state = take(select_state_bytes(g.B));
+  l.sel_s = take(select_state_bytes(g.B));
+  l.sel_t = take(select_state_bytes(g.B));
   l.lvl = take(N);
   l.pd_part = take(F * g.nC * g.HW * sizeof(float));
   l.sig = take(N * sizeof(float));
@@ -75,17 +78,20 @@ Layout make_layout(const Geo& g) {
   l.ptr_a = take(N * sizeof(int32_t));
   l.ptr_b = take(N * sizeof(int32_t));
   l.rank = take(N * sizeof(int32_t));
-  const size_t hist = reduce_hist_entries(g.N);
-  size_t sb = scan_blocks(g.N), sb2 = scan_blocks((int)hist);
-  l.blocksum = take((sb > sb2 ? sb : sb2) * sizeof(int32_t));
   l.key_a = take(N * sizeof(int32_t));
   l.val_a = take(N * sizeof(int32_t));
   l.key_b = take(N * sizeof(int32_t));
   l.val_b = take(N * sizeof(int32_t));
-  l.hist = take(hist * sizeof(int32_t));
+  l.order = take(N * sizeof(int32_t));
+  l.orow = take(N * sizeof(int32_t));
+  l.hist = take(reduce_hist_entries(g.N) * sizeof(int32_t));
+  l.tot = take(2048 * sizeof(int32_t));
+  l.tile_roots = take(reduce_tiles(g.N) * sizeof(int32_t));
+  l.tile_live = take(reduce_tiles(g.N) * sizeof(int32_t));
   l.seg = take((N + 1) * sizeof(int32_t));
-  l.kdev = take(sizeof(int32_t));
+  l.kdev = take(2 * sizeof(int32_t));
   l.bigpart = take(reduce_bigpart_floats(g) * sizeof(float));
+  l.bigw = take(reduce_bigw_entries(g) * sizeof(int32_t));
   l.total = off;
   return l;
 }
@@ -105,6 +111,8 @@ struct sttm_ctx {
   const int32_t* node_map_temporal = nullptr;  // caller's node map of the last temporal statistics pass
   std::vector<float> h_tau_s, h_tau_t;         // host staging that outlives the asynchronous uploads
   std::vector<int> h_target_s, h_target_t;
+  bool target_s_on_device = false, target_t_on_device = false;  // the device copy equals the host staging
+  bool sel_s_dirty = false, sel_t_dirty = false;                // searched since the statistics pass
   std::string err;
   // optional per-kernel timing of the three feature passes (HIP events on the context's stream)
   bool profiling = false;
@@ -136,6 +144,7 @@ template <class T> T* at(sttm_ctx* c, size_t off) { return reinterpret_cast<T*>(
 int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int root_grid) {
   if (dtype != STTM_F32 && dtype != STTM_BF16) return fail(c, STTM_ERR_DTYPE, "dtype must be STTM_F32 or STTM_BF16");
   Geo g;
+  std::memset(&g, 0, sizeof g);
   if (!make_geo(B, T, H, W, D, dtype, root_grid, &g))
     return fail(c, STTM_ERR_SHAPE,
                 "need B,T >= 1, B*T <= 65535, 1 <= H,W <= 32, D % 8 == 0, B*T*H*W < 2^31, root_grid a power of two <= P");
@@ -146,10 +155,12 @@ int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int ro
     snprintf(buf, sizeof buf, "workspace too small: have %zu bytes, need %zu", c->ws_bytes, l.total);
     return fail(c, STTM_ERR_WORKSPACE, buf);
   }
+  const bool same = c->bound && std::memcmp(&c->g, &g, sizeof g) == 0;
   c->g = g;
   c->lay = l;
   c->bound = true;
   c->have_spatial = c->have_tau_s = c->have_temporal = c->have_tau_t = false;
+  if (!same) c->target_s_on_device = c->target_t_on_device = false;  // the layout moved: upload targets again
   return STTM_OK;
 }
 
@@ -190,13 +201,15 @@ int after_launch(sttm_ctx* c) { return hip_check(c, hipGetLastError(), "kernel l
 int run_spatial_stats(sttm_ctx* c, const void* feats) {
   {
     Timed t(c, STTM_KERNEL_PYRAMID_STATS);
-    launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum), c->stream);
+    launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum),
+                         at<SelState>(c, c->lay.sel_s), c->stream);
   }
   launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nrm2), at<float>(c, c->lay.sim),
                           at<float>(c, c->lay.m), at<uint32_t>(c, c->lay.sel_key_s), at<uint8_t>(c, c->lay.sel_w_s),
-                          c->stream);
+                          at<SelState>(c, c->lay.sel_s), c->stream);
   int rc = after_launch(c);
   if (rc == STTM_OK) {
+    c->sel_s_dirty = false;
     c->have_spatial = true;
     c->have_temporal = false;
     c->feats_spatial = feats;
@@ -208,13 +221,14 @@ int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, 
   {
     Timed t(c, STTM_KERNEL_TEMPORAL_DOTS);
     launch_temporal_dots(c->g, feats, node_level, at<float>(c, c->lay.nsum), at<float>(c, c->lay.pd_part),
-                         c->stream);
+                         at<SelState>(c, c->lay.sel_t), c->stream);
   }
   launch_temporal_resolve(c->g, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
                           at<float>(c, c->lay.sig), at<float>(c, c->lay.e), at<uint32_t>(c, c->lay.sel_key_t),
-                          c->stream);
+                          at<SelState>(c, c->lay.sel_t), c->stream);
   int rc = after_launch(c);
   if (rc == STTM_OK) {
+    c->sel_t_dirty = false;
     c->have_temporal = true;
     c->node_map_temporal = node_map;
   }
@@ -396,23 +410,32 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
     const double k = target_keep_host[b];
     if (!(k > 0.0 && k <= 1.0)) return fail(ctx, STTM_ERR_ARG, "target_keep must be in (0, 1]");
   }
-  std::vector<int>& h_target = stage == STTM_STAGE_SPATIAL ? ctx->h_target_s : ctx->h_target_t;
-  h_target.resize(g.B);
+  const bool spatial = stage == STTM_STAGE_SPATIAL;
+  std::vector<int>& h_target = spatial ? ctx->h_target_s : ctx->h_target_t;
+  bool& on_device = spatial ? ctx->target_s_on_device : ctx->target_t_on_device;
+  std::vector<int> want(g.B);
   for (int b = 0; b < g.B; ++b) {
     const double k = target_keep_host[b];
-    h_target[b] = (int)std::floor((stage == STTM_STAGE_SPATIAL ? std::sqrt(k) : k) * thw);
+    want[b] = (int)std::floor((spatial ? std::sqrt(k) : k) * thw);
   }
   int rc;
-  int* target_dev = at<int>(ctx, stage == STTM_STAGE_SPATIAL ? ctx->lay.target_s : ctx->lay.target_t);
-  STTM_HIP(ctx, hipMemcpyAsync(target_dev, h_target.data(), g.B * sizeof(int), hipMemcpyHostToDevice,
-                               ctx->stream));
-  float* tau_dev = at<float>(ctx, stage == STTM_STAGE_SPATIAL ? ctx->lay.tau_s : ctx->lay.tau_t);
-  if (stage == STTM_STAGE_SPATIAL)
+  int* target_dev = at<int>(ctx, spatial ? ctx->lay.target_s : ctx->lay.target_t);
+  if (!on_device || want != h_target) {  // the same targets as last time are already there
+    h_target = want;
+    STTM_HIP(ctx, hipMemcpyAsync(target_dev, h_target.data(), g.B * sizeof(int), hipMemcpyHostToDevice,
+                                 ctx->stream));
+    on_device = true;
+  }
+  float* tau_dev = at<float>(ctx, spatial ? ctx->lay.tau_s : ctx->lay.tau_t);
+  if (spatial) {
     launch_select_spatial(g, at<uint32_t>(ctx, ctx->lay.sel_key_s), at<uint8_t>(ctx, ctx->lay.sel_w_s),
-                          target_dev, at<char>(ctx, ctx->lay.sel_state), tau_dev, ctx->stream);
-  else
+                          target_dev, at<SelState>(ctx, ctx->lay.sel_s), ctx->sel_s_dirty, tau_dev, ctx->stream);
+    ctx->sel_s_dirty = true;
+  } else {
     launch_select_temporal(g, ctx->node_map_temporal, at<uint32_t>(ctx, ctx->lay.sel_key_t), target_dev,
-                           at<char>(ctx, ctx->lay.sel_state), tau_dev, ctx->stream);
+                           at<SelState>(ctx, ctx->lay.sel_t), ctx->sel_t_dirty, tau_dev, ctx->stream);
+    ctx->sel_t_dirty = true;
+  }
   rc = after_launch(ctx);
   if (rc) return rc;
   if (stage == STTM_STAGE_SPATIAL) ctx->have_tau_s = true; else ctx->have_tau_t = true;
@@ -423,38 +446,48 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
   return STTM_OK;
 }
 
-int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids_dev, int out_dtype,
-                int64_t capacity, void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev,
-                int64_t* offsets_dev, int64_t* n_out_host) {
+int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids_dev,
+                const int32_t* node_map_dev, const uint8_t* node_level_dev, int out_dtype, int64_t capacity,
+                void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev, int64_t* offsets_dev,
+                int64_t* n_out_host) {
   if (!ctx) return STTM_ERR_NULL;
   if (!cluster_ids_dev || !merged_dev || !offsets_dev)
     return fail(ctx, STTM_ERR_NULL, "cluster_ids, merged and offsets are required");
+  if ((node_map_dev == nullptr) != (node_level_dev == nullptr))
+    return fail(ctx, STTM_ERR_NULL, "node_map and node_level go together (both or neither)");
   if (out_dtype != STTM_F32 && out_dtype != STTM_BF16) return fail(ctx, STTM_ERR_DTYPE, "bad out_dtype");
   if (capacity < 0) return fail(ctx, STTM_ERR_ARG, "capacity < 0");
   if (!ctx->bound) return fail(ctx, STTM_ERR_STATE, "no shape bound (run the spatial stage first)");
   int rc = check_feats(ctx, feats_dev);
   if (rc) return rc;
+  if (node_map_dev && (!ctx->have_spatial || ctx->feats_spatial != feats_dev))
+    return fail(ctx, STTM_ERR_STATE,
+                "a partition was given but the workspace holds no stage-1 statistics of these features");
   if (reinterpret_cast<uintptr_t>(merged_dev) & 15) return fail(ctx, STTM_ERR_ARG, "merged must be 16-byte aligned");
   STTM_HIP(ctx, hipSetDevice(ctx->device));
   ReduceBuffers rb;
   rb.rank = at<int32_t>(ctx, ctx->lay.rank);
-  rb.blocksum = at<int32_t>(ctx, ctx->lay.blocksum);
   rb.key_a = at<int32_t>(ctx, ctx->lay.key_a);
   rb.val_a = at<int32_t>(ctx, ctx->lay.val_a);
   rb.key_b = at<int32_t>(ctx, ctx->lay.key_b);
   rb.val_b = at<int32_t>(ctx, ctx->lay.val_b);
+  rb.order = at<int32_t>(ctx, ctx->lay.order);
+  rb.orow = at<int32_t>(ctx, ctx->lay.orow);
   rb.hist = at<int32_t>(ctx, ctx->lay.hist);
+  rb.tot = at<int32_t>(ctx, ctx->lay.tot);
+  rb.tile_roots = at<int32_t>(ctx, ctx->lay.tile_roots);
+  rb.tile_live = at<int32_t>(ctx, ctx->lay.tile_live);
   rb.seg = at<int32_t>(ctx, ctx->lay.seg);
   rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
   rb.bigpart = at<float>(ctx, ctx->lay.bigpart);
-  const int32_t* orow = nullptr;
-  rb.orow_out = &orow;
-  const int32_t* order = nullptr;
-  launch_reduce_prepare(ctx->g, cluster_ids_dev, capacity, counts_dev, out_ids_dev, offsets_dev, rb, &order,
-                        ctx->stream);
+  rb.bigw = at<int32_t>(ctx, ctx->lay.bigw);
+  launch_reduce_prepare(ctx->g, cluster_ids_dev, node_map_dev, node_level_dev, capacity, out_ids_dev, offsets_dev,
+                        rb, ctx->stream);
   {
     Timed t(ctx, STTM_KERNEL_REDUCE_GATHER);
-    launch_reduce_gather(ctx->g, feats_dev, out_dtype, capacity, merged_dev, rb, order, ctx->stream);
+    launch_reduce_gather(ctx->g, feats_dev, at<float>(ctx, ctx->lay.nsum), node_map_dev, node_level_dev, out_dtype,
+                         capacity,
+                         merged_dev, counts_dev, rb, ctx->stream);
   }
   rc = after_launch(ctx);
   if (rc) return rc;

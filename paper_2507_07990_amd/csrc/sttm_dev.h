@@ -112,26 +112,69 @@ __device__ inline void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
-struct Workspace;  // see sttm_api.hip
+// ---- budget search state (one per video and stage) ---------------------------------------------------
+// Token count as a function of the threshold is K(tau) = base + sum_j w_j [v_j <= tau]; the search is an
+// MSB-first radix select (11 + 11 + 10 bits) over the order-preserving integer image of v.
+constexpr int kSelBins = 2048;
+struct SelState {
+  unsigned hist[3][kSelBins];  // weight per digit: level 0 over all elements, levels 1-2 under the found prefix
+  unsigned lo_out;             // largest key whose leading 22 bits are below the found prefix (0 = none)
+  unsigned pad[31];
+};
 
-void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, hipStream_t s);
+// One workgroup zeroes a state.
+__device__ inline void sel_clear(SelState* st) {
+  unsigned* p = reinterpret_cast<unsigned*>(st);
+  for (int j = threadIdx.x; j < (int)(sizeof(SelState) / 4); j += blockDim.x) p[j] = 0;
+}
+
+// Adds w to hist[digit] for the lanes with valid set; every lane of the wavefront must call it. The two
+// most frequent leading digits of the wavefront are combined before the atomic (real similarities sit in
+// tight clusters, which would otherwise serialise on one LDS word); whatever is left goes through plain
+// LDS atomics.
+__device__ inline void wave_hist_add(unsigned* hist, bool valid, unsigned digit, unsigned w) {
+  unsigned long long todo = __ballot(valid);
+  for (int it = 0; it < 2 && todo; ++it) {
+    const int leader = __ffsll((long long)todo) - 1;
+    const unsigned d = __shfl(digit, leader, 64);
+    const bool mine = valid && digit == d;
+    const unsigned long long m = __ballot(mine);
+    const unsigned sum = __popcll(__ballot(mine && (w & 1))) + 2u * __popcll(__ballot(mine && (w & 2)));
+    if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d], sum);
+    todo &= ~m;
+  }
+  if ((todo >> (threadIdx.x & 63)) & 1ull) atomicAdd(&hist[digit], w);
+}
+
+// Adds a workgroup's LDS histogram of leading digits to the state's level-0 histogram (call after a barrier).
+__device__ inline void sel_flush_level0(SelState* st, const unsigned* lds_hist) {
+  for (int j = threadIdx.x; j < kSelBins; j += blockDim.x)
+    if (lds_hist[j]) atomicAdd(&st->hist[0][j], lds_hist[j]);
+}
+
+// ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
+
+// `sel`: the spatial search states [B]; cleared by the statistics pass, level 0 filled by the finalize kernel.
+void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
+                          hipStream_t s);
 void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
-                             uint32_t* sel_key, uint8_t* sel_w, hipStream_t s);
+                             uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s);
 void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
                            uint8_t* node_level, hipStream_t s);
+// `dirty`: the state has been searched since its statistics pass (levels 1-2 must be cleared first).
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
-                           void* state, float* tau, hipStream_t s);
+                           SelState* state, bool dirty, float* tau, hipStream_t s);
 void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
-                            void* state, float* tau, hipStream_t s);
-size_t select_state_bytes(int B);
+                            SelState* state, bool dirty, float* tau, hipStream_t s);
+inline size_t select_state_bytes(int B) { return (size_t)B * sizeof(SelState); }
+// `sel`: the temporal search states [B]; cleared here, level 0 filled by launch_temporal_resolve.
 void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
-                          float* pd_part, hipStream_t s);
+                          float* pd_part, SelState* sel, hipStream_t s);
 // fp32 sums of the pyramid nodes at levels >= 3: [F][nsum_nodes][D]
 inline size_t nsum_nodes(const Geo& g) { return g.L >= 3 ? (size_t)(g.NN - g.lvl_base[3]) : 0; }
 void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
                              const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
-                             hipStream_t s);
+                             SelState* sel, hipStream_t s);
 void launch_temporal_parent(const Geo& g, const int32_t* node_map, const uint8_t* node_level, const float* sig,
                             const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s);
 void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* node_map, int32_t* cluster_ids,
@@ -139,25 +182,32 @@ void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* n
 void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_level, hipStream_t s);
 
 struct ReduceBuffers {
-  int32_t* rank;      // [N]   exclusive scan of root flags
-  int32_t* blocksum;  // scan scratch
-  int32_t* key_a;     // [N] sort ping
-  int32_t* val_a;     // [N]
-  int32_t* key_b;     // [N] sort pong
-  int32_t* val_b;     // [N]
-  int32_t* hist;      // radix histogram table
-  int32_t* seg;       // [N+1] first sorted position of every output row
-  int32_t* kdev;      // [1] number of clusters
-  float* bigpart;     // window partial sums of clusters with more than 64 members
-  const int32_t** orow_out;  // host slot: where launch_reduce_prepare left the row-of-position array
+  int32_t* rank;        // [N]   exclusive count of roots before every cell
+  int32_t* key_a;       // [N] sort ping
+  int32_t* val_a;       // [N]
+  int32_t* key_b;       // [N] sort pong
+  int32_t* val_b;       // [N]
+  int32_t* order;       // [N] sorted element list (live part first)
+  int32_t* orow;        // [N] output row of every list position
+  int32_t* hist;        // [tiles][digits] radix histogram of the running pass
+  int32_t* tot;         // [digits] column totals (large inputs)
+  int32_t* tile_roots;  // [tiles]
+  int32_t* tile_live;   // [tiles]
+  int32_t* seg;         // [N+1] first list position of every output row
+  int32_t* kdev;        // [2] number of clusters, length of the live list
+  float* bigpart;       // window partial sums of clusters with more than 64 elements
+  int32_t* bigw;        // member counts of those partial sums
 };
-void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t capacity, int32_t* counts,
-                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
-                           const int32_t** order_out, hipStream_t s);
-void launch_reduce_gather(const Geo& g, const void* feats, int out_dtype, int64_t capacity, void* merged,
-                          const ReduceBuffers& rb, const int32_t* order, hipStream_t s);
+// node_map / node_level: the stage-1 partition, or both NULL (every cell is its own list element).
+void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map,
+                           const uint8_t* node_level, int64_t capacity, int32_t* out_ids, int64_t* offsets,
+                           const ReduceBuffers& rb, hipStream_t s);
+void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
+                          const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
+                          const ReduceBuffers& rb, hipStream_t s);
 size_t reduce_bigpart_floats(const Geo& g);
+size_t reduce_bigw_entries(const Geo& g);
 size_t reduce_hist_entries(int N);
-size_t scan_blocks(int n);
+size_t reduce_tiles(int N);
 
 }  // namespace sttm

@@ -1,25 +1,44 @@
 // Reduce stage (Sec. 3.1 / 3.3 / 3.4): one output token per cluster = mean of its member tokens, rows in
-// ascending cluster id. Integer plumbing: rank of every root (prefix sum), member lists (stable radix
-// sort of the cells by cluster id), then the one feature pass that gathers and averages.
+// ascending cluster id. Integer plumbing: rank of every root (prefix sum over tiles), member lists (stable
+// LSD radix sort of the list elements by cluster id), then the one feature pass that gathers and averages.
+//
+// A list element is a cell, or -- when the caller hands over the stage-1 partition -- a whole node at level
+// >= 3, represented by its top-left cell: its per-channel sum was stored by the spatial pass, so its up to
+// 4^level cells are not read again; the other cells of such a node take no part in the list ("dropped", key -1).
 #include "sttm_dev.h"
 
 namespace sttm {
 
-// ---- exclusive prefix sum over int32 -------------------------------------------------------------------
-constexpr int kScanBlock = 256;
-constexpr int kScanPer = 8;
-constexpr int kScanTile = kScanBlock * kScanPer;  // 2048 elements per workgroup
+constexpr int kSortThreads = 256;
+constexpr int kSortPer = 8;
+constexpr int kSortTile = kSortThreads * kSortPer;  // 2048 elements per workgroup
+constexpr int kSortWaves = kSortThreads / kWave;
+constexpr int kMaxDigitBits = 11;
+constexpr int kMaxDigits = 1 << kMaxDigitBits;
+constexpr int kInKernelColumns = 256;  // up to this many tiles a scatter workgroup sums the histogram columns itself
 
-size_t scan_blocks(int n) { return (size_t)(n + kScanTile - 1) / kScanTile; }
+struct SortPlan {
+  int passes, dbits, nb;
+  bool prescan;
+};
 
-// MODE 0: input = in[i]; MODE 1: input = (in[i] == i) (root flags of a cluster map)
-template <int MODE> __device__ inline int scan_input(const int32_t* in, int i) {
-  return MODE == 0 ? in[i] : (in[i] == i ? 1 : 0);
+static SortPlan sort_plan(int N) {
+  SortPlan p;
+  int bits = 1;
+  while ((1ll << bits) < (long long)N) ++bits;  // keys 0..N-1
+  p.passes = (bits + kMaxDigitBits - 1) / kMaxDigitBits;
+  p.dbits = (bits + p.passes - 1) / p.passes;
+  p.nb = (N + kSortTile - 1) / kSortTile;
+  p.prescan = p.nb > kInKernelColumns;
+  return p;
 }
 
+size_t reduce_tiles(int N) { return (size_t)(N + kSortTile - 1) / kSortTile; }
+size_t reduce_hist_entries(int N) { return (size_t)kMaxDigits * reduce_tiles(N); }
+
+// Exclusive prefix of v over the 256 threads of the workgroup; *total = sum over all threads.
 __device__ inline int block_exclusive_scan(int v, int* total) {
-  // 256 threads; returns the exclusive prefix of v within the workgroup
-  __shared__ int wsum[kScanBlock / kWave];
+  __shared__ int wsum[kSortWaves];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int inc = v;
 #pragma unroll
@@ -31,7 +50,7 @@ __device__ inline int block_exclusive_scan(int v, int* total) {
   __syncthreads();
   int base = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < kScanBlock / kWave; ++w) {
+  for (int w = 0; w < kSortWaves; ++w) {
     if (w < wave) base += wsum[w];
     tot += wsum[w];
   }
@@ -40,177 +59,368 @@ __device__ inline int block_exclusive_scan(int v, int* total) {
   return base + inc - v;
 }
 
-template <int MODE>
-__global__ __launch_bounds__(kScanBlock) void k_scan_local(int n, const int32_t* in, int32_t* out,
-                                                           int32_t* __restrict__ blocksum) {
-  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanPer;
-  int v[kScanPer], s = 0;
+// Sum of v over the workgroup, returned to every thread.
+__device__ inline int block_sum(int v) {
+  int total;
+  (void)block_exclusive_scan(v, &total);
+  return total;
+}
+
+__device__ inline int node_cells(const Geo& g, int cell_in_frame, int lvl) {
+  const int y = cell_in_frame / g.W, x = cell_in_frame - y * g.W, s = 1 << lvl;
+  return (min(y + s, g.H) - y) * (min(x + s, g.W) - x);
+}
+// True when the node with top-left cell c (in-frame index) at level lv is represented by its stored sum.
+__device__ inline bool node_is_summed(const Geo& g, int c, int lv) { return lv >= 3 && node_cells(g, c, lv) >= 2; }
+// The cell that stands for the second half of a summed node: the next valid cell of the node in raster order.
+__device__ inline int node_second_cell(const Geo& g, int c) { return (c % g.W) + 1 < g.W ? c + 1 : c + g.W; }
+
+// ------------------------------------------------------------------------------------------------
+// k_reduce_prep: one workgroup per tile of 2048 cells. Sort keys (cluster id, or -1 for a cell covered by a
+// stored node sum), tile-local exclusive ranks of the roots (cells that are their own cluster id), the
+// tile's totals, and the tile's digit histogram of the first sort pass.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSortThreads) void k_reduce_prep(Geo g, const int32_t* __restrict__ cluster_ids,
+                                                              const int32_t* __restrict__ node_map,
+                                                              const uint8_t* __restrict__ node_level, int dbits,
+                                                              int32_t* __restrict__ keys, int32_t* __restrict__ rank,
+                                                              int32_t* __restrict__ tile_roots,
+                                                              int32_t* __restrict__ tile_live,
+                                                              int32_t* __restrict__ hist) {
+  __shared__ int cnt[kMaxDigits];
+  const int DIG = 1 << dbits, b = blockIdx.x, tid = threadIdx.x;
+  for (int d = tid; d < DIG; d += kSortThreads) cnt[d] = 0;
+  __syncthreads();
+  const int i0 = b * kSortTile + tid * kSortPer;
+  int root[kSortPer], nroot = 0, nlive = 0;
 #pragma unroll
-  for (int j = 0; j < kScanPer; ++j) {
-    v[j] = (base + j < n) ? scan_input<MODE>(in, base + j) : 0;
-    s += v[j];
+  for (int j = 0; j < kSortPer; ++j) {
+    const int i = i0 + j;
+    root[j] = 0;
+    if (i < g.N) {
+      const int cid = cluster_ids[i];
+      bool live = true;
+      if (node_map && node_level[i] >= 3) {  // a node with a stored sum: only the cells standing for it stay
+        const int rep = node_map[i], c = rep % g.HW;
+        if (node_is_summed(g, c, node_level[i]))
+          live = i == rep || (g.vec == 8 && i == rep - c + node_second_cell(g, c));
+      }
+      keys[i] = live ? cid : -1;
+      root[j] = cid == i;
+      nroot += root[j];
+      nlive += live;
+      if (live) atomicAdd(&cnt[cid & (DIG - 1)], 1);
+    }
   }
   int total;
-  int ex = block_exclusive_scan(s, &total);
+  int ex = block_exclusive_scan(nroot, &total);
 #pragma unroll
-  for (int j = 0; j < kScanPer; ++j) {
-    if (base + j < n) out[base + j] = ex;
-    ex += v[j];
+  for (int j = 0; j < kSortPer; ++j) {
+    if (i0 + j < g.N) rank[i0 + j] = ex;
+    ex += root[j];
   }
-  if (threadIdx.x == 0) blocksum[blockIdx.x] = total;
-}
-
-// One workgroup scans the per-block totals in place (exclusive), sequentially over tiles.
-__global__ __launch_bounds__(kScanBlock) void k_scan_tops(int nb, int32_t* __restrict__ blocksum,
-                                                          int32_t* __restrict__ grand_total) {
-  int carry = 0;
-  for (int t0 = 0; t0 < nb; t0 += kScanBlock) {
-    const int i = t0 + threadIdx.x;
-    const int v = i < nb ? blocksum[i] : 0;
-    int total;
-    const int ex = block_exclusive_scan(v, &total);
-    if (i < nb) blocksum[i] = carry + ex;
-    carry += total;
-  }
-  if (threadIdx.x == 0 && grand_total) *grand_total = carry;
-}
-
-__global__ __launch_bounds__(kScanBlock) void k_scan_add(int n, int32_t* __restrict__ out,
-                                                         const int32_t* __restrict__ blocksum) {
-  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanPer;
-  const int add = blocksum[blockIdx.x];
-#pragma unroll
-  for (int j = 0; j < kScanPer; ++j)
-    if (base + j < n) out[base + j] += add;
-}
-
-template <int MODE>
-static void exclusive_scan(int n, const int32_t* in, int32_t* out, int32_t* blocksum, int32_t* total,
-                           hipStream_t s) {
-  const int nb = (int)scan_blocks(n);
-  hipLaunchKernelGGL(k_scan_local<MODE>, dim3(nb), dim3(kScanBlock), 0, s, n, in, out, blocksum);
-  hipLaunchKernelGGL(k_scan_tops, dim3(1), dim3(kScanBlock), 0, s, nb, blocksum, total);
-  hipLaunchKernelGGL(k_scan_add, dim3(nb), dim3(kScanBlock), 0, s, n, out, blocksum);
-}
-
-// ---- stable LSD radix sort of (key, value) pairs, 11-bit digits --------------------------------------
-// A workgroup is one wavefront that owns kSortTile consecutive elements; it handles them 64 at a time in
-// index order, so ranks inside the tile are stable without any cross-wave ordering.
-constexpr int kSortTile = 1024;
-constexpr int kRadixBits = 11;
-constexpr int kRadix = 1 << kRadixBits;
-
-size_t reduce_hist_entries(int N) { return (size_t)kRadix * ((N + kSortTile - 1) / kSortTile); }
-
-__global__ __launch_bounds__(64) void k_sort_hist(int n, int shift, const int32_t* __restrict__ keys,
-                                                  int32_t* __restrict__ hist, int nblocks) {
-  __shared__ int cnt[kRadix];
-  for (int j = threadIdx.x; j < kRadix; j += 64) cnt[j] = 0;
-  __syncthreads();
-  const int base = blockIdx.x * kSortTile;
-  for (int o = threadIdx.x; o < kSortTile; o += 64) {
-    const int i = base + o;
-    if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & (kRadix - 1)], 1);
+  const int live_total = block_sum(nlive);
+  if (tid == 0) {
+    tile_roots[b] = total;
+    tile_live[b] = live_total;
   }
   __syncthreads();
-  for (int j = threadIdx.x; j < kRadix; j += 64) hist[j * nblocks + blockIdx.x] = cnt[j];
+  for (int d = tid; d < DIG; d += kSortThreads) hist[(size_t)b * DIG + d] = cnt[d];
 }
 
-__global__ __launch_bounds__(64) void k_sort_scatter(int n, int shift, const int32_t* __restrict__ keys,
-                                                     const int32_t* __restrict__ vals,
-                                                     int32_t* __restrict__ keys_out,
-                                                     int32_t* __restrict__ vals_out,
-                                                     const int32_t* __restrict__ hist, int nblocks,
-                                                     int first_pass) {
-  __shared__ int cur[kRadix];
-  const int lane = threadIdx.x;
-  for (int j = lane; j < kRadix; j += 64) cur[j] = hist[j * nblocks + blockIdx.x];
+// Digit histogram per tile of the (compacted) keys of a later pass; tiles beyond the list write zeros.
+__global__ __launch_bounds__(kSortThreads) void k_sort_hist(const int32_t* __restrict__ kdev, int shift, int dbits,
+                                                            const int32_t* __restrict__ keys,
+                                                            int32_t* __restrict__ hist) {
+  __shared__ int cnt[kMaxDigits];
+  const int DIG = 1 << dbits, b = blockIdx.x, tid = threadIdx.x, n = kdev[1];
+  for (int d = tid; d < DIG; d += kSortThreads) cnt[d] = 0;
   __syncthreads();
-  const int base = blockIdx.x * kSortTile;
-  const unsigned long long below = (1ull << lane) - 1ull;
-  for (int o = 0; o < kSortTile; o += 64) {
-    const int i = base + o + lane;
-    const bool ok = i < n;
-    const int key = ok ? keys[i] : 0;
-    const int val = ok ? (first_pass ? i : vals[i]) : 0;
-    const int digit = (key >> shift) & (kRadix - 1);
-    // lanes holding the same digit
-    unsigned long long same = __ballot(ok);
 #pragma unroll
-    for (int bit = 0; bit < kRadixBits; ++bit) {
-      const unsigned long long m = __ballot((digit >> bit) & 1);
-      same &= ((digit >> bit) & 1) ? m : ~m;
-    }
-    if (ok) {
-      const int rank = __popcll(same & below);
-      const int dst = cur[digit] + rank;
-      keys_out[dst] = key;
-      vals_out[dst] = val;
-    }
-    __syncthreads();
-    if (ok && (same >> lane) >> 1 == 0)  // highest lane of its digit group advances the cursor
-      cur[digit] += __popcll(same);
-    __syncthreads();
+  for (int j = 0; j < kSortPer; ++j) {
+    const int i = b * kSortTile + j * kSortThreads + tid;
+    if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & (DIG - 1)], 1);
   }
+  __syncthreads();
+  for (int d = tid; d < DIG; d += kSortThreads) hist[(size_t)b * DIG + d] = cnt[d];
 }
 
-// ---- ranks, segment starts, bookkeeping outputs ------------------------------------------------------
 __global__ __launch_bounds__(256) void k_fill_i32(int n, int32_t* __restrict__ p, int32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
 }
 
-// out_ids, per-video offsets and the cluster count from the exclusive scan of the root flags.
-__global__ __launch_bounds__(256) void k_root_outputs(Geo g, const int32_t* __restrict__ cluster_ids,
-                                                      const int32_t* __restrict__ rank,
-                                                      const int32_t* __restrict__ kdev, int64_t capacity,
-                                                      int32_t* __restrict__ out_ids,
-                                                      int64_t* __restrict__ offsets) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= g.N) return;
-  if (cluster_ids[i] == i && out_ids && rank[i] < capacity) out_ids[rank[i]] = i;
-  const int per_video = g.T * g.HW;
-  if (i % per_video == 0) offsets[i / per_video] = rank[i];
-  if (i == 0) offsets[g.B] = *kdev;
-}
-
-// seg[k] = first sorted position of output row k, seg[K] = N; orow[p] = output row of sorted position p.
-__global__ __launch_bounds__(256) void k_segments(int n, const int32_t* __restrict__ skey,
-                                                  const int32_t* __restrict__ rank,
-                                                  const int32_t* __restrict__ kdev, int32_t* __restrict__ seg,
-                                                  int32_t* __restrict__ orow) {
-  const int p = blockIdx.x * blockDim.x + threadIdx.x;
-  if (p >= n) return;
-  const int key = skey[p];
-  const int k = rank[key];
-  orow[p] = k;
-  if (p == 0 || skey[p - 1] != key) seg[k] = p;
-  if (p == n - 1) seg[*kdev] = n;
-}
-
-__global__ __launch_bounds__(256) void k_counts(const int32_t* __restrict__ kdev, const int32_t* __restrict__ seg,
-                                                int64_t capacity, int32_t* __restrict__ counts) {
-  const int k = blockIdx.x * blockDim.x + threadIdx.x;
-  if (k < *kdev && k < capacity) counts[k] = seg[k + 1] - seg[k];
+// Large inputs only: turns every column (digit) of hist[tile][digit] into its exclusive prefix over the
+// tiles and leaves the column total in tot[digit].
+__global__ __launch_bounds__(256) void k_sort_colscan(int nb, int DIG, int32_t* __restrict__ hist,
+                                                      int32_t* __restrict__ tot) {
+  const int d = blockIdx.x * blockDim.x + threadIdx.x;
+  if (d >= DIG) return;
+  int run = 0;
+  for (int t = 0; t < nb; ++t) {
+    const int v = hist[(size_t)t * DIG + d];
+    hist[(size_t)t * DIG + d] = run;
+    run += v;
+  }
+  tot[d] = run;
 }
 
 // ------------------------------------------------------------------------------------------------
-// The gather/average pass. The sorted member list is cut into items of kItem consecutive positions;
-// an item owns the clusters whose list starts inside it. One wavefront per (item, chunk of the row):
-// a lane owns VEC channels. All index look-ups of the item are done lane-parallel first, then all row
-// loads are issued, then the rows are summed in list order (ascending flat index, fp32) with the
-// cluster boundaries handled as wave-uniform control flow.
-// Clusters with more than kBig members are left to the two kernels below, which cut them at fixed
-// kBig-aligned list positions so that the summation order does not depend on scheduling.
+// k_sort_pass: one stable scatter pass, one workgroup per tile of 2048 elements. The workgroup first turns
+// the histogram into its own start offset for every digit (summing the columns over the tiles before it
+// unless k_sort_colscan did so), then every wavefront ranks its 512 consecutive elements 64 at a time in
+// index order (ballot matching), so the order of equal keys is kept.
+//   FIRST: elements are the cells themselves (value = index), dropped cells (key < 0) stay behind, so the
+//          output is compact. Also makes the root ranks global, and writes out_ids, the per-video offsets
+//          and the totals (K, list length).
+//   LAST:  writes the sorted element list, the output row of every list position and the first list
+//          position of every row (the root is the smallest index of its cluster, hence first in its list).
+// ------------------------------------------------------------------------------------------------
+struct SortArgs {
+  int n, shift, dbits, nb, prescan;
+  const int32_t* keys;
+  const int32_t* vals;
+  int32_t* keys_out;
+  int32_t* vals_out;  // LAST: the sorted element list
+  const int32_t* hist;
+  const int32_t* tot;
+  // FIRST
+  const int32_t* cluster_ids;
+  int32_t* rank;
+  const int32_t* tile_roots;
+  const int32_t* tile_live;
+  int32_t* kdev;  // [0] = K, [1] = list length
+  int32_t* out_ids;
+  int64_t* offsets;
+  int64_t capacity;
+  int per_video, B;
+  // LAST
+  int32_t* orow;
+  int32_t* seg;
+};
+
+template <bool FIRST, bool LAST>
+__global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
+  __shared__ int s_base[kMaxDigits];
+  __shared__ int cur[kSortWaves][kMaxDigits];
+  const int DIG = 1 << a.dbits, b = blockIdx.x, tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int n = FIRST ? a.n : a.kdev[1];
+
+  // ---- start offset of every digit for this tile (a thread owns `dpt` consecutive digits)
+  {
+    constexpr int kDpt = kMaxDigits / kSortThreads;
+    const int dpt = DIG >= kSortThreads ? DIG / kSortThreads : 1;
+    int tv[kDpt], cv[kDpt], s = 0;
+#pragma unroll
+    for (int j = 0; j < kDpt; ++j) {
+      const int d = tid * dpt + j;
+      tv[j] = cv[j] = 0;
+      if (j < dpt && d < DIG) {
+        if (a.prescan) {
+          tv[j] = a.tot[d];
+          cv[j] = a.hist[(size_t)b * DIG + d];
+        } else {
+          int run = 0, mine = 0;
+          for (int t0 = 0; t0 < a.nb; t0 += 8) {  // eight independent loads at a time
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = t0 + u < a.nb ? a.hist[(size_t)(t0 + u) * DIG + d] : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              if (t0 + u == b) mine = run;
+              run += v[u];
+            }
+          }
+          tv[j] = run;
+          cv[j] = mine;
+        }
+      }
+      s += tv[j];
+    }
+    int total;
+    int ex = block_exclusive_scan(s, &total);
+#pragma unroll
+    for (int j = 0; j < kDpt; ++j) {
+      const int d = tid * dpt + j;
+      if (j < dpt && d < DIG) s_base[d] = ex + cv[j];
+      ex += tv[j];
+    }
+  }
+  int root_prefix = 0;
+  if (FIRST) {
+    int before = 0, all = 0, live = 0;
+    for (int t = tid; t < a.nb; t += kSortThreads) {
+      const int v = a.tile_roots[t];
+      all += v;
+      if (t < b) before += v;
+      if (b == 0) live += a.tile_live[t];
+    }
+    root_prefix = block_sum(before);
+    if (b == 0) {
+      all = block_sum(all);
+      live = block_sum(live);
+      if (tid == 0) {
+        a.kdev[0] = all;
+        a.kdev[1] = live;
+        a.offsets[a.B] = all;
+        if (LAST) a.seg[all] = live;
+      }
+    }
+  }
+  if (LAST && !FIRST && b == 0 && tid == 0) a.seg[a.kdev[0]] = n;
+  for (int d = tid; d < DIG; d += kSortThreads)
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) cur[w][d] = 0;
+  __syncthreads();
+
+  // ---- loads and per-wavefront digit counts of its 512 elements
+  const int e0 = b * kSortTile + wave * (kSortTile / kSortWaves);
+  int key[kSortPer], val[kSortPer], aux[kSortPer];
+  bool ok[kSortPer];
+#pragma unroll
+  for (int r = 0; r < kSortPer; ++r) {
+    const int i = e0 + r * 64 + lane;
+    key[r] = -1;
+    val[r] = 0;
+    if (i < n) {
+      key[r] = a.keys[i];
+      val[r] = FIRST ? i : a.vals[i];
+    }
+    ok[r] = key[r] >= 0;
+    if (ok[r]) atomicAdd(&cur[wave][(key[r] >> a.shift) & (DIG - 1)], 1);
+  }
+#pragma unroll
+  for (int r = 0; r < kSortPer; ++r) {
+    aux[r] = 0;
+    if (LAST && ok[r]) aux[r] = a.rank[key[r]];  // output row of the element's cluster
+  }
+  if (FIRST) {
+    // bookkeeping outputs of the cells themselves
+#pragma unroll
+    for (int r = 0; r < kSortPer; ++r) {
+      const int i = e0 + r * 64 + lane;
+      if (i >= n) continue;
+      const int rk = a.rank[i] + root_prefix;
+      if (b != 0) a.rank[i] = rk;
+      if (a.cluster_ids[i] == i && a.out_ids && rk < a.capacity) a.out_ids[rk] = i;
+      if (i % a.per_video == 0) a.offsets[i / a.per_video] = rk;
+    }
+  }
+  __syncthreads();
+  for (int d = tid; d < DIG; d += kSortThreads) {
+    int run = s_base[d];
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) {
+      const int c = cur[w][d];
+      cur[w][d] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+
+  // ---- ranked scatter, 64 elements at a time in index order
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int* mycur = cur[wave];
+#pragma unroll
+  for (int r = 0; r < kSortPer; ++r) {
+    const int digit = (key[r] >> a.shift) & (DIG - 1);
+    unsigned long long same = __ballot(ok[r]);
+    for (int bit = 0; bit < a.dbits; ++bit) {
+      const unsigned long long m = __ballot((digit >> bit) & 1);
+      same &= ((digit >> bit) & 1) ? m : ~m;
+    }
+    if (ok[r]) {
+      const int dst = mycur[digit] + __popcll(same & below);
+      if (LAST) {
+        a.vals_out[dst] = val[r];
+        a.orow[dst] = aux[r];
+        if (key[r] == val[r]) a.seg[aux[r]] = dst;
+      } else {
+        a.keys_out[dst] = key[r];
+        a.vals_out[dst] = val[r];
+      }
+    }
+    wave_lds_fence();
+    if (ok[r] && ((same >> lane) >> 1) == 0)  // highest lane of its digit group advances the cursor
+      mycur[digit] += __popcll(same);
+    wave_lds_fence();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The gather/average pass. Every list slot is one 16-byte load per lane: a cell's row (VEC channels of the
+// input type), or four fp32 channels of a stored node sum -- with bf16 input a lane owns eight channels, so
+// such a node takes two slots (its top-left cell and the next cell of the node stand for the two halves).
+// The list is cut into items of kItem consecutive slots; an item owns the clusters whose list starts
+// inside it. One wavefront per (item, chunk of the row). All index look-ups of the item are done
+// lane-parallel first, then all loads are issued, then the slots are added up in list order (fp32) with the
+// cluster boundaries handled as wave-uniform control flow. Clusters with more than kBig slots are left to
+// the two kernels below, which cut them at fixed kBig-aligned list positions so that the summation order
+// does not depend on scheduling.
 // ------------------------------------------------------------------------------------------------
 constexpr int kItem = 16;
 constexpr int kBig = 64;
+constexpr int kTail = 8;
 
-template <int DT> __device__ inline void acc_row(const typename Row<DT>::Raw& r, float (&acc)[Row<DT>::VEC]) {
-  float t[Row<DT>::VEC];
-  Row<DT>::unpack(r, t);
+// Where a list slot's data lives.
+struct Slot {
+  int kind;    // 0 = cell row, 1 / 2 = first / second four channels of a lane's share of a node sum
+  int idx;     // flat cell index, or row of the node-sum table
+  int weight;  // member cells it stands for
+};
+
+template <int DT>
+__device__ inline Slot describe(const Geo& g, const int32_t* __restrict__ node_map,
+                                const uint8_t* __restrict__ lvl, int cell) {
+  Slot e;
+  e.kind = 0;
+  e.idx = cell;
+  e.weight = 1;
+  if (lvl) {
+    const int lv = lvl[cell];
+    if (lv >= 3) {
+      const int rep = node_map[cell];
+      const int f = rep / g.HW, c = rep - f * g.HW;
+      if (node_is_summed(g, c, lv)) {
+        const int y = c / g.W, x = c - y * g.W;
+        e.idx = f * (g.NN - g.lvl_base[3]) + node_index(g, lv, y >> lv, x >> lv) - g.lvl_base[3];
+        e.kind = cell == rep ? 1 : 2;
+        e.weight = cell == rep ? node_cells(g, c, lv) : 0;
+      }
+    }
+  }
+  return e;
+}
+
+template <int DT>
+__device__ inline typename Row<DT>::Raw load_slot(const void* feats, const float* nsum, int D, int ch0, int kind,
+                                                  int idx) {
+  typedef Row<DT> R;
+  if (kind == 0)
+    return *reinterpret_cast<const typename R::Raw*>(reinterpret_cast<const typename R::Elem*>(feats) +
+                                                     (size_t)idx * D + ch0);
+  return *reinterpret_cast<const typename R::Raw*>(nsum + (size_t)idx * D + ch0 + (kind - 1) * 4);
+}
+
+__device__ inline void acc_slot(const float4& r, int, float (&acc)[4]) {  // fp32 rows and node sums share a layout
+  acc[0] += r.x; acc[1] += r.y; acc[2] += r.z; acc[3] += r.w;
+}
+__device__ inline void acc_slot(const uint4& r, int kind, float (&acc)[8]) {
+  if (kind == 0) {
+    float t[8];
+    Row<1>::unpack(r, t);
 #pragma unroll
-  for (int v = 0; v < Row<DT>::VEC; ++v) acc[v] += t[v];
+    for (int v = 0; v < 8; ++v) acc[v] += t[v];
+  } else {
+    const float f0 = __uint_as_float(r.x), f1 = __uint_as_float(r.y);
+    const float f2 = __uint_as_float(r.z), f3 = __uint_as_float(r.w);
+    if (kind == 1) {
+      acc[0] += f0; acc[1] += f1; acc[2] += f2; acc[3] += f3;
+    } else {
+      acc[4] += f0; acc[5] += f1; acc[6] += f2; acc[7] += f3;
+    }
+  }
 }
 
 template <int DT, int ODT>
@@ -235,58 +445,103 @@ __device__ inline void store_mean(void* merged_v, size_t elem_off, const float (
   }
 }
 
+struct GatherArgs {
+  const void* feats;
+  const float* nsum;
+  const int32_t* node_map;  // the stage-1 partition, or both NULL when every slot is a cell
+  const uint8_t* lvl;
+  const int32_t* order;
+  const int32_t* orow;
+  const int32_t* seg;
+  const int32_t* kdev;
+  int64_t capacity;
+  void* merged;
+  int32_t* counts;
+  float* bigpart;
+  int32_t* bigw;
+};
+
 template <int DT, int ODT>
-__global__ __launch_bounds__(1024) void k_reduce(Geo g, const void* __restrict__ feats_v,
-                                                 const int32_t* __restrict__ order,
-                                                 const int32_t* __restrict__ orow,
-                                                 const int32_t* __restrict__ seg, int64_t capacity,
-                                                 void* __restrict__ merged_v) {
+__global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-  const int p0 = blockIdx.x * kItem, p1 = min(p0 + kItem, g.N);
-  const typename R::Elem* fb = reinterpret_cast<const typename R::Elem*>(feats_v);
-  // lane j < kItem describes sorted position p0 + j
-  int cell_v = 0, row_v = -1, beg_v = 0, end_v = 0;
+  const int M = a.kdev[1];
+  const int p0 = blockIdx.x * kItem, p1 = min(p0 + kItem, M);
+  if (p0 >= M) return;
+  // lane j < kItem describes list position p0 + j
+  Slot sv = {0, 0, 0};
+  int row_v = -1, beg_v = 0, end_v = 0;
   if (lane < kItem && p0 + lane < p1) {
-    cell_v = order[p0 + lane];
-    row_v = orow[p0 + lane];
-    beg_v = seg[row_v];
-    end_v = seg[row_v + 1];
+    sv = describe<DT>(g, a.node_map, a.lvl, a.order[p0 + lane]);
+    row_v = a.orow[p0 + lane];
+    beg_v = a.seg[row_v];
+    end_v = a.seg[row_v + 1];
   }
   for (int chunk = wave; chunk < g.nC; chunk += nw) {
     const int ch0 = chunk * g.cch + lane * VEC;
     const bool act = ch0 < g.D;
-    // issue every row load of the item that this item owns
+    // issue every load of the positions this item owns
     typename R::Raw raw[kItem];
 #pragma unroll
     for (int j = 0; j < kItem; ++j) {
-      const int beg = __shfl(beg_v, j, 64), end = __shfl(end_v, j, 64), cell = __shfl(cell_v, j, 64);
+      const int beg = __shfl(beg_v, j, 64), end = __shfl(end_v, j, 64);
+      const int kind = __shfl(sv.kind, j, 64), idx = __shfl(sv.idx, j, 64);
       raw[j] = R::zero();
       const bool use = p0 + j < p1 && beg >= p0 && end - beg <= kBig;  // wave-uniform
-      if (use && act) raw[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)cell * g.D + ch0);
+      if (use && act) raw[j] = load_slot<DT>(a.feats, a.nsum, g.D, ch0, kind, idx);
     }
     float acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    int members = 0, open_row = -1, open_end = 0;  // the cluster still open after the item's last position
 #pragma unroll
     for (int j = 0; j < kItem; ++j) {
       const int beg = __shfl(beg_v, j, 64), end = __shfl(end_v, j, 64), row = __shfl(row_v, j, 64);
+      const int kind = __shfl(sv.kind, j, 64), wgt = __shfl(sv.weight, j, 64);
       const bool use = p0 + j < p1 && beg >= p0 && end - beg <= kBig;
-      if (!use) continue;
-      acc_row<DT>(raw[j], acc);
-      const int p = p0 + j;
-      if (p + 1 == end || j == kItem - 1 || p + 1 == p1) {
-        // the cluster either ends here, or runs past the item: finish it from the list
-        for (int q = p + 1; q < end; ++q) {
-          typename R::Raw r = R::zero();
-          if (act) r = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)order[q] * g.D + ch0);
-          acc_row<DT>(r, acc);
-        }
-        if (act && row < capacity)
-          store_mean<DT, ODT>(merged_v, (size_t)row * g.D + ch0, acc, 1.f / (float)(end - beg));
+      if (use) {
+        acc_slot(raw[j], kind, acc);
+        members += wgt;
+        const int p = p0 + j;
+        if (p + 1 == end) {
+          if (row < a.capacity) {
+            if (act) store_mean<DT, ODT>(a.merged, (size_t)row * g.D + ch0, acc, 1.f / (float)members);
+            if (chunk == 0 && lane == 0 && a.counts) a.counts[row] = members;
+          }
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+          for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+          members = 0;
+        } else if (p + 1 == p1) {
+          open_row = row;
+          open_end = end;
+        }
+      }
+    }
+    if (open_row >= 0) {
+      // the last cluster runs past the item: finish it from the list, kTail loads in flight
+      for (int q = p1; q < open_end; q += kTail) {
+        Slot ts = {0, 0, 0};
+        if (lane < kTail && q + lane < open_end) ts = describe<DT>(g, a.node_map, a.lvl, a.order[q + lane]);
+        typename R::Raw tr[kTail];
+#pragma unroll
+        for (int u = 0; u < kTail; ++u) {
+          const int kd = __shfl(ts.kind, u, 64), ix = __shfl(ts.idx, u, 64);
+          tr[u] = R::zero();
+          if (q + u < open_end && act) tr[u] = load_slot<DT>(a.feats, a.nsum, g.D, ch0, kd, ix);
+        }
+#pragma unroll
+        for (int u = 0; u < kTail; ++u) {
+          const int kd = __shfl(ts.kind, u, 64), wg = __shfl(ts.weight, u, 64);
+          if (q + u < open_end) {
+            acc_slot(tr[u], kd, acc);
+            members += wg;
+          }
+        }
+      }
+      if (open_row < a.capacity) {
+        if (act) store_mean<DT, ODT>(a.merged, (size_t)open_row * g.D + ch0, acc, 1.f / (float)members);
+        if (chunk == 0 && lane == 0 && a.counts) a.counts[open_row] = members;
       }
     }
   }
@@ -295,39 +550,39 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, const void* __restrict__
 // Partial sums of the big clusters over fixed windows of kBig list positions: slot 0 = the big cluster
 // running into the window from the left, slot 1 = the big cluster starting inside it (at most one each).
 template <int DT>
-__global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, const void* __restrict__ feats_v,
-                                                             const int32_t* __restrict__ order,
-                                                             const int32_t* __restrict__ orow,
-                                                             const int32_t* __restrict__ seg,
-                                                             float* __restrict__ bigpart) {
+__global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, GatherArgs a) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, g.N);
-  int beg = -1, end = -1, cell_v = 0;
+  const int M = a.kdev[1];
+  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, M);
+  if (w0 >= M) return;
+  int beg = -1, end = -1;
+  int cell = 0;
   if (w0 + lane < w1) {
-    const int row = orow[w0 + lane];
-    beg = seg[row];
-    end = seg[row + 1];
-    cell_v = order[w0 + lane];
+    const int row = a.orow[w0 + lane];
+    beg = a.seg[row];
+    end = a.seg[row + 1];
+    cell = a.order[w0 + lane];
   }
   const bool big = end - beg > kBig;
   const int beg0 = __shfl(beg, 0, 64), end0 = __shfl(end, 0, 64);
   const bool has_left = (end0 - beg0 > kBig) && beg0 < w0;
   const unsigned long long starts = __ballot(big && beg == w0 + lane);
   if (!has_left && starts == 0) return;
-  const typename R::Elem* fb = reinterpret_cast<const typename R::Elem*>(feats_v);
+  Slot sv = {0, 0, 0};
+  if (w0 + lane < w1) sv = describe<DT>(g, a.node_map, a.lvl, cell);
   for (int slot = 0; slot < 2; ++slot) {
-    int a, b;
+    int pa, pb;
     if (slot == 0) {
       if (!has_left) continue;
-      a = w0;
-      b = min(end0, w1);
+      pa = w0;
+      pb = min(end0, w1);
     } else {
       if (starts == 0) continue;
       const int l = __ffsll((long long)starts) - 1;
-      a = w0 + l;
-      b = min(__shfl(end, l, 64), w1);
+      pa = w0 + l;
+      pb = min(__shfl(end, l, 64), w1);
     }
     for (int chunk = wave; chunk < g.nC; chunk += nw) {
       const int ch0 = chunk * g.cch + lane * VEC;
@@ -335,21 +590,29 @@ __global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, const void* 
       float acc[VEC];
 #pragma unroll
       for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-      // rows a..b-1 of the window, eight loads in flight; the cell of list position w0 + l sits in lane l
-      for (int q = a; q < b; q += 8) {
+      int members = 0;
+      // slots pa..pb-1 of the window, eight loads in flight; the slot of list position w0 + l sits in lane l
+      for (int q = pa; q < pb; q += 8) {
         typename R::Raw r[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          const int cell = __shfl(cell_v, min(q + j, w1 - 1) - w0, 64);
+          const int src = min(q + j, w1 - 1) - w0;
+          const int kd = __shfl(sv.kind, src, 64), ix = __shfl(sv.idx, src, 64);
           r[j] = R::zero();
-          if (q + j < b && act) r[j] = *reinterpret_cast<const typename R::Raw*>(fb + (size_t)cell * g.D + ch0);
+          if (q + j < pb && act) r[j] = load_slot<DT>(a.feats, a.nsum, g.D, ch0, kd, ix);
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (q + j < b) acc_row<DT>(r[j], acc);
+        for (int j = 0; j < 8; ++j) {
+          const int src = min(q + j, w1 - 1) - w0;
+          const int kd = __shfl(sv.kind, src, 64), wg = __shfl(sv.weight, src, 64);
+          if (q + j >= pb) continue;
+          acc_slot(r[j], kd, acc);
+          members += wg;
+        }
       }
+      if (chunk == 0 && lane == 0) a.bigw[blockIdx.x * 2 + slot] = members;
       if (!act) continue;
-      float* o = bigpart + ((size_t)blockIdx.x * 2 + slot) * g.D + ch0;
+      float* o = a.bigpart + ((size_t)blockIdx.x * 2 + slot) * g.D + ch0;
 #pragma unroll
       for (int v = 0; v < VEC; ++v) o[v] = acc[v];
     }
@@ -358,93 +621,101 @@ __global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, const void* 
 
 // The window in which a big cluster starts adds up its window partials in window order and stores the mean.
 template <int DT, int ODT>
-__global__ __launch_bounds__(1024) void k_reduce_big_combine(Geo g, const int32_t* __restrict__ orow,
-                                                             const int32_t* __restrict__ seg,
-                                                             const float* __restrict__ bigpart, int64_t capacity,
-                                                             void* __restrict__ merged_v) {
+__global__ __launch_bounds__(1024) void k_reduce_big_combine(Geo g, GatherArgs a) {
   constexpr int VEC = Row<DT>::VEC;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, g.N);
+  const int M = a.kdev[1];
+  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, M);
+  if (w0 >= M) return;
   int beg = -1, end = -1, row = -1;
   if (w0 + lane < w1) {
-    row = orow[w0 + lane];
-    beg = seg[row];
-    end = seg[row + 1];
+    row = a.orow[w0 + lane];
+    beg = a.seg[row];
+    end = a.seg[row + 1];
   }
   const unsigned long long starts = __ballot(end - beg > kBig && beg == w0 + lane);
   if (starts == 0) return;
   const int l = __ffsll((long long)starts) - 1;
-  const int b = __shfl(beg, l, 64), e = __shfl(end, l, 64), k = __shfl(row, l, 64);
-  if (k >= capacity) return;
+  const int e = __shfl(end, l, 64), k = __shfl(row, l, 64);
+  if (k >= a.capacity) return;
   const int wlast = (e - 1) / kBig;
+  int members = a.bigw[blockIdx.x * 2 + 1];
+  for (int w = blockIdx.x + 1; w <= wlast; ++w) members += a.bigw[w * 2];
+  if (wave == 0 && lane == 0 && a.counts) a.counts[k] = members;
   for (int chunk = wave; chunk < g.nC; chunk += nw) {
     const int ch0 = chunk * g.cch + lane * VEC;
     if (ch0 >= g.D) continue;
     float acc[VEC];
-    const float* pp = bigpart + ((size_t)blockIdx.x * 2 + 1) * g.D + ch0;
+    const float* pp = a.bigpart + ((size_t)blockIdx.x * 2 + 1) * g.D + ch0;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = pp[v];
     for (int w = blockIdx.x + 1; w <= wlast; ++w) {
-      const float* q = bigpart + ((size_t)w * 2) * g.D + ch0;
+      const float* q = a.bigpart + ((size_t)w * 2) * g.D + ch0;
 #pragma unroll
       for (int v = 0; v < VEC; ++v) acc[v] += q[v];
     }
-    store_mean<DT, ODT>(merged_v, (size_t)k * g.D + ch0, acc, 1.f / (float)(e - b));
+    store_mean<DT, ODT>(a.merged, (size_t)k * g.D + ch0, acc, 1.f / (float)members);
   }
 }
 
 size_t reduce_bigpart_floats(const Geo& g) { return (size_t)((g.N + kBig - 1) / kBig) * 2 * g.D; }
+size_t reduce_bigw_entries(const Geo& g) { return (size_t)((g.N + kBig - 1) / kBig) * 2; }
 
-// Integer plumbing of the reduce stage; leaves the sorted member list in `*order_out`.
-void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, int64_t capacity, int32_t* counts,
-                           int32_t* out_ids, int64_t* offsets, const ReduceBuffers& rb,
-                           const int32_t** order_out, hipStream_t s) {
+// Integer plumbing of the reduce stage: sorted element list, row of every list position, row starts.
+void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map,
+                           const uint8_t* node_level, int64_t capacity, int32_t* out_ids, int64_t* offsets,
+                           const ReduceBuffers& rb, hipStream_t s) {
   const int N = g.N;
-  const dim3 b256(256), gN((N + 255) / 256);
-  // ranks of the roots, K, per-video offsets, out_ids
-  exclusive_scan<1>(N, cluster_ids, rb.rank, rb.blocksum, rb.kdev, s);
-  hipLaunchKernelGGL(k_root_outputs, gN, b256, 0, s, g, cluster_ids, rb.rank, rb.kdev, capacity, out_ids,
-                     offsets);
-  // member lists: stable sort of the cells by cluster id
-  int bits = 1;
-  while ((1ll << bits) < (long long)N) ++bits;
-  const int nblocks = (N + kSortTile - 1) / kSortTile;
-  const int32_t* kin = cluster_ids;
+  const SortPlan pl = sort_plan(N);
+  const int DIG = 1 << pl.dbits;
+  const dim3 grid(pl.nb), block(kSortThreads);
+  hipLaunchKernelGGL(k_reduce_prep, grid, block, 0, s, g, cluster_ids, node_map, node_level, pl.dbits, rb.key_a,
+                     rb.rank, rb.tile_roots, rb.tile_live, rb.hist);
+  const int32_t* kin = rb.key_a;
   const int32_t* vin = nullptr;
-  int32_t* kout = rb.key_a;
-  int32_t* vout = rb.val_a;
-  int pass = 0;
-  for (int shift = 0; shift < bits; shift += kRadixBits, ++pass) {
-    hipLaunchKernelGGL(k_sort_hist, dim3(nblocks), dim3(64), 0, s, N, shift, kin, rb.hist, nblocks);
-    exclusive_scan<0>(kRadix * nblocks, rb.hist, rb.hist, rb.blocksum, (int32_t*)nullptr, s);
-    hipLaunchKernelGGL(k_sort_scatter, dim3(nblocks), dim3(64), 0, s, N, shift, kin, vin, kout, vout, rb.hist,
-                       nblocks, pass == 0 ? 1 : 0);
+  int32_t* kout = rb.key_b;
+  int32_t* vout = rb.val_b;
+  for (int pass = 0; pass < pl.passes; ++pass) {
+    const bool first = pass == 0, last = pass == pl.passes - 1;
+    if (!first)
+      hipLaunchKernelGGL(k_sort_hist, grid, block, 0, s, rb.kdev, pass * pl.dbits, pl.dbits, kin, rb.hist);
+    if (pl.prescan)
+      hipLaunchKernelGGL(k_sort_colscan, dim3((DIG + 255) / 256), dim3(256), 0, s, pl.nb, DIG, rb.hist, rb.tot);
+    SortArgs a;
+    a.n = N; a.shift = pass * pl.dbits; a.dbits = pl.dbits; a.nb = pl.nb; a.prescan = pl.prescan ? 1 : 0;
+    a.keys = kin; a.vals = vin; a.keys_out = kout; a.vals_out = last ? rb.order : vout;
+    a.hist = rb.hist; a.tot = rb.tot;
+    a.cluster_ids = cluster_ids; a.rank = rb.rank; a.tile_roots = rb.tile_roots; a.tile_live = rb.tile_live;
+    a.kdev = rb.kdev; a.out_ids = out_ids; a.offsets = offsets; a.capacity = capacity;
+    a.per_video = g.T * g.HW; a.B = g.B;
+    a.orow = rb.orow; a.seg = rb.seg;
+    if (first && last) hipLaunchKernelGGL((k_sort_pass<true, true>), grid, block, 0, s, a);
+    else if (first) hipLaunchKernelGGL((k_sort_pass<true, false>), grid, block, 0, s, a);
+    else if (last) hipLaunchKernelGGL((k_sort_pass<false, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_sort_pass<false, false>), grid, block, 0, s, a);
     kin = kout;
     vin = vout;
-    if (kout == rb.key_a) { kout = rb.key_b; vout = rb.val_b; } else { kout = rb.key_a; vout = rb.val_a; }
+    if (kout == rb.key_b) { kout = rb.key_a; vout = rb.val_a; } else { kout = rb.key_b; vout = rb.val_b; }
   }
-  // kout is now the free key buffer: it receives the output row of every sorted position
-  hipLaunchKernelGGL(k_segments, gN, b256, 0, s, N, kin, rb.rank, rb.kdev, rb.seg, kout);
-  if (counts) hipLaunchKernelGGL(k_counts, gN, b256, 0, s, rb.kdev, rb.seg, capacity, counts);
-  *order_out = vin;
-  rb.orow_out[0] = kout;
 }
 
 // The feature pass of the reduce stage (three kernels; the two for big clusters exit at once when there are none).
-void launch_reduce_gather(const Geo& g, const void* feats, int out_dtype, int64_t capacity, void* merged,
-                          const ReduceBuffers& rb, const int32_t* order, hipStream_t s) {
-  const int32_t* orow = rb.orow_out[0];
+void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
+                          const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
+                          const ReduceBuffers& rb, hipStream_t s) {
   const int nitems = (g.N + kItem - 1) / kItem;
   const int nwin = (g.N + kBig - 1) / kBig;
   const int nw = g.nC < 16 ? g.nC : 16;
   dim3 grid(nitems), gridw(nwin), block(64 * nw);
-#define STTM_REDUCE(DT, ODT)                                                                                     \
-  do {                                                                                                           \
-    hipLaunchKernelGGL((k_reduce<DT, ODT>), grid, block, 0, s, g, feats, order, orow, rb.seg, capacity, merged); \
-    hipLaunchKernelGGL((k_reduce_big_partial<DT>), gridw, block, 0, s, g, feats, order, orow, rb.seg,            \
-                       rb.bigpart);                                                                              \
-    hipLaunchKernelGGL((k_reduce_big_combine<DT, ODT>), gridw, block, 0, s, g, orow, rb.seg, rb.bigpart,         \
-                       capacity, merged);                                                                        \
+  GatherArgs a;
+  a.feats = feats; a.nsum = nsum; a.node_map = node_map; a.lvl = node_level; a.order = rb.order; a.orow = rb.orow; a.seg = rb.seg;
+  a.kdev = rb.kdev; a.capacity = capacity; a.merged = merged; a.counts = counts; a.bigpart = rb.bigpart;
+  a.bigw = rb.bigw;
+#define STTM_REDUCE(DT, ODT)                                                       \
+  do {                                                                             \
+    hipLaunchKernelGGL((k_reduce<DT, ODT>), grid, block, 0, s, g, a);              \
+    hipLaunchKernelGGL((k_reduce_big_partial<DT>), gridw, block, 0, s, g, a);      \
+    hipLaunchKernelGGL((k_reduce_big_combine<DT, ODT>), gridw, block, 0, s, g, a); \
   } while (0)
   if (g.dtype == 1) {
     if (out_dtype == 1) STTM_REDUCE(1, 1); else STTM_REDUCE(1, 0);

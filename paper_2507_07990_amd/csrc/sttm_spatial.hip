@@ -25,11 +25,13 @@ constexpr int kStatsWaves = 4;
 
 template <int DT>
 __global__ __launch_bounds__(256) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
-                                                       float* __restrict__ part, float* __restrict__ nsum) {
+                                                       float* __restrict__ part, float* __restrict__ nsum,
+                                                       SelState* __restrict__ sel) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   STTM_DYNAMIC_LDS(float, smem);
   const int chunk = blockIdx.x, f = blockIdx.y;
+  if (chunk == 0 && f % g.T == 0) sel_clear(sel + f / g.T);  // the budget search of this video starts afresh
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ch0 = chunk * g.cch + lane * VEC;
   const bool act = ch0 < g.D;
@@ -248,13 +250,14 @@ static size_t stats_lds_bytes(const Geo& g) {
   return fl * sizeof(float);
 }
 
-void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, hipStream_t s) {
+void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
+                          hipStream_t s) {
   dim3 grid(g.nC, g.F), block(256);
   size_t lds = stats_lds_bytes(g);
   if (g.dtype == 1)
-    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, lds, s, g, feats, part, nsum);
+    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, lds, s, g, feats, part, nsum, sel);
   else
-    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, lds, s, g, feats, part, nsum);
+    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, lds, s, g, feats, part, nsum, sel);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -265,8 +268,11 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* n
 __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __restrict__ part,
                                                           float* __restrict__ nrm2, float* __restrict__ sim,
                                                           float* __restrict__ m, uint32_t* __restrict__ sel_key,
-                                                          uint8_t* __restrict__ sel_w) {
+                                                          uint8_t* __restrict__ sel_w,
+                                                          SelState* __restrict__ sel) {
   STTM_DYNAMIC_LDS(float, sm);
+  __shared__ unsigned h0[kSelBins];
+  for (int j = threadIdx.x; j < kSelBins; j += blockDim.x) h0[j] = 0;
   float* s_n = sm;
   float* s_sim = sm + g.NN;
   float* s_m = sm + 2 * g.NN;
@@ -317,35 +323,44 @@ __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __
     m[fo + idx] = mv;
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
-    int lvl, by, bx;
-    node_decode(g, idx, lvl, by, bx);
-    float s = -2.f;
-    if (lvl >= 1 && node_exists(g, lvl, by, bx)) {
-      int l = lvl, y = by, x = bx;
-      while (true) {
-        const float v = s_sim[node_index(g, l, y, x)];
-        s = fmaxf(s, (v != v) ? -2.f : v);  // NaN always splits
-        if (l == g.L) break;
-        ++l; y >>= 1; x >>= 1;
+  for (int i0 = 0; i0 < g.NN; i0 += blockDim.x) {  // uniform trip count: the histogram update is wave-wide
+    const int idx = i0 + threadIdx.x;
+    uint32_t key = 0;
+    unsigned wgt = 0;
+    if (idx < g.NN) {
+      int lvl, by, bx;
+      node_decode(g, idx, lvl, by, bx);
+      float s = -2.f;
+      if (lvl >= 1 && node_exists(g, lvl, by, bx)) {
+        int l = lvl, y = by, x = bx;
+        while (true) {
+          const float v = s_sim[node_index(g, l, y, x)];
+          s = fmaxf(s, (v != v) ? -2.f : v);  // NaN always splits
+          if (l == g.L) break;
+          ++l; y >>= 1; x >>= 1;
+        }
+      }
+      // compact (value, weight) element of the budget search: upper-level nodes with >= 2 children
+      if (lvl >= 1) {
+        int kids = 0;
+        if (node_exists(g, lvl, by, bx))
+          for (int k = 0; k < 4; ++k) kids += node_exists(g, lvl - 1, 2 * by + (k >> 1), 2 * bx + (k & 1));
+        const size_t o = (size_t)f * (g.NN - g.lvl_base[1]) + (idx - g.lvl_base[1]);
+        if (kids >= 2) { key = float_key(s); wgt = (unsigned)(kids - 1); }
+        sel_key[o] = key;
+        sel_w[o] = (uint8_t)wgt;
       }
     }
-    // compact (value, weight) element of the budget search: upper-level nodes with >= 2 children
-    if (lvl >= 1) {
-      int kids = 0;
-      if (node_exists(g, lvl, by, bx))
-        for (int k = 0; k < 4; ++k) kids += node_exists(g, lvl - 1, 2 * by + (k >> 1), 2 * bx + (k & 1));
-      const size_t o = (size_t)f * (g.NN - g.lvl_base[1]) + (idx - g.lvl_base[1]);
-      sel_key[o] = kids >= 2 ? float_key(s) : 0u;
-      sel_w[o] = kids >= 2 ? (uint8_t)(kids - 1) : 0;
-    }
+    wave_hist_add(h0, wgt != 0, key >> 21, wgt);
   }
+  __syncthreads();
+  sel_flush_level0(sel + f / g.T, h0);
 }
 
 void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
-                             uint32_t* sel_key, uint8_t* sel_w, hipStream_t s) {
+                             uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s) {
   hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(256), 3 * g.NN * sizeof(float), s, g, part, nrm2, sim,
-                     m, sel_key, sel_w);
+                     m, sel_key, sel_w, sel);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -406,56 +421,38 @@ void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_lev
 
 // ------------------------------------------------------------------------------------------------
 // Budget-driven thresholds. Token count as a function of the threshold is the step function
-// K(tau) = base + sum_j w_j [v_j <= tau]. One workgroup per video finds, by an MSB-first radix select
-// (11 + 11 + 10 bits) over the order-preserving integer image of v, the smallest value whose cumulative
-// weight exceeds target - base, then the largest value below it, and takes the midpoint of the two.
+// K(tau) = base + sum_j w_j [v_j <= tau]. An MSB-first radix select (11 + 11 + 10 bits) over the
+// order-preserving integer image of v finds the smallest value whose cumulative weight exceeds
+// target - base, then the largest value below it; tau is the midpoint of the two.
+// The level-0 histogram is filled by the statistics pass of the stage; two launches follow, grid
+// (slices, videos): every workgroup re-derives the prefix found so far from the (complete) earlier
+// histograms and bins its slice under it (the second also collects the largest key below the prefix); a
+// last small launch resolves the last digit and writes tau.
 // Input: keys[video][per_video] (0 = not an element), weights (NULL = 1 for every element).
 // ------------------------------------------------------------------------------------------------
-constexpr int kSelBins = 2048;
 constexpr int kSelPer = 8;   // elements per thread and pass
 constexpr int kSelThreads = 256;
-
-// Adds w to hist[digit] for the lanes with valid set. The two most frequent leading digits of the wavefront
-// are combined before the atomic (real similarities sit in tight clusters, which would otherwise serialise
-// on one LDS word); whatever is left goes through plain LDS atomics.
-__device__ inline void wave_hist_add(unsigned* hist, bool valid, unsigned digit, unsigned w) {
-  unsigned long long todo = __ballot(valid);
-  for (int it = 0; it < 2 && todo; ++it) {
-    const int leader = __ffsll((long long)todo) - 1;
-    const unsigned d = __shfl(digit, leader, 64);
-    const bool mine = valid && digit == d;
-    const unsigned long long m = __ballot(mine);
-    const unsigned sum = __popcll(__ballot(mine && (w & 1))) + 2u * __popcll(__ballot(mine && (w & 2)));
-    if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d], sum);
-    todo &= ~m;
-  }
-  if ((todo >> (threadIdx.x & 63)) & 1ull) atomicAdd(&hist[digit], w);
-}
-
-// Per-video state of one search in global memory: three pass histograms and the largest key below the result.
-struct SelState {
-  unsigned hist[3][kSelBins];
-  unsigned lo;
-  unsigned pad[3];
-};
 
 __device__ inline int sel_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
 __device__ inline int sel_width(int pass) { return pass == 2 ? 10 : 11; }
 
 // Workgroup-wide (256 threads): the first bin of `hist` at which acc + running weight exceeds `budget`.
 // Returns false when the whole histogram fits. All threads get the same answer.
+// *below = largest non-empty bin before the found one, or -1.
 __device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long long acc,
-                                unsigned long long budget, unsigned* digit, unsigned long long* acc_out) {
+                                unsigned long long budget, unsigned* digit, unsigned long long* acc_out,
+                                int* below) {
   __shared__ unsigned long long wsum[kSelThreads / 64];
   __shared__ unsigned s_digit;
   __shared__ unsigned long long s_acc;
-  __shared__ int s_found;
+  __shared__ int s_found, s_below;
+  constexpr int PER = kSelBins / kSelThreads;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  unsigned h[kSelBins / kSelThreads];
+  unsigned h[PER];
   unsigned long long tot = 0;
 #pragma unroll
-  for (int j = 0; j < kSelBins / kSelThreads; ++j) {
-    h[j] = hist[tid * (kSelBins / kSelThreads) + j];
+  for (int j = 0; j < PER; ++j) {
+    h[j] = hist[tid * PER + j];
     tot += h[j];
   }
   unsigned long long inc = tot;
@@ -464,22 +461,29 @@ __device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long
     const unsigned long long t = __shfl_up(inc, o, 64);
     if (lane >= o) inc += t;
   }
-  if (tid == 0) s_found = 0;
+  if (tid == 0) { s_found = 0; s_below = -1; }
   if (lane == 63) wsum[wave] = inc;
   __syncthreads();
   unsigned long long ex = acc + inc - tot;
   for (int w = 0; w < wave; ++w) ex += wsum[w];
 #pragma unroll
-  for (int j = 0; j < kSelBins / kSelThreads; ++j) {
+  for (int j = 0; j < PER; ++j) {
     if (ex <= budget && ex + h[j] > budget) {
       s_found = 1;
-      s_digit = (unsigned)(tid * (kSelBins / kSelThreads) + j);
+      s_digit = (unsigned)(tid * PER + j);
       s_acc = ex;
     }
     ex += h[j];
   }
   __syncthreads();
   const bool found = s_found != 0;
+  if (found && below) {
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+      if (h[j] && tid * PER + j < (int)s_digit) atomicMax(&s_below, tid * PER + j);
+    __syncthreads();
+    *below = s_below;
+  }
   *digit = s_digit;
   *acc_out = s_acc;
   __syncthreads();
@@ -504,134 +508,140 @@ __device__ inline int sel_base(const Geo& g, int b, int base_const, const int32_
   return r;
 }
 
-// Resolves the passes before `upto`: prefix of the searched key and the weight below it.
+// Resolves the levels before `upto`: prefix of the searched key and the weight below it.
 // Returns 0 = fine, 1 = everything fits (tau = 1), 2 = even the base exceeds the target (tau = -2).
-__device__ inline int sel_resolve(const Geo& g, const SelState* st, int b, int upto, const int* target,
-                                  int base_const, const int32_t* node_map, unsigned* prefix,
-                                  unsigned long long* budget_out) {
-  const long long budget = (long long)target[b] - sel_base(g, b, base_const, node_map);
+__device__ inline int sel_resolve(const Geo& g, const SelState* st, int upto, int target, int base,
+                                  unsigned* prefix, unsigned long long* budget_out,
+                                  unsigned long long* acc_out) {
+  const long long budget = (long long)target - base;
   *prefix = 0;
   *budget_out = 0;
+  *acc_out = 0;
   if (budget < 0) return 2;
   *budget_out = (unsigned long long)budget;
   unsigned long long acc = 0;
   for (int p = 0; p < upto; ++p) {
     unsigned d;
     unsigned long long a2;
-    if (!sel_pick(st[b].hist[p], acc, (unsigned long long)budget, &d, &a2)) return 1;
+    if (!sel_pick(st->hist[p], acc, (unsigned long long)budget, &d, &a2, nullptr)) return 1;
     *prefix = (*prefix << sel_width(p)) | d;
     acc = a2;
   }
+  *acc_out = acc;
   return 0;
 }
 
-__global__ __launch_bounds__(256) void k_select_clear(SelState* st) {
-  unsigned* p = reinterpret_cast<unsigned*>(st + blockIdx.x);
-  for (int j = threadIdx.x; j < (int)(sizeof(SelState) / 4); j += blockDim.x) p[j] = 0;
+// Clears what a search leaves behind (levels 1-2, the lower neighbour, the counter); level 0 stays.
+__global__ __launch_bounds__(256) void k_select_reset(SelState* st) {
+  SelState* s = st + blockIdx.x;
+  for (int j = threadIdx.x; j < kSelBins; j += blockDim.x) s->hist[1][j] = s->hist[2][j] = 0;
+  if (threadIdx.x == 0) s->lo_out = 0;
 }
 
-// One pass: grid (slices, videos). Every workgroup re-derives the prefix found by the earlier passes from
-// their (complete) histograms, bins its slice in LDS and adds the non-empty bins to the video's histogram.
-// PASS == 3: instead of binning, the largest key below the searched one is collected.
-template <int PASS>
+template <int PASS>  // 1 or 2
 __global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32_t* __restrict__ keys,
                                                              const uint8_t* __restrict__ weights, int per_video,
                                                              const int* __restrict__ target, int base_const,
                                                              const int32_t* __restrict__ node_map,
-                                                             SelState* __restrict__ st) {
+                                                             SelState* __restrict__ states) {
   __shared__ unsigned hist[kSelBins];
   const int b = blockIdx.y, tid = threadIdx.x;
+  SelState* st = states + b;
+  const int base = sel_base(g, b, base_const, node_map);
   unsigned prefix;
-  unsigned long long budget;
-  if (sel_resolve(g, st, b, PASS < 3 ? PASS : 3, target, base_const, node_map, &prefix, &budget) != 0) return;
-  const uint32_t* kv = keys + (size_t)b * per_video;
-  const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
-  const int j0 = blockIdx.x * (kSelThreads * kSelPer);
-  uint32_t key[kSelPer];
-  unsigned w[kSelPer];
+  unsigned long long budget, acc;
+  const int rc = sel_resolve(g, st, PASS, target[b], base, &prefix, &budget, &acc);
+  if (rc == 0) {
+    const uint32_t* kv = keys + (size_t)b * per_video;
+    const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
+    const int j0 = blockIdx.x * (kSelThreads * kSelPer);
+    uint32_t key[kSelPer];
+    unsigned w[kSelPer];
 #pragma unroll
-  for (int u = 0; u < kSelPer; ++u) {
-    const int j = j0 + u * kSelThreads + tid;
-    key[u] = j < per_video ? kv[j] : 0u;
-    w[u] = 1u;
-    if (wv) w[u] = j < per_video ? wv[j] : 0u;
-    if (w[u] == 0) key[u] = 0;
-  }
-  if (PASS == 3) {
+    for (int u = 0; u < kSelPer; ++u) {
+      const int j = j0 + u * kSelThreads + tid;
+      key[u] = j < per_video ? kv[j] : 0u;
+      w[u] = 1u;
+      if (wv) w[u] = j < per_video ? wv[j] : 0u;
+      if (w[u] == 0) key[u] = 0;
+    }
+    const int shift = sel_shift(PASS), width = sel_width(PASS);
+    for (int j = tid; j < kSelBins; j += kSelThreads) hist[j] = 0;
+    __syncthreads();
     unsigned lo = 0;  // key 0 is below every real value
 #pragma unroll
-    for (int u = 0; u < kSelPer; ++u)
-      if (key[u] && key[u] < prefix && key[u] > lo) lo = key[u];
+    for (int u = 0; u < kSelPer; ++u) {
+      const unsigned top = key[u] >> (shift + width);
+      const bool valid = key[u] != 0 && top == prefix;
+      wave_hist_add(hist, valid, (key[u] >> shift) & ((1u << width) - 1u), w[u]);
+      if (PASS == 2 && key[u] != 0 && top < prefix && key[u] > lo) lo = key[u];
+    }
+    if (PASS == 2) {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) lo = max(lo, (unsigned)__shfl_xor((int)lo, o, 64));
-    if ((tid & 63) == 0 && lo) atomicMax(&st[b].lo, lo);
-    return;
+      for (int o = 32; o > 0; o >>= 1) lo = max(lo, (unsigned)__shfl_xor((int)lo, o, 64));
+      if ((tid & 63) == 0 && lo) atomicMax(&st->lo_out, lo);
+    }
+    __syncthreads();
+    for (int j = tid; j < kSelBins; j += kSelThreads)
+      if (hist[j]) atomicAdd(&st->hist[PASS][j], hist[j]);
   }
-  constexpr int P = PASS < 3 ? PASS : 0;
-  const int shift = sel_shift(P), width = sel_width(P);
-  for (int j = tid; j < kSelBins; j += kSelThreads) hist[j] = 0;
-  __syncthreads();
-#pragma unroll
-  for (int u = 0; u < kSelPer; ++u) {
-    const bool valid = key[u] != 0 && (P == 0 || (key[u] >> (shift + width)) == prefix);
-    wave_hist_add(hist, valid, (key[u] >> shift) & ((1u << width) - 1u), w[u]);
-  }
-  __syncthreads();
-  for (int j = tid; j < kSelBins; j += kSelThreads)
-    if (hist[j]) atomicAdd(&st[b].hist[P][j], hist[j]);
 }
 
 // tau = midpoint between the searched key and the largest key below it.
 __global__ __launch_bounds__(kSelThreads) void k_select_tau(Geo g, const int* __restrict__ target, int base_const,
                                                             const int32_t* __restrict__ node_map,
-                                                            const SelState* __restrict__ st,
+                                                            const SelState* __restrict__ states,
                                                             float* __restrict__ tau) {
   const int b = blockIdx.x;
-  unsigned over;
-  unsigned long long budget;
-  const int rc = sel_resolve(g, st, b, 3, target, base_const, node_map, &over, &budget);
-  if (threadIdx.x != 0) return;
-  if (rc == 2) { tau[b] = -2.f; return; }
-  if (rc == 1) { tau[b] = 1.f; return; }
-  const float hi = key_float(over);
-  const float lof = st[b].lo ? key_float(st[b].lo) : -2.f;
-  float mid = 0.5f * (lof + hi);
-  if (!(mid < hi)) mid = lof;
-  tau[b] = mid;
+  const SelState* st = states + b;
+  const int base = sel_base(g, b, base_const, node_map);
+  unsigned prefix;
+  unsigned long long budget, acc;
+  const int rc = sel_resolve(g, st, 2, target[b], base, &prefix, &budget, &acc);
+  float t = 1.f;
+  if (rc == 2) {
+    t = -2.f;
+  } else if (rc == 0) {
+    unsigned d2;
+    unsigned long long a2;
+    int below;
+    if (sel_pick(st->hist[2], acc, budget, &d2, &a2, &below)) {
+      const unsigned over = (prefix << 10) | d2;
+      const unsigned lo_key = below >= 0 ? ((prefix << 10) | (unsigned)below) : st->lo_out;
+      const float hi = key_float(over);
+      const float lof = lo_key ? key_float(lo_key) : -2.f;
+      t = 0.5f * (lof + hi);
+      if (!(t < hi)) t = lof;
+    }
+  }
+  if (threadIdx.x == 0) tau[b] = t;
 }
 
-size_t select_state_bytes(int B) { return (size_t)B * sizeof(SelState); }
-
 static void launch_select(const Geo& g, const uint32_t* keys, const uint8_t* weights, int per_video,
-                          const int* target, int base_const, const int32_t* node_map, void* state, float* tau,
-                          hipStream_t s) {
-  SelState* st = static_cast<SelState*>(state);
-  const int slices = (per_video + kSelThreads * kSelPer - 1) / (kSelThreads * kSelPer);
+                          const int* target, int base_const, const int32_t* node_map, SelState* st, bool dirty,
+                          float* tau, hipStream_t s) {
+  const int slices = per_video > 0 ? (per_video + kSelThreads * kSelPer - 1) / (kSelThreads * kSelPer) : 1;
   const dim3 grid(slices, g.B), block(kSelThreads);
-  hipLaunchKernelGGL(k_select_clear, dim3(g.B), block, 0, s, st);
-  hipLaunchKernelGGL(k_select_pass<0>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
-                     node_map, st);
+  if (dirty) hipLaunchKernelGGL(k_select_reset, dim3(g.B), dim3(256), 0, s, st);
   hipLaunchKernelGGL(k_select_pass<1>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
                      node_map, st);
   hipLaunchKernelGGL(k_select_pass<2>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
-                     node_map, st);
-  hipLaunchKernelGGL(k_select_pass<3>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
                      node_map, st);
   hipLaunchKernelGGL(k_select_tau, dim3(g.B), block, 0, s, g, target, base_const, node_map, st, tau);
 }
 
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
-                           void* state, float* tau, hipStream_t s) {
+                           SelState* state, bool dirty, float* tau, hipStream_t s) {
   int roots = 0;
   for (int ry = 0; ry < g.R; ++ry)
     for (int rx = 0; rx < g.R; ++rx) roots += node_exists(g, g.L, ry, rx);
   const int per_video = g.T * (g.NN - g.lvl_base[1]);
-  launch_select(g, keys, weights, per_video, target, roots * g.T, nullptr, state, tau, s);
+  launch_select(g, keys, weights, per_video, target, roots * g.T, nullptr, state, dirty, tau, s);
 }
 
 void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
-                            void* state, float* tau, hipStream_t s) {
-  launch_select(g, keys, nullptr, g.T * g.HW, target, 0, node_map, state, tau, s);
+                            SelState* state, bool dirty, float* tau, hipStream_t s) {
+  launch_select(g, keys, nullptr, g.T * g.HW, target, 0, node_map, state, dirty, tau, s);
 }
 
 }  // namespace sttm

@@ -75,7 +75,8 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __restrict__ feats_v,
                                                        const uint8_t* __restrict__ node_level,
                                                        const float* __restrict__ nsum,
-                                                       float* __restrict__ pd_part) {
+                                                       float* __restrict__ pd_part,
+                                                       SelState* __restrict__ sel) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   STTM_DYNAMIC_LDS(float, bigS);  // [big join blocks][cch]
@@ -90,6 +91,7 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int H = g.H, W = g.W, HW = g.HW;
   const int NB = g.NN - g.lvl_base[3];
+  if (chunk == 0 && t == 1) sel_clear(sel + b);  // the temporal budget search of this video starts afresh
   if (threadIdx.x == 0) { nfast = nmid = nbig = n0 = nX = 0; }
   for (int c = threadIdx.x; c < HW; c += blockDim.x) {
     lvl_t[c] = node_level[(size_t)f * HW + c];
@@ -322,16 +324,21 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
   }
 }
 
+__global__ __launch_bounds__(256) void k_select_clear_all(SelState* st) { sel_clear(st + blockIdx.x); }
+
 void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
-                          float* pd_part, hipStream_t s) {
-  if (g.T < 2) return;
+                          float* pd_part, SelState* sel, hipStream_t s) {
+  if (g.T < 2) {  // no frame pairs: only the search states have to be reset
+    hipLaunchKernelGGL(k_select_clear_all, dim3(g.B), dim3(256), 0, s, sel);
+    return;
+  }
   dim3 grid(g.nC, g.B * (g.T - 1)), block(256);
   const int U = g.P >= 8 ? g.P >> 3 : 1;
   const size_t lds = g.L >= 3 ? (size_t)U * U * g.cch * sizeof(float) : 0;
   if (g.dtype == 1)
-    hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, lds, s, g, feats, node_level, nsum, pd_part);
+    hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
   else
-    hipLaunchKernelGGL(k_temporal_dots<0>, grid, block, lds, s, g, feats, node_level, nsum, pd_part);
+    hipLaunchKernelGGL(k_temporal_dots<0>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
 }
 
 __device__ inline int node_idx_of(const Geo& g, int lvl, int y0, int x0) {
@@ -367,9 +374,11 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* 
                                                           const float* __restrict__ pd_part,
                                                           const float* __restrict__ nrm2,
                                                           float* __restrict__ sig, float* __restrict__ e,
-                                                          uint32_t* __restrict__ sel_key) {
+                                                          uint32_t* __restrict__ sel_key,
+                                                          SelState* __restrict__ sel) {
   __shared__ PairFrame pf;
   __shared__ unsigned ekey[1024];
+  __shared__ unsigned h0[kSelBins];
   const int f = blockIdx.x, HW = g.HW, W = g.W;
   if (f % g.T == 0) {
     for (int c = threadIdx.x; c < HW; c += blockDim.x) sel_key[(size_t)f * HW + c] = 0;
@@ -377,6 +386,7 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* 
   }
   load_pair_frame(g, f, node_map, node_level, pf);
   for (int c = threadIdx.x; c < HW; c += blockDim.x) ekey[c] = 0;
+  for (int j = threadIdx.x; j < kSelBins; j += blockDim.x) h0[j] = 0;
   __syncthreads();
   for (int c = threadIdx.x; c < HW; c += blockDim.x) {
     const int a = pf.lvl_t[c], b = pf.lvl_p[c];
@@ -391,20 +401,29 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* 
     if (v == v) atomicMax(&ekey[n], float_key(v));
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < HW; c += blockDim.x) {
-    const size_t i = (size_t)f * HW + c;
-    if (pf.rep_t[c] != c) { sel_key[i] = 0; continue; }
-    const unsigned k = ekey[c];                 // 0 only if every similarity was NaN
-    e[i] = k ? key_float(k) : -2.f;
-    sel_key[i] = k ? k : float_key(-2.f);
+  for (int c0 = 0; c0 < HW; c0 += blockDim.x) {  // uniform trip count: the histogram update is wave-wide
+    const int c = c0 + threadIdx.x;
+    unsigned key = 0;
+    if (c < HW) {
+      const size_t i = (size_t)f * HW + c;
+      if (pf.rep_t[c] == c) {
+        const unsigned k = ekey[c];                 // 0 only if every similarity was NaN
+        e[i] = k ? key_float(k) : -2.f;
+        key = k ? k : float_key(-2.f);
+      }
+      sel_key[i] = key;
+    }
+    wave_hist_add(h0, key != 0, key >> 21, 1u);
   }
+  __syncthreads();
+  sel_flush_level0(sel + f / g.T, h0);
 }
 
 void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
                              const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
-                             hipStream_t s) {
+                             SelState* sel, hipStream_t s) {
   hipLaunchKernelGGL(k_temporal_resolve, dim3(g.F), dim3(256), 0, s, g, node_map, node_level, pd_part, nrm2, sig,
-                     e, sel_key);
+                     e, sel_key, sel);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -469,11 +488,15 @@ __global__ __launch_bounds__(256) void k_root_jump(int n, const int32_t* __restr
   dst[i] = p;
 }
 
-__global__ __launch_bounds__(256) void k_cluster_ids(int n, const int32_t* __restrict__ root,
-                                                     const int32_t* __restrict__ node_map,
-                                                     int32_t* __restrict__ cluster_ids) {
+// Last round, taken from every cell's node: cluster id = root of the node covering the cell.
+__global__ __launch_bounds__(256) void k_root_jump_cells(int n, int hops, const int32_t* __restrict__ src,
+                                                         const int32_t* __restrict__ node_map,
+                                                         int32_t* __restrict__ cluster_ids) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) cluster_ids[i] = root[node_map[i]];
+  if (i >= n) return;
+  int p = node_map[i];
+  for (int h = 0; h < hops; ++h) p = src[p];
+  cluster_ids[i] = p;
 }
 
 void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* node_map, int32_t* cluster_ids,
@@ -483,11 +506,12 @@ void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* n
   dim3 grid((g.N + 255) / 256), block(256);
   int32_t* src = ptr_a;
   int32_t* dst = ptr_b;
-  for (int r = 0; r < rounds; ++r) {
+  for (int r = 0; r + 1 < rounds; ++r) {
     hipLaunchKernelGGL(k_root_jump, grid, block, 0, s, g.N, src, dst);
     int32_t* tmp = src; src = dst; dst = tmp;
   }
-  hipLaunchKernelGGL(k_cluster_ids, grid, block, 0, s, g.N, src, node_map, cluster_ids);
+  hipLaunchKernelGGL(k_root_jump_cells, grid, block, 0, s, g.N, rounds > 0 ? kHops : 0, src, node_map,
+                     cluster_ids);
 }
 
 }  // namespace sttm

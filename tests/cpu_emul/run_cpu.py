@@ -37,7 +37,7 @@ def load():
     return lib
 
 
-def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, lib=None):
+def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, lib=None, use_nodes=True):
     lib = lib or load()
     B, T, H, W, D = feats.shape
     dt = STTM_BF16 if feats.dtype == np.uint16 else STTM_F32
@@ -102,8 +102,9 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     out_ids = np.zeros(N, np.int32)
     offsets = np.zeros(B + 1, np.int64)
     n = C.c_int64(-1)
-    chk(lib.sttm_reduce(h, _p(x), _p(cluster), out_dtype, C.c_int64(N), _p(merged), _p(counts), _p(out_ids),
-                        _p(offsets), C.byref(n)))
+    chk(lib.sttm_reduce(h, _p(x), _p(cluster), _p(node_map) if use_nodes else None,
+                        _p(node_level) if use_nodes else None, out_dtype, C.c_int64(N), _p(merged), _p(counts),
+                        _p(out_ids), _p(offsets), C.byref(n)))
     K = int(n.value)
     r.K = K
     if out_dtype == STTM_BF16:

@@ -45,7 +45,8 @@ def _to_dev(feats: np.ndarray):
 
 
 def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_grid: int = 1,
-            out_dtype: Optional[int] = None, node_map_override=None, ctx=None, feats_dev=None) -> GpuResult:
+            out_dtype: Optional[int] = None, node_map_override=None, ctx=None, feats_dev=None,
+            use_nodes: bool = True) -> GpuResult:
     """Whole path through the C ABI. Fixed thresholds, or `keep` (budget mode)."""
     import torch
     B, T, H, W, D = feats.shape
@@ -105,7 +106,8 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     counts = torch.zeros(N, dtype=torch.int32, device=dev)
     out_ids = torch.zeros(N, dtype=torch.int32, device=dev)
     offsets = torch.zeros(B + 1, dtype=torch.int64, device=dev)
-    K = s.sttm_reduce(x, cluster, out_dtype, N, merged, counts, out_ids, offsets)
+    K = s.sttm_reduce(x, cluster, node_map if use_nodes else None, node_level if use_nodes else None, out_dtype, N,
+                      merged, counts, out_ids, offsets)
     _trace("reduce stage")
     r.K = K
     r.merged = merged[:K].float().cpu().numpy()

@@ -179,7 +179,7 @@ def test_error_paths(lib):
     s.sttm_spatial_quadtree(x, lib.STTM_F32, 1, 2, 8, 8, 16, 1, [1.0], nm)
     s.sttm_temporal_merge(x, nm, None, [1.0], cl)
     with pytest.raises(lib.SttmError) as e:
-        s.sttm_reduce(x, cl, lib.STTM_F32, 4, merged, None, None, off)
+        s.sttm_reduce(x, cl, None, None, lib.STTM_F32, 4, merged, None, None, off)
     assert e.value.code == lib.STTM_ERR_CAPACITY and int(off[1].item()) == 128
     torch.cuda.synchronize()
     np.testing.assert_array_equal(merged.cpu().numpy(), x.view(128, 16)[:4].cpu().numpy())
