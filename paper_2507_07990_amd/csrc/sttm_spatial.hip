@@ -7,100 +7,182 @@ namespace sttm {
 // ------------------------------------------------------------------------------------------------
 // k_pyramid_stats: the one pass over the features of the spatial stage.
 //
-// Grid (chunk, frame); a workgroup is 4 wavefronts. A lane owns VEC consecutive channels of one chunk
-// of the token rows, so all pyramid sums are private to the lane and only the scalars (squared norms,
-// parent-child dot products) are reduced across lanes: each wavefront stages its per-lane partial
-// scalars in LDS as [scalar][lane] and then lets lane r add up row r.
-// A wavefront walks "units" = 8x8 cell blocks (level 3) quadrant by quadrant: 4 tiles (4x4, level 2)
-// of 4 level-1 blocks of 4 cells. Levels above 3 are finished by the whole workgroup from the
-// per-channel level-3 sums kept in LDS.
-// Output: part[f][chunk][0][node] = partial squared norm of the node's sum over this chunk's channels,
-//         part[f][chunk][1][node] = partial dot product of the node's sum with its parent's sum,
-//         nsum[f][node - first level-3 node][D] = the per-channel sums of the nodes at levels >= 3 (fp32),
-//         which the later stages read instead of re-adding up to P*P token rows.
+// Grid (chunk, unit, frame); a workgroup is ONE wavefront that owns a "unit" = an 8x8 cell block (level 3)
+// of one frame for one chunk of the token rows. Units at the ragged edge of the grid are smaller, but every
+// workgroup is a single wavefront, so the hardware dispatcher evens the load out. A lane owns VEC
+// consecutive channels, so all pyramid sums are private to the lane and only scalars are reduced across
+// lanes: the wavefront stages its per-lane partial scalars in LDS as [scalar][lane] and then lets lane r
+// add up row r.
+// The unit is walked quadrant by quadrant: 4 tiles (4x4, level 2) of 4 level-1 blocks of 4 cells. The row
+// loads of the next tile are issued before the current one is worked on; cells and blocks beyond the
+// grid's edge cost neither loads nor arithmetic (the tests are wave-uniform).
+// Scalars: the squared norm of every cell, and for every node below the root the dot product of its sum
+// with its parent's sum. (The squared norm of a parent is the sum of its children's dot products with it,
+// which the finalize kernel adds up.)
+// Output: part[f][chunk][0][cell node] = partial squared norm over this chunk's channels,
+//         part[f][chunk][1][node]      = partial dot product of the node's sum with its parent's sum
+//         (levels 0..2 here; level 3 and above by k_pyramid_upper when the pyramid is taller than a unit),
+//         nsum[f][node - first level-3 node][D] = the per-channel sums of the level-3 nodes (fp32), which
+//         the later stages read instead of re-adding up to 64 token rows.
 // ------------------------------------------------------------------------------------------------
-constexpr int kTileRows = 40;    // 16 n0 + 16 d0 + 4 n1 + 4 d1
+constexpr int kTileRows = 36;    // 16 n0 + 16 d0 + 4 d1
 constexpr int kRowStride = 68;   // 64 lanes + pad, keeps 16-byte alignment of every row
-constexpr int kStatsWaves = 4;
 
+// Issues the row loads of the tile whose top-left cell is (ty, tx); th x tw of its 4x4 cells are valid.
 template <int DT>
-__global__ __launch_bounds__(256) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
-                                                       float* __restrict__ part, float* __restrict__ nsum,
-                                                       SelState* __restrict__ sel) {
+__device__ __forceinline__ void tile_load(typename Row<DT>::Raw (&raw)[16], const typename Row<DT>::Elem* fbase,
+                                          int W, int D, int ty, int tx, int th, int tw, bool act) {
+  typedef Row<DT> R;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int q1 = i >> 2, k = i & 3;
+    const int dy = (q1 >> 1) * 2 + (k >> 1), dx = (q1 & 1) * 2 + (k & 1);
+    raw[i] = R::zero();
+    if (dy < th && dx < tw && act)
+      raw[i] = *reinterpret_cast<const typename R::Raw*>(fbase + (size_t)((ty + dy) * W + tx + dx) * D);
+  }
+}
+
+// Sums and scalars of one tile; returns the tile's per-channel sum in S2. Writes the scalars of the tile's
+// cells and level-1 blocks to the per-chunk tables.
+template <int DT>
+__device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>::Raw (&raw)[16], float* tb,
+                                           int lane, int ty, int tx, int th, int tw, float* pn,
+                                           float* pd, float (&S2)[Row<DT>::VEC]) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
-  STTM_DYNAMIC_LDS(float, smem);
-  const int chunk = blockIdx.x, f = blockIdx.y;
-  if (chunk == 0 && f % g.T == 0) sel_clear(sel + f / g.T);  // the budget search of this video starts afresh
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+  for (int v = 0; v < VEC; ++v) S2[v] = 0.f;
+  float S1[4][VEC];
+#pragma unroll
+  for (int q1 = 0; q1 < 4; ++q1) {
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) S1[q1][v] = 0.f;
+    if ((q1 >> 1) * 2 >= th || (q1 & 1) * 2 >= tw) continue;  // block beyond the edge (wave-uniform)
+    float x[4][VEC];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) R::unpack(raw[q1 * 4 + k], x[k]);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) S1[q1][v] = (x[0][v] + x[1][v]) + (x[2][v] + x[3][v]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if ((q1 >> 1) * 2 + (k >> 1) >= th || (q1 & 1) * 2 + (k & 1) >= tw) continue;
+      float n0 = 0.f, d0 = 0.f;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) {
+        n0 = fmaf(x[k][v], x[k][v], n0);
+        d0 = fmaf(x[k][v], S1[q1][v], d0);
+      }
+      tb[(q1 * 4 + k) * kRowStride + lane] = n0;
+      tb[(16 + q1 * 4 + k) * kRowStride + lane] = d0;
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) S2[v] += S1[q1][v];
+  }
+#pragma unroll
+  for (int q1 = 0; q1 < 4; ++q1) {
+    if ((q1 >> 1) * 2 >= th || (q1 & 1) * 2 >= tw) continue;
+    float d1 = 0.f;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) d1 = fmaf(S1[q1][v], S2[v], d1);
+    tb[(32 + q1) * kRowStride + lane] = d1;
+  }
+  wave_lds_fence();
+  if (lane < kTileRows) {
+    // which node / table does row `lane` belong to
+    const int r = lane;
+    int lvl, dy, dx;
+    bool is_dot;
+    if (r < 32) {
+      is_dot = r >= 16;
+      const int q1 = (r & 15) >> 2, k = r & 3;
+      lvl = 0;
+      dy = (q1 >> 1) * 2 + (k >> 1);
+      dx = (q1 & 1) * 2 + (k & 1);
+    } else {
+      is_dot = true;
+      const int q1 = r - 32;
+      lvl = 1;
+      dy = (q1 >> 1) * 2;
+      dx = (q1 & 1) * 2;
+    }
+    if (dy < th && dx < tw && !(is_dot && lvl >= g.L) && lvl <= g.L) {
+      const float4* row = reinterpret_cast<const float4*>(tb + r * kRowStride);
+      float acc = 0.f;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        float4 q = row[j];
+        acc += (q.x + q.y) + (q.z + q.w);
+      }
+      (is_dot ? pd : pn)[node_index(g, lvl, (ty + dy) >> lvl, (tx + dx) >> lvl)] = acc;
+    }
+  }
+  wave_lds_fence();
+}
+
+constexpr int kFramesPerWave = 1;  // a wavefront walks the same unit of this many consecutive frames
+
+template <int DT>
+__global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
+                                                      float* __restrict__ part, float* __restrict__ nsum,
+                                                      SelState* __restrict__ sel) {
+  typedef Row<DT> R;
+  constexpr int VEC = R::VEC;
+  __shared__ float tb[kTileRows * kRowStride];
+  const int chunk = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+  const int f0 = blockIdx.z * kFramesPerWave, f1 = min(f0 + kFramesPerWave, g.F);
   const int ch0 = chunk * g.cch + lane * VEC;
   const bool act = ch0 < g.D;
-  const int H = g.H, W = g.W, P = g.P, L = g.L;
-  float* tb = smem + wave * (kTileRows * kRowStride);
-  float* s3buf = smem + kStatsWaves * (kTileRows * kRowStride);
-  float* pn = part + (size_t)(f * g.nC + chunk) * 2 * g.NN;
-  float* pd = pn + g.NN;
+  const int H = g.H, W = g.W, L = g.L;
+  const size_t frame_elems = (size_t)g.HW * g.D;
   const typename R::Elem* fbase =
-      reinterpret_cast<const typename R::Elem*>(feats_v) + (size_t)f * g.HW * g.D + (act ? ch0 : 0);
-  const int U = P >= 8 ? (P >> 3) : 1;
+      reinterpret_cast<const typename R::Elem*>(feats_v) + (size_t)f0 * frame_elems + (act ? ch0 : 0);
+  const int UX = (W + 7) >> 3;  // units per row that hold valid cells
+  const int y3 = (u / UX) * 8, x3 = (u % UX) * 8;
+  const int vh = min(8, H - y3), vw = min(8, W - x3);  // valid rows / columns of the unit
 
-  for (int u = wave; u < U * U; u += kStatsWaves) {
-    const int y3 = (u / U) * 8, x3 = (u % U) * 8;
-    float S3[VEC];
+  typename R::Raw bufA[16], bufB[16];
+  tile_load<DT>(bufA, fbase, W, g.D, y3, x3, min(vh, 4), min(vw, 4), act);
+  for (int f = f0; f < f1; ++f, fbase += frame_elems) {
+    if (chunk == 0 && u == 0 && f % g.T == 0) sel_clear(sel + f / g.T);  // this video's budget search starts afresh
+    float* pn = part + (size_t)(f * g.nC + chunk) * 2 * g.NN;
+    float* pd = pn + g.NN;
+    float S3[VEC], S2[4][VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) S3[v] = 0.f;
-    if (y3 < H && x3 < W) {
-      float S2[4][VEC];
 #pragma unroll
-      for (int q2 = 0; q2 < 4; ++q2) {
-        const int ty = y3 + (q2 >> 1) * 4, tx = x3 + (q2 & 1) * 4;
+    for (int q2 = 0; q2 < 4; ++q2) {
+      const int ty = y3 + (q2 >> 1) * 4, tx = x3 + (q2 & 1) * 4;
+      const int th = max(0, min(4, vh - (q2 >> 1) * 4)), tw = max(0, min(4, vw - (q2 & 1) * 4));
+      {  // the next tile's rows (the first tile of the next frame after the last one) fly while this one is worked on
+        const int n = (q2 + 1) & 3;
+        const typename R::Elem* nb = q2 < 3 ? fbase : fbase + frame_elems;
+        int nh = max(0, min(4, vh - (n >> 1) * 4)), nw = max(0, min(4, vw - (n & 1) * 4));
+        if (nh == 0 || nw == 0 || (q2 == 3 && f + 1 >= f1)) nh = nw = 0;
+        tile_load<DT>((q2 & 1) ? bufA : bufB, nb, W, g.D, y3 + (n >> 1) * 4, x3 + (n & 1) * 4, nh, nw, act);
+      }
+      if (th > 0 && tw > 0) {
+        tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, ty, tx, th, tw, pn, pd, S2[q2]);
+      } else {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) S2[q2][v] = 0.f;
-        if (ty >= H || tx >= W) continue;  // wave-uniform
-        typename R::Raw raw[16];
+      }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int q1 = i >> 2, k = i & 3;
-          const int y = ty + (q1 >> 1) * 2 + (k >> 1), x = tx + (q1 & 1) * 2 + (k & 1);
-          raw[i] = R::zero();
-          if (y < H && x < W && act)
-            raw[i] = *reinterpret_cast<const typename R::Raw*>(fbase + (size_t)(y * W + x) * g.D);
-        }
-        float S1[4][VEC];
+      for (int v = 0; v < VEC; ++v) S3[v] += S2[q2][v];
+    }
+    // level-2 dot products of the four tiles with the unit's sum
+    if (L >= 3) {
 #pragma unroll
-        for (int q1 = 0; q1 < 4; ++q1) {
-          float x[4][VEC];
+      for (int q2 = 0; q2 < 4; ++q2) {
+        float d2 = 0.f;
 #pragma unroll
-          for (int k = 0; k < 4; ++k) R::unpack(raw[q1 * 4 + k], x[k]);
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) S1[q1][v] = (x[0][v] + x[1][v]) + (x[2][v] + x[3][v]);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            float n0 = 0.f, d0 = 0.f;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-              n0 = fmaf(x[k][v], x[k][v], n0);
-              d0 = fmaf(x[k][v], S1[q1][v], d0);
-            }
-            tb[(q1 * 4 + k) * kRowStride + lane] = n0;
-            tb[(16 + q1 * 4 + k) * kRowStride + lane] = d0;
-          }
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) S2[q2][v] += S1[q1][v];
-        }
-#pragma unroll
-        for (int q1 = 0; q1 < 4; ++q1) {
-          float n1 = 0.f, d1 = 0.f;
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) {
-            n1 = fmaf(S1[q1][v], S1[q1][v], n1);
-            d1 = fmaf(S1[q1][v], S2[q2][v], d1);
-          }
-          tb[(32 + q1) * kRowStride + lane] = n1;
-          tb[(36 + q1) * kRowStride + lane] = d1;
-        }
-        wave_lds_fence();
-        if (lane < kTileRows) {
+        for (int v = 0; v < VEC; ++v) d2 = fmaf(S2[q2][v], S3[v], d2);
+        tb[q2 * kRowStride + lane] = d2;
+      }
+      wave_lds_fence();
+      if (lane < 4) {
+        const int q2 = lane;
+        if ((q2 >> 1) * 4 < vh && (q2 & 1) * 4 < vw) {
           const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
           float acc = 0.f;
 #pragma unroll
@@ -108,156 +190,81 @@ __global__ __launch_bounds__(256) void k_pyramid_stats(Geo g, const void* __rest
             float4 q = row[j];
             acc += (q.x + q.y) + (q.z + q.w);
           }
-          // which node / table does row `lane` belong to
-          int r = lane, lvl, by, bx;
-          bool is_dot;
-          if (r < 32) {
-            is_dot = r >= 16;
-            const int q1 = (r & 15) >> 2, k = r & 3;
-            lvl = 0;
-            by = ty + (q1 >> 1) * 2 + (k >> 1);
-            bx = tx + (q1 & 1) * 2 + (k & 1);
-          } else {
-            is_dot = r >= 36;
-            const int q1 = (r - 32) & 3;
-            lvl = 1;
-            by = (ty >> 1) + (q1 >> 1);
-            bx = (tx >> 1) + (q1 & 1);
-          }
-          const int side = P >> lvl;
-          if (lvl <= L && by < side && bx < side && !(is_dot && lvl >= L))
-            (is_dot ? pd : pn)[node_index(g, lvl, by, bx)] = acc;
+          pd[node_index(g, 2, (y3 >> 2) + (q2 >> 1), (x3 >> 2) + (q2 & 1))] = acc;
         }
-        wave_lds_fence();
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) S3[v] += S2[q2][v];
-      }
-      // level-2 scalars of the four tiles and the level-3 norm of the unit
-#pragma unroll
-      for (int q2 = 0; q2 < 4; ++q2) {
-        float n2 = 0.f, d2 = 0.f;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-          n2 = fmaf(S2[q2][v], S2[q2][v], n2);
-          d2 = fmaf(S2[q2][v], S3[v], d2);
-        }
-        tb[q2 * kRowStride + lane] = n2;
-        tb[(4 + q2) * kRowStride + lane] = d2;
-      }
-      {
-        float n3 = 0.f;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) n3 = fmaf(S3[v], S3[v], n3);
-        tb[8 * kRowStride + lane] = n3;
       }
       wave_lds_fence();
-      if (lane < 9) {
-        const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
-        float acc = 0.f;
+      if (act) {
+        float* o = nsum + ((size_t)f * (g.NN - g.lvl_base[3]) + (y3 >> 3) * (g.P >> 3) + (x3 >> 3)) * g.D + ch0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          float4 q = row[j];
-          acc += (q.x + q.y) + (q.z + q.w);
-        }
-        int lvl, by, bx;
-        bool is_dot = false;
-        if (lane < 8) {
-          const int q2 = lane & 3;
-          is_dot = lane >= 4;
-          lvl = 2;
-          by = (y3 >> 2) + (q2 >> 1);
-          bx = (x3 >> 2) + (q2 & 1);
-        } else {
-          lvl = 3;
-          by = y3 >> 3;
-          bx = x3 >> 3;
-        }
-        const int side = P >> lvl;
-        if (lvl <= L && by < side && bx < side && !(is_dot && lvl >= L))
-          (is_dot ? pd : pn)[node_index(g, lvl, by, bx)] = acc;
+        for (int v = 0; v < VEC; v += 4)
+          *reinterpret_cast<float4*>(o + v) = make_float4(S3[v], S3[v + 1], S3[v + 2], S3[v + 3]);
       }
-      wave_lds_fence();
-    }
-    if (L > 3) {
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) s3buf[u * g.cch + lane * VEC + v] = S3[v];
-    }
-    if (L >= 3 && y3 < H && x3 < W && act) {
-      float* o = nsum + ((size_t)f * (g.NN - g.lvl_base[3]) + (y3 >> 3) * (P >> 3) + (x3 >> 3)) * g.D + ch0;
-#pragma unroll
-      for (int v = 0; v < VEC; v += 4)
-        *reinterpret_cast<float4*>(o + v) = make_float4(S3[v], S3[v + 1], S3[v + 2], S3[v + 3]);
-    }
-  }
-
-  if (L > 3) {
-    // Levels 4..L from the per-channel level-3 sums: thread t owns channels t, t+256, ...
-    __shared__ float red[kStatsWaves][5];
-    __syncthreads();
-    float* child = s3buf;
-    float* cur = s3buf + U * U * g.cch;
-    for (int lvl = 4; lvl <= L; ++lvl) {
-      const int G = P >> lvl, Gc = G * 2;
-      for (int nd = 0; nd < G * G; ++nd) {
-        const int by = nd / G, bx = nd % G;
-        float tot[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int c = threadIdx.x; c < g.cch; c += 256) {
-          float a[4];
-#pragma unroll
-          for (int k = 0; k < 4; ++k)
-            a[k] = child[((2 * by + (k >> 1)) * Gc + 2 * bx + (k & 1)) * g.cch + c];
-          const float S = (a[0] + a[1]) + (a[2] + a[3]);
-          cur[nd * g.cch + c] = S;
-          if (chunk * g.cch + c < g.D)
-            nsum[((size_t)f * (g.NN - g.lvl_base[3]) + node_index(g, lvl, by, bx) - g.lvl_base[3]) * g.D +
-                 chunk * g.cch + c] = S;
-          tot[0] = fmaf(S, S, tot[0]);
-#pragma unroll
-          for (int k = 0; k < 4; ++k) tot[1 + k] = fmaf(a[k], S, tot[1 + k]);
-        }
-#pragma unroll
-        for (int j = 0; j < 5; ++j) {
-          const float r = wave_sum(tot[j]);
-          if (lane == 0) red[wave][j] = r;
-        }
-        __syncthreads();
-        if (threadIdx.x < 5) {
-          const int j = threadIdx.x;
-          const float r = (red[0][j] + red[1][j]) + (red[2][j] + red[3][j]);
-          if (j == 0) {
-            pn[node_index(g, lvl, by, bx)] = r;
-          } else {
-            const int k = j - 1;
-            pd[node_index(g, lvl - 1, 2 * by + (k >> 1), 2 * bx + (k & 1))] = r;
-          }
-        }
-        __syncthreads();
-      }
-      child = cur;
-      cur = cur + G * G * g.cch;
     }
   }
 }
 
-static size_t stats_lds_bytes(const Geo& g) {
-  size_t fl = (size_t)kStatsWaves * kTileRows * kRowStride;
-  if (g.L > 3) {
-    int U = g.P >> 3;
-    size_t nodes = (size_t)U * U;
-    for (int lvl = 4; lvl <= g.L; ++lvl) nodes += (size_t)(g.P >> lvl) * (g.P >> lvl);
-    fl += nodes * g.cch;
+// ------------------------------------------------------------------------------------------------
+// k_pyramid_upper: levels 4..L from the stored level-3 sums, one wavefront per (chunk, frame); a lane owns
+// four channels (the chunk is covered in VEC/4 sweeps). For every node: the sum of its existing children
+// (stored next to the level-3 sums) and the partial dot product of every child with it, in the same
+// per-chunk tables as above.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_pyramid_upper(Geo g, float* __restrict__ part, float* __restrict__ nsum) {
+  const int chunk = blockIdx.x, f = blockIdx.y, lane = threadIdx.x;
+  const int NB = g.NN - g.lvl_base[3];
+  float* pd = part + (size_t)(f * g.nC + chunk) * 2 * g.NN + g.NN;
+  float* rows = nsum + (size_t)f * NB * g.D;
+  for (int lvl = 4; lvl <= g.L; ++lvl) {
+    const int G = g.P >> lvl;
+    for (int nd = 0; nd < G * G; ++nd) {
+      const int by = nd / G, bx = nd - by * G;
+      if (!node_exists(g, lvl, by, bx)) continue;  // wave-uniform
+      float tot[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int c = lane * 4; c < g.cch; c += 256) {
+        const int ch = chunk * g.cch + c;
+        if (ch >= g.D) continue;
+        float4 a[4];
+        float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
+          a[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (node_exists(g, lvl - 1, cy, cx))
+            a[k] = *reinterpret_cast<const float4*>(rows + (size_t)(node_index(g, lvl - 1, cy, cx) - g.lvl_base[3]) * g.D + ch);
+        }
+        S.x = (a[0].x + a[1].x) + (a[2].x + a[3].x);
+        S.y = (a[0].y + a[1].y) + (a[2].y + a[3].y);
+        S.z = (a[0].z + a[1].z) + (a[2].z + a[3].z);
+        S.w = (a[0].w + a[1].w) + (a[2].w + a[3].w);
+        *reinterpret_cast<float4*>(rows + (size_t)(node_index(g, lvl, by, bx) - g.lvl_base[3]) * g.D + ch) = S;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          tot[k] = fmaf(a[k].x, S.x, fmaf(a[k].y, S.y, fmaf(a[k].z, S.z, fmaf(a[k].w, S.w, tot[k]))));
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) tot[j] = wave_sum(tot[j]);
+      if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
+          if (node_exists(g, lvl - 1, cy, cx)) pd[node_index(g, lvl - 1, cy, cx)] = tot[k];
+        }
+      }
+    }
+    // the next level reads back, lane by lane, exactly the channels this lane has just stored
   }
-  return fl * sizeof(float);
 }
 
 void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
                           hipStream_t s) {
-  dim3 grid(g.nC, g.F), block(256);
-  size_t lds = stats_lds_bytes(g);
+  const int UX = (g.W + 7) / 8, UY = (g.H + 7) / 8;
+  dim3 grid(g.nC, UX * UY, (g.F + kFramesPerWave - 1) / kFramesPerWave), block(64);
   if (g.dtype == 1)
-    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, lds, s, g, feats, part, nsum, sel);
+    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, 0, s, g, feats, part, nsum, sel);
   else
-    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, lds, s, g, feats, part, nsum, sel);
+    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, 0, s, g, feats, part, nsum, sel);
+  if (g.L > 3) hipLaunchKernelGGL(k_pyramid_upper, dim3(g.nC, g.F), dim3(64), 0, s, g, part, nsum);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -285,12 +292,28 @@ __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __
     if (node_exists(g, lvl, by, bx)) {
       for (int c = 0; c < g.nC; ++c) {
         const float* p = part + (size_t)(f * g.nC + c) * 2 * g.NN;
-        n += p[idx];
+        if (lvl == 0) n += p[idx];
         if (lvl < g.L) d += p[g.NN + idx];
       }
     }
     s_n[idx] = n;
     s_sim[idx] = d;  // dot for now
+  }
+  __syncthreads();
+  // squared norm of a node above the cells = sum over its children of (child sum) . (node sum)
+  for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
+    int lvl, by, bx;
+    node_decode(g, idx, lvl, by, bx);
+    float n = s_n[idx];
+    if (lvl >= 1) {
+      n = 0.f;
+      if (node_exists(g, lvl, by, bx))
+        for (int k = 0; k < 4; ++k) {
+          const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
+          if (node_exists(g, lvl - 1, cy, cx)) n += s_sim[node_index(g, lvl - 1, cy, cx)];
+        }
+      s_n[idx] = n;
+    }
     nrm2[fo + idx] = n;
   }
   __syncthreads();

@@ -84,8 +84,15 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
   __shared__ int16_t fast[256], mid[64], bighead[16], pairs0[1024], pairsX[512];
   __shared__ int nfast, nmid, nbig, n0, nX;
   __shared__ float tbuf[4][kFastRows * 68];
-  const int chunk = blockIdx.x;
-  const int pair = gridDim.y - 1 - blockIdx.y;  // frame pairs of all videos: (b, t) with t >= 1
+  // Workgroups are handed to the eight accelerator dies (each with an L2 of its own) round-robin by their
+  // linear index. A frame is read by two pairs: the mapping gives every die a contiguous range of pairs and
+  // walks it pair by pair, all chunks of a pair together, so the two readers of a frame run on the same die
+  // at about the same time and the second one finds the rows in that L2.
+  const int npairs = g.B * (g.T - 1), per_die = (npairs + 7) / 8;
+  const int die = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int chunk = slot % g.nC, pl = slot / g.nC;
+  if (pl >= per_die || die * per_die + pl >= npairs) return;
+  const int pair = npairs - 1 - (die * per_die + pl);  // frame pairs of all videos: (b, t) with t >= 1
   const int b = pair / (g.T - 1), t = pair - b * (g.T - 1) + 1;
   const int f = b * g.T + t;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -332,7 +339,8 @@ void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_l
     hipLaunchKernelGGL(k_select_clear_all, dim3(g.B), dim3(256), 0, s, sel);
     return;
   }
-  dim3 grid(g.nC, g.B * (g.T - 1)), block(256);
+  const int per_die = (g.B * (g.T - 1) + 7) / 8;
+  dim3 grid(8 * per_die * g.nC), block(256);
   const int U = g.P >= 8 ? g.P >> 3 : 1;
   const size_t lds = g.L >= 3 ? (size_t)U * U * g.cch * sizeof(float) : 0;
   if (g.dtype == 1)
