@@ -25,6 +25,21 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
+def stored_traffic(config: int, keep):
+    """HBM-side bytes per launch of the feature kernels, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    runs of this very script (summaries under profiles/; bench.py itself cannot run a profiler around itself).
+    Returns {kernel: read + written bytes} or {} when no summary covers the workload."""
+    names = {(3, 0.5): "whole_path_long_video_keep50.txt", (3, 0.3): "whole_path_long_video_keep30.txt"}
+    path = os.path.join(ROOT, "profiles", names.get((config, keep), "-"))
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "traffic_bytes":
+                out[f[1]] = int(f[2]) + int(f[3])
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,6 +139,9 @@ def main() -> int:
         avg_ms = ms / max(n, 1)
         kernels[name] = {"avg_ms": avg_ms, "launches": n, "alg_bytes": nbytes,
                          "GBps": nbytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else None}
+    traffic = stored_traffic(args.config, keep)
+    for name in kernels:
+        kernels[name]["traffic_bytes"] = traffic.get(name)
     dom = max(kernels, key=lambda kk: kernels[kk]["avg_ms"])
     achieved = kernels[dom]["GBps"]
     path_bytes = N * D * esz + K * D * esz + 9 * N + 8 * K
@@ -139,7 +157,7 @@ def main() -> int:
                                                    f"tau_s={cfg.tau_s} tau_t={cfg.tau_t}"),
                    "tokens": N, "kept_tokens": K, "kept_fraction": rho, "generate_s": gen_s},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": traffic.get(dom),
                      "alg_bytes_per_launch": kernels[dom]["alg_bytes"], "kernels": kernels},
         "path": {"alg_bytes_per_step": path_bytes,
                  "whole_path_GBps": path_bytes / (elapsed / args.steps) / 1e9,

@@ -204,6 +204,7 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
     launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum),
                          at<SelState>(c, c->lay.sel_s), c->stream);
   }
+  launch_pyramid_upper(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum), c->stream);
   launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nrm2), at<float>(c, c->lay.sim),
                           at<float>(c, c->lay.m), at<uint32_t>(c, c->lay.sel_key_s), at<uint8_t>(c, c->lay.sel_w_s),
                           at<SelState>(c, c->lay.sel_s), c->stream);
@@ -486,9 +487,10 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
   {
     Timed t(ctx, STTM_KERNEL_REDUCE_GATHER);
     launch_reduce_gather(ctx->g, feats_dev, at<float>(ctx, ctx->lay.nsum), node_map_dev, node_level_dev, out_dtype,
-                         capacity,
-                         merged_dev, counts_dev, rb, ctx->stream);
+                         capacity, merged_dev, counts_dev, rb, ctx->stream);
   }
+  launch_reduce_big(ctx->g, feats_dev, at<float>(ctx, ctx->lay.nsum), node_map_dev, node_level_dev, out_dtype,
+                    capacity, merged_dev, counts_dev, rb, ctx->stream);
   rc = after_launch(ctx);
   if (rc) return rc;
   if (n_out_host) {

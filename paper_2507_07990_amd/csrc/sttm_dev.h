@@ -157,6 +157,8 @@ __device__ inline void sel_flush_level0(SelState* st, const unsigned* lds_hist) 
 // `sel`: the spatial search states [B]; cleared by the statistics pass, level 0 filled by the finalize kernel.
 void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
                           hipStream_t s);
+// Levels above an 8x8 unit from the stored unit sums (nothing to do when the pyramid is no taller).
+void launch_pyramid_upper(const Geo& g, float* part, float* nsum, hipStream_t s);
 void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
                              uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s);
 void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
@@ -205,6 +207,9 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32
 void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                           const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
                           const ReduceBuffers& rb, hipStream_t s);
+void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
+                       const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
+                       const ReduceBuffers& rb, hipStream_t s);
 size_t reduce_bigpart_floats(const Geo& g);
 size_t reduce_bigw_entries(const Geo& g);
 size_t reduce_hist_entries(int N);

@@ -699,30 +699,52 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32
   }
 }
 
-// The feature pass of the reduce stage (three kernels; the two for big clusters exit at once when there are none).
+static GatherArgs gather_args(const void* feats, const float* nsum, const int32_t* node_map,
+                              const uint8_t* node_level, int64_t capacity, void* merged, int32_t* counts,
+                              const ReduceBuffers& rb) {
+  GatherArgs a;
+  a.feats = feats; a.nsum = nsum; a.node_map = node_map; a.lvl = node_level; a.order = rb.order; a.orow = rb.orow;
+  a.seg = rb.seg; a.kdev = rb.kdev; a.capacity = capacity; a.merged = merged; a.counts = counts;
+  a.bigpart = rb.bigpart; a.bigw = rb.bigw;
+  return a;
+}
+
+// The feature pass of the reduce stage: the gather over the whole list (clusters of up to kBig slots) ...
 void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                           const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
                           const ReduceBuffers& rb, hipStream_t s) {
   const int nitems = (g.N + kItem - 1) / kItem;
+  const int nw = g.nC < 16 ? g.nC : 16;
+  dim3 grid(nitems), block(64 * nw);
+  const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb);
+  if (g.dtype == 1) {
+    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce<1, 1>), grid, block, 0, s, g, a);
+    else hipLaunchKernelGGL((k_reduce<1, 0>), grid, block, 0, s, g, a);
+  } else {
+    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce<0, 1>), grid, block, 0, s, g, a);
+    else hipLaunchKernelGGL((k_reduce<0, 0>), grid, block, 0, s, g, a);
+  }
+}
+
+// ... and the clusters with more than kBig slots (two kernels that exit at once when there are none).
+void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
+                       const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
+                       const ReduceBuffers& rb, hipStream_t s) {
   const int nwin = (g.N + kBig - 1) / kBig;
   const int nw = g.nC < 16 ? g.nC : 16;
-  dim3 grid(nitems), gridw(nwin), block(64 * nw);
-  GatherArgs a;
-  a.feats = feats; a.nsum = nsum; a.node_map = node_map; a.lvl = node_level; a.order = rb.order; a.orow = rb.orow; a.seg = rb.seg;
-  a.kdev = rb.kdev; a.capacity = capacity; a.merged = merged; a.counts = counts; a.bigpart = rb.bigpart;
-  a.bigw = rb.bigw;
-#define STTM_REDUCE(DT, ODT)                                                       \
+  dim3 gridw(nwin), block(64 * nw);
+  const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb);
+#define STTM_BIG(DT, ODT)                                                          \
   do {                                                                             \
-    hipLaunchKernelGGL((k_reduce<DT, ODT>), grid, block, 0, s, g, a);              \
     hipLaunchKernelGGL((k_reduce_big_partial<DT>), gridw, block, 0, s, g, a);      \
     hipLaunchKernelGGL((k_reduce_big_combine<DT, ODT>), gridw, block, 0, s, g, a); \
   } while (0)
   if (g.dtype == 1) {
-    if (out_dtype == 1) STTM_REDUCE(1, 1); else STTM_REDUCE(1, 0);
+    if (out_dtype == 1) STTM_BIG(1, 1); else STTM_BIG(1, 0);
   } else {
-    if (out_dtype == 1) STTM_REDUCE(0, 1); else STTM_REDUCE(0, 0);
+    if (out_dtype == 1) STTM_BIG(0, 1); else STTM_BIG(0, 0);
   }
-#undef STTM_REDUCE
+#undef STTM_BIG
 }
 
 }  // namespace sttm

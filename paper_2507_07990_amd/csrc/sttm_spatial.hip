@@ -264,6 +264,9 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* n
     hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, 0, s, g, feats, part, nsum, sel);
   else
     hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, 0, s, g, feats, part, nsum, sel);
+}
+
+void launch_pyramid_upper(const Geo& g, float* part, float* nsum, hipStream_t s) {
   if (g.L > 3) hipLaunchKernelGGL(k_pyramid_upper, dim3(g.nC, g.F), dim3(64), 0, s, g, part, nsum);
 }
 

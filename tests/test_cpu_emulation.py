@@ -1,0 +1,50 @@
+"""The library's kernels compiled for host threads (tests/cpu_emul) against the oracle, on the CPU.
+
+Not a product path: the stand-in runs one OS thread per GPU thread so that the control flow, indexing and
+synchronisation of the kernels can be exercised (and debugged with host tools) where there is no GPU."""
+import math
+import shutil
+
+import numpy as np
+import pytest
+
+from paper_2507_07990_amd import workloads as wl
+from tests import parity as P
+
+pytestmark = pytest.mark.skipif(shutil.which("g++") is None, reason="needs g++")
+
+
+class _EmulLib:
+    STTM_BF16, STTM_F32 = 1, 0
+
+    def __init__(self, rc):
+        self._lib = rc.load()
+        self._lib.sttm_node_index.restype = int
+
+    def sttm_node_index(self, H, W, R, lvl, by, bx):
+        return self._lib.sttm_node_index(H, W, R, lvl, by, bx)
+
+
+@pytest.fixture(scope="module")
+def emul():
+    from tests.cpu_emul import build_cpu, run_cpu
+    build_cpu.build()
+    return run_cpu, _EmulLib(run_cpu)
+
+
+def _variant(seed, B, T, H, W, D, dtype):
+    depth = int(math.log2(wl.pow2_ceil(max(H, W))))
+    return wl.Workload("v", seed, B, T, H, W, D, dtype, depth, 0.1, 0.7)
+
+
+@pytest.mark.parametrize("seed,B,T,H,W,D,dtype,kw", [
+    (90, 1, 3, 8, 8, 16, "f32", dict(tau_s=0.8, tau_t=0.8)),
+    (91, 2, 3, 5, 6, 24, "bf16", dict(keep=0.5)),
+    (92, 1, 2, 9, 9, 16, "bf16", dict(tau_s=0.2, tau_t=0.2)),   # nodes that the reduce takes from stored sums
+])
+def test_emulated_kernels_match_the_oracle(emul, seed, B, T, H, W, D, dtype, kw):
+    run_cpu, fake = emul
+    feats = wl.generate(_variant(seed, B, T, H, W, D, dtype))
+    r = run_cpu.run_cpu(feats, **kw)
+    info = P.check_parity(fake, feats, r, **kw)
+    assert info["K"] == r.K and int(r.counts.sum()) == feats[..., 0].size

@@ -111,6 +111,53 @@ def test_degenerate_inputs(lib):
     assert r.cluster_ids[0, 1, 3, 3] == 169 + 3 * 13 + 3
 
 
+@pytest.mark.parametrize("seed,T,H,W,D,dtype,tau_s,tau_t", [
+    (70, 6, 13, 13, 136, "bf16", 0.3, 0.3),      # whole-frame and 8x8 nodes: their stored sums stand for them
+    (71, 5, 16, 16, 72, "f32", 0.4, 0.5),
+    (72, 7, 9, 9, 64, "bf16", 0.2, 0.2),         # the 8x8 node at (8, 8) holds a single valid cell
+    (73, 4, 27, 27, 40, "bf16", 0.5, 0.4),       # five levels
+    (74, 40, 8, 8, 16, "f32", 1.0, 0.2),         # long chains of single cells: clusters of more than 64 list slots
+])
+def test_reduce_with_and_without_node_sums(lib, seed, T, H, W, D, dtype, tau_s, tau_t):
+    """The reduce call takes the stage-1 partition as an option; both ways must match the oracle."""
+    cfg = _variant(seed, 1, T, H, W, D, dtype)
+    feats = wl.generate(cfg)
+    print(f"case seed={seed} shape={feats.shape} dtype={feats.dtype}", flush=True)
+    a = P.run_gpu(lib, feats, tau_s=tau_s, tau_t=tau_t, use_nodes=True)
+    P.check_parity(lib, feats, a, tau_s=tau_s, tau_t=tau_t)
+    b = P.run_gpu(lib, feats, tau_s=tau_s, tau_t=tau_t, use_nodes=False, ctx=a.ctx, feats_dev=a.feats_dev)
+    P.check_parity(lib, feats, b, tau_s=tau_s, tau_t=tau_t)
+    assert (a.counts == b.counts).all() and (a.out_ids == b.out_ids).all() and (a.offsets == b.offsets).all()
+    tol = P.TOL_BF16 if dtype == "bf16" else P.TOL_F32
+    assert np.abs(a.merged - b.merged).max() <= tol
+
+
+def test_budget_call_can_be_repeated(lib):
+    """One statistics pass serves any number of budget searches (the search state is reset in between)."""
+    import torch
+    cfg = _variant(80, 2, 6, 13, 13, 72, "bf16")
+    feats = wl.generate(cfg)
+    B, T, H, W, D = feats.shape
+    x = P._to_dev(feats)
+    s = lib.Sttm(0)
+    s.ensure_workspace(B, T, H, W, D, lib.STTM_BF16, 1)
+    s.sttm_spatial_stats(x, lib.STTM_BF16, B, T, H, W, D, 1)
+    t50 = s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, 0.5)
+    t30 = s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, [0.3, 0.9])
+    again = s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, 0.5)
+    assert (t50 == again).all() and t30[0] <= t50[0] and t30[1] >= t50[1]
+    nm = torch.empty(B * T * H * W, dtype=torch.int32, device="cuda:0")
+    lv = torch.empty(B * T * H * W, dtype=torch.uint8, device="cuda:0")
+    s.sttm_spatial_quadtree(x, lib.STTM_BF16, B, T, H, W, D, 1, None, nm, lv)
+    s.sttm_temporal_stats(x, nm, lv)
+    u50 = s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.5)
+    u30 = s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.3)
+    again = s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.5)
+    assert (u50 == again).all() and (u30 <= u50).all()
+    r = P.run_gpu(lib, feats, keep=0.5)
+    assert (r.tau_s == t50).all() and (r.tau_t == u50).all()
+
+
 def test_bitwise_reproducible(lib):
     cfg = _variant(50, 2, 8, 13, 13, 520, "bf16")
     feats = wl.generate(cfg)
