@@ -20,7 +20,7 @@ struct Layout {
   size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_s, sel_t, lvl,
       pd_part, sig, e, parent, ptr_a, ptr_b;
   size_t rank, key_a, val_a, key_b, val_b, order, orow, hist, tot, tile_roots, tile_live, seg, kdev,
-      bigpart, bigw;
+      bigpart, bigw, biglist;
   size_t total;
 };
 
@@ -89,9 +89,10 @@ Layout make_layout(const Geo& g) {
   l.tile_roots = take(reduce_tiles(g.N) * sizeof(int32_t));
   l.tile_live = take(reduce_tiles(g.N) * sizeof(int32_t));
   l.seg = take((N + 1) * sizeof(int32_t));
-  l.kdev = take(2 * sizeof(int32_t));
+  l.kdev = take(4 * sizeof(int32_t));
   l.bigpart = take(reduce_bigpart_floats(g) * sizeof(float));
   l.bigw = take(reduce_bigw_entries(g) * sizeof(int32_t));
+  l.biglist = take(reduce_biglist_entries(g) * 4 * sizeof(int32_t));
   l.total = off;
   return l;
 }
@@ -482,6 +483,7 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
   rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
   rb.bigpart = at<float>(ctx, ctx->lay.bigpart);
   rb.bigw = at<int32_t>(ctx, ctx->lay.bigw);
+  rb.biglist = at<int32_t>(ctx, ctx->lay.biglist);
   launch_reduce_prepare(ctx->g, cluster_ids_dev, node_map_dev, node_level_dev, capacity, out_ids_dev, offsets_dev,
                         rb, ctx->stream);
   {

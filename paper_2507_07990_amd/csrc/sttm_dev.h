@@ -116,10 +116,19 @@ __device__ inline void wave_lds_fence() {
 // Token count as a function of the threshold is K(tau) = base + sum_j w_j [v_j <= tau]; the search is an
 // MSB-first radix select (11 + 11 + 10 bits) over the order-preserving integer image of v.
 constexpr int kSelBins = 2048;
+// What a search pass found, handed to the next launch so that it does not have to derive it again.
+struct SelFound {
+  unsigned long long budget;  // target - base
+  unsigned long long acc;     // weight of the keys below the prefix
+  unsigned prefix;            // leading digits of the searched key found so far
+  int rc;                     // 0 = searching, 1 = everything fits (tau = 1), 2 = the base alone exceeds the target
+};
 struct SelState {
   unsigned hist[3][kSelBins];  // weight per digit: level 0 over all elements, levels 1-2 under the found prefix
   unsigned lo_out;             // largest key whose leading 22 bits are below the found prefix (0 = none)
-  unsigned pad[31];
+  unsigned pad0[3];
+  SelFound found[2];           // after the first / second digit
+  unsigned pad[16];
 };
 
 // One workgroup zeroes a state.
@@ -196,9 +205,10 @@ struct ReduceBuffers {
   int32_t* tile_roots;  // [tiles]
   int32_t* tile_live;   // [tiles]
   int32_t* seg;         // [N+1] first list position of every output row
-  int32_t* kdev;        // [2] number of clusters, length of the live list
-  float* bigpart;       // window partial sums of clusters with more than 64 elements
-  int32_t* bigw;        // member counts of those partial sums
+  int32_t* kdev;        // [4] number of clusters, length of the live list, length of the big-cluster list
+  int32_t* biglist;     // [big clusters][4] output row, first list position, end of the list, unused
+  float* bigpart;       // [gather items][2][D] partial sums of clusters with more than 64 list slots
+  int32_t* bigw;        // [gather items][2] member cells behind those partial sums
 };
 // node_map / node_level: the stage-1 partition, or both NULL (every cell is its own list element).
 void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map,
@@ -212,6 +222,7 @@ void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const
                        const ReduceBuffers& rb, hipStream_t s);
 size_t reduce_bigpart_floats(const Geo& g);
 size_t reduce_bigw_entries(const Geo& g);
+size_t reduce_biglist_entries(const Geo& g);
 size_t reduce_hist_entries(int N);
 size_t reduce_tiles(int N);
 

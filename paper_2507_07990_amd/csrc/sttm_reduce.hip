@@ -14,6 +14,9 @@ constexpr int kSortPer = 8;
 constexpr int kSortTile = kSortThreads * kSortPer;  // 2048 elements per workgroup
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxDigitBits = 11;
+constexpr int kItem = 16;  // list positions per gather item
+constexpr int kBig = 64;   // clusters with more list slots than this are summed window by window
+constexpr int kTail = 8;
 constexpr int kMaxDigits = 1 << kMaxDigitBits;
 constexpr int kInKernelColumns = 256;  // up to this many tiles a scatter workgroup sums the histogram columns itself
 
@@ -28,6 +31,7 @@ static SortPlan sort_plan(int N) {
   while ((1ll << bits) < (long long)N) ++bits;  // keys 0..N-1
   p.passes = (bits + kMaxDigitBits - 1) / kMaxDigitBits;
   p.dbits = (bits + p.passes - 1) / p.passes;
+  if (p.dbits < 2) p.dbits = 2;  // a histogram row is read in pieces of four digits
   p.nb = (N + kSortTile - 1) / kSortTile;
   p.prescan = p.nb > kInKernelColumns;
   return p;
@@ -86,23 +90,38 @@ __global__ __launch_bounds__(kSortThreads) void k_reduce_prep(Geo g, const int32
                                                               int32_t* __restrict__ keys, int32_t* __restrict__ rank,
                                                               int32_t* __restrict__ tile_roots,
                                                               int32_t* __restrict__ tile_live,
-                                                              int32_t* __restrict__ hist) {
+                                                              int32_t* __restrict__ hist,
+                                                              int32_t* __restrict__ bigcount) {
   __shared__ int cnt[kMaxDigits];
   const int DIG = 1 << dbits, b = blockIdx.x, tid = threadIdx.x;
   for (int d = tid; d < DIG; d += kSortThreads) cnt[d] = 0;
+  if (b == 0 && tid == 0) *bigcount = 0;  // the list of big clusters starts empty
   __syncthreads();
   const int i0 = b * kSortTile + tid * kSortPer;
   int root[kSortPer], nroot = 0, nlive = 0;
+  int cidv[kSortPer], repv[kSortPer], lvv[kSortPer];
+#pragma unroll
+  for (int j = 0; j < kSortPer; ++j) {  // all loads first: they do not depend on one another
+    const int i = i0 + j;
+    cidv[j] = repv[j] = lvv[j] = 0;
+    if (i < g.N) {
+      cidv[j] = cluster_ids[i];
+      if (node_map) {
+        repv[j] = node_map[i];
+        lvv[j] = node_level[i];
+      }
+    }
+  }
 #pragma unroll
   for (int j = 0; j < kSortPer; ++j) {
     const int i = i0 + j;
     root[j] = 0;
     if (i < g.N) {
-      const int cid = cluster_ids[i];
+      const int cid = cidv[j];
       bool live = true;
-      if (node_map && node_level[i] >= 3) {  // a node with a stored sum: only the cells standing for it stay
-        const int rep = node_map[i], c = rep % g.HW;
-        if (node_is_summed(g, c, node_level[i]))
+      if (lvv[j] >= 3) {  // a node with a stored sum: only the cells standing for it stay
+        const int rep = repv[j], c = rep % g.HW;
+        if (node_is_summed(g, c, lvv[j]))
           live = i == rep || (g.vec == 8 && i == rep - c + node_second_cell(g, c));
       }
       keys[i] = live ? cid : -1;
@@ -207,7 +226,85 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
   const int wave = tid >> 6, lane = tid & 63;
   const int n = FIRST ? a.n : a.kdev[1];
 
-  // ---- start offset of every digit for this tile (a thread owns `dpt` consecutive digits)
+  // ---- everything this tile reads per element is requested first, so that it arrives while the offsets
+  //      are worked out
+  const int e0 = b * kSortTile + wave * (kSortTile / kSortWaves);
+  int key[kSortPer], val[kSortPer], aux[kSortPer];
+  int rk0[kSortPer], cid[kSortPer];
+  bool ok[kSortPer];
+#pragma unroll
+  for (int r = 0; r < kSortPer; ++r) {
+    const int i = e0 + r * 64 + lane;
+    key[r] = -1;
+    val[r] = rk0[r] = cid[r] = 0;
+    if (i < n) {
+      key[r] = a.keys[i];
+      val[r] = FIRST ? i : a.vals[i];
+      if (FIRST) {
+        rk0[r] = a.rank[i];
+        cid[r] = a.cluster_ids[i];
+      }
+    }
+    ok[r] = key[r] >= 0;
+  }
+  int roots_before = 0, roots_all = 0, live_all = 0;
+  if (FIRST) {
+    for (int t = tid; t < a.nb; t += kSortThreads) {
+      const int v = a.tile_roots[t];
+      roots_all += v;
+      if (t < b) roots_before += v;
+      if (b == 0) live_all += a.tile_live[t];
+    }
+  }
+
+  // ---- start offset of every digit for this tile
+  int* tot = cur[0];   // column totals and the part of them that lies in the tiles before this one
+  int* mine = cur[1];  // (the cursors are not in use yet)
+  if (!a.prescan) {
+    // hist[tile][digit] is read as 16-byte pieces, consecutive threads next to each other, sixteen loads in
+    // flight per thread; the four digits a thread sees do not change from load to load (two sets when a row
+    // has more pieces than the workgroup has threads)
+    for (int d = tid; d < DIG; d += kSortThreads) tot[d] = mine[d] = 0;
+    __syncthreads();
+    const int vshift = a.dbits - 2, VC = 1 << vshift;  // 16-byte pieces per tile row
+    const int total4 = a.nb << vshift;
+    const int4* h4 = reinterpret_cast<const int4*>(a.hist);
+    int at[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, am[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    for (int q0 = tid; q0 < total4; q0 += 16 * kSortThreads) {
+      int4 v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int q = q0 + u * kSortThreads;
+        v[u] = q < total4 ? h4[q] : make_int4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int q = q0 + u * kSortThreads;
+        const bool before = (q >> vshift) < b;  // the piece's tile
+        const int e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          at[u & 1][i] += e[i];
+          if (before) am[u & 1][i] += e[i];
+        }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int vc = (tid + k * kSortThreads) & (VC - 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (at[k][i]) atomicAdd(&tot[vc * 4 + i], at[k][i]);
+        if (am[k][i]) atomicAdd(&mine[vc * 4 + i], am[k][i]);
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int r = 0; r < kSortPer; ++r) {
+    aux[r] = 0;
+    if (LAST && ok[r]) aux[r] = a.rank[key[r]];  // output row of the element's cluster (arrives during the scan)
+  }
   {
     constexpr int kDpt = kMaxDigits / kSortThreads;
     const int dpt = DIG >= kSortThreads ? DIG / kSortThreads : 1;
@@ -217,29 +314,13 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
       const int d = tid * dpt + j;
       tv[j] = cv[j] = 0;
       if (j < dpt && d < DIG) {
-        if (a.prescan) {
-          tv[j] = a.tot[d];
-          cv[j] = a.hist[(size_t)b * DIG + d];
-        } else {
-          int run = 0, mine = 0;
-          for (int t0 = 0; t0 < a.nb; t0 += 8) {  // eight independent loads at a time
-            int v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = t0 + u < a.nb ? a.hist[(size_t)(t0 + u) * DIG + d] : 0;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-              if (t0 + u == b) mine = run;
-              run += v[u];
-            }
-          }
-          tv[j] = run;
-          cv[j] = mine;
-        }
+        tv[j] = a.prescan ? a.tot[d] : tot[d];
+        cv[j] = a.prescan ? a.hist[(size_t)b * DIG + d] : mine[d];
       }
       s += tv[j];
     }
     int total;
-    int ex = block_exclusive_scan(s, &total);
+    int ex = block_exclusive_scan(s, &total);  // (its barriers also fence the reads above from the clearing below)
 #pragma unroll
     for (int j = 0; j < kDpt; ++j) {
       const int d = tid * dpt + j;
@@ -249,17 +330,9 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
   }
   int root_prefix = 0;
   if (FIRST) {
-    int before = 0, all = 0, live = 0;
-    for (int t = tid; t < a.nb; t += kSortThreads) {
-      const int v = a.tile_roots[t];
-      all += v;
-      if (t < b) before += v;
-      if (b == 0) live += a.tile_live[t];
-    }
-    root_prefix = block_sum(before);
+    root_prefix = block_sum(roots_before);
     if (b == 0) {
-      all = block_sum(all);
-      live = block_sum(live);
+      const int all = block_sum(roots_all), live = block_sum(live_all);
       if (tid == 0) {
         a.kdev[0] = all;
         a.kdev[1] = live;
@@ -274,36 +347,19 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
     for (int w = 0; w < kSortWaves; ++w) cur[w][d] = 0;
   __syncthreads();
 
-  // ---- loads and per-wavefront digit counts of its 512 elements
-  const int e0 = b * kSortTile + wave * (kSortTile / kSortWaves);
-  int key[kSortPer], val[kSortPer], aux[kSortPer];
-  bool ok[kSortPer];
+  // ---- per-wavefront digit counts of its 512 elements
 #pragma unroll
-  for (int r = 0; r < kSortPer; ++r) {
-    const int i = e0 + r * 64 + lane;
-    key[r] = -1;
-    val[r] = 0;
-    if (i < n) {
-      key[r] = a.keys[i];
-      val[r] = FIRST ? i : a.vals[i];
-    }
-    ok[r] = key[r] >= 0;
+  for (int r = 0; r < kSortPer; ++r)
     if (ok[r]) atomicAdd(&cur[wave][(key[r] >> a.shift) & (DIG - 1)], 1);
-  }
-#pragma unroll
-  for (int r = 0; r < kSortPer; ++r) {
-    aux[r] = 0;
-    if (LAST && ok[r]) aux[r] = a.rank[key[r]];  // output row of the element's cluster
-  }
   if (FIRST) {
     // bookkeeping outputs of the cells themselves
 #pragma unroll
     for (int r = 0; r < kSortPer; ++r) {
       const int i = e0 + r * 64 + lane;
       if (i >= n) continue;
-      const int rk = a.rank[i] + root_prefix;
+      const int rk = rk0[r] + root_prefix;
       if (b != 0) a.rank[i] = rk;
-      if (a.cluster_ids[i] == i && a.out_ids && rk < a.capacity) a.out_ids[rk] = i;
+      if (cid[r] == i && a.out_ids && rk < a.capacity) a.out_ids[rk] = i;
       if (i % a.per_video == 0) a.offsets[i / a.per_video] = rk;
     }
   }
@@ -319,19 +375,25 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
   }
   __syncthreads();
 
-  // ---- ranked scatter, 64 elements at a time in index order
+  // ---- ranked scatter, 64 elements at a time in index order: first which lanes hold the same digit (no
+  //      memory involved), then the cursors
   const unsigned long long below = (1ull << lane) - 1ull;
   int* mycur = cur[wave];
+  unsigned long long same[kSortPer];
 #pragma unroll
   for (int r = 0; r < kSortPer; ++r) {
     const int digit = (key[r] >> a.shift) & (DIG - 1);
-    unsigned long long same = __ballot(ok[r]);
+    same[r] = __ballot(ok[r]);
     for (int bit = 0; bit < a.dbits; ++bit) {
       const unsigned long long m = __ballot((digit >> bit) & 1);
-      same &= ((digit >> bit) & 1) ? m : ~m;
+      same[r] &= ((digit >> bit) & 1) ? m : ~m;
     }
+  }
+#pragma unroll
+  for (int r = 0; r < kSortPer; ++r) {
+    const int digit = (key[r] >> a.shift) & (DIG - 1);
     if (ok[r]) {
-      const int dst = mycur[digit] + __popcll(same & below);
+      const int dst = mycur[digit] + __popcll(same[r] & below);
       if (LAST) {
         a.vals_out[dst] = val[r];
         a.orow[dst] = aux[r];
@@ -342,8 +404,8 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
       }
     }
     wave_lds_fence();
-    if (ok[r] && ((same >> lane) >> 1) == 0)  // highest lane of its digit group advances the cursor
-      mycur[digit] += __popcll(same);
+    if (ok[r] && ((same[r] >> lane) >> 1) == 0)  // highest lane of its digit group advances the cursor
+      mycur[digit] += __popcll(same[r]);
     wave_lds_fence();
   }
 }
@@ -355,13 +417,12 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
 // The list is cut into items of kItem consecutive slots; an item owns the clusters whose list starts
 // inside it. One wavefront per (item, chunk of the row). All index look-ups of the item are done
 // lane-parallel first, then all loads are issued, then the slots are added up in list order (fp32) with the
-// cluster boundaries handled as wave-uniform control flow. Clusters with more than kBig slots are left to
-// the two kernels below, which cut them at fixed kBig-aligned list positions so that the summation order
-// does not depend on scheduling.
+// cluster boundaries handled as wave-uniform control flow. A cluster with more than kBig slots is not
+// followed past the item: every item adds up the slots of such a cluster that lie inside it and leaves the
+// partial sum in the workspace (at most two per item: the cluster running in from the left and the one
+// starting inside), the item in which the cluster starts puts it on a list, and k_reduce_big_combine adds
+// the partial sums up in item order -- so the summation order does not depend on scheduling.
 // ------------------------------------------------------------------------------------------------
-constexpr int kItem = 16;
-constexpr int kBig = 64;
-constexpr int kTail = 8;
 
 // Where a list slot's data lives.
 struct Slot {
@@ -457,9 +518,17 @@ struct GatherArgs {
   int64_t capacity;
   void* merged;
   int32_t* counts;
-  float* bigpart;
-  int32_t* bigw;
+  float* bigpart;     // [items][2][D] partial sums of big clusters
+  int32_t* bigw;      // [items][2] member cells behind them
+  int4* biglist;      // one entry per big cluster: output row, first list position, end of its list
+  int32_t* bigcount;  // length of that list
 };
+
+template <int VEC>
+__device__ inline void store_partial(float* o, const float (&acc)[VEC]) {
+#pragma unroll
+  for (int v = 0; v < VEC; v += 4) *reinterpret_cast<float4*>(o + v) = make_float4(acc[v], acc[v + 1], acc[v + 2], acc[v + 3]);
+}
 
 template <int DT, int ODT>
 __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
@@ -481,14 +550,14 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
   for (int chunk = wave; chunk < g.nC; chunk += nw) {
     const int ch0 = chunk * g.cch + lane * VEC;
     const bool act = ch0 < g.D;
-    // issue every load of the positions this item owns
+    // issue every load of the positions this item adds up: clusters starting here, and big ones
     typename R::Raw raw[kItem];
 #pragma unroll
     for (int j = 0; j < kItem; ++j) {
       const int beg = __shfl(beg_v, j, 64), end = __shfl(end_v, j, 64);
       const int kind = __shfl(sv.kind, j, 64), idx = __shfl(sv.idx, j, 64);
       raw[j] = R::zero();
-      const bool use = p0 + j < p1 && beg >= p0 && end - beg <= kBig;  // wave-uniform
+      const bool use = p0 + j < p1 && (beg >= p0 || end - beg > kBig);  // wave-uniform
       if (use && act) raw[j] = load_slot<DT>(a.feats, a.nsum, g.D, ch0, kind, idx);
     }
     float acc[VEC];
@@ -499,12 +568,26 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
     for (int j = 0; j < kItem; ++j) {
       const int beg = __shfl(beg_v, j, 64), end = __shfl(end_v, j, 64), row = __shfl(row_v, j, 64);
       const int kind = __shfl(sv.kind, j, 64), wgt = __shfl(sv.weight, j, 64);
-      const bool use = p0 + j < p1 && beg >= p0 && end - beg <= kBig;
+      const bool big = end - beg > kBig;
+      const bool use = p0 + j < p1 && (beg >= p0 || big);
       if (use) {
         acc_slot(raw[j], kind, acc);
         members += wgt;
         const int p = p0 + j;
-        if (p + 1 == end) {
+        const bool closes = p + 1 == end, last = p + 1 == p1;
+        if (big) {
+          if (closes || last) {  // this item's share of a big cluster
+            const int slot = beg < p0 ? 0 : 1;
+            if (act) store_partial<VEC>(a.bigpart + ((size_t)blockIdx.x * 2 + slot) * g.D + ch0, acc);
+            if (chunk == 0 && lane == 0) {
+              a.bigw[blockIdx.x * 2 + slot] = members;
+              if (slot == 1) a.biglist[atomicAdd(a.bigcount, 1)] = make_int4(row, beg, end, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+            members = 0;
+          }
+        } else if (closes) {
           if (row < a.capacity) {
             if (act) store_mean<DT, ODT>(a.merged, (size_t)row * g.D + ch0, acc, 1.f / (float)members);
             if (chunk == 0 && lane == 0 && a.counts) a.counts[row] = members;
@@ -512,7 +595,7 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
 #pragma unroll
           for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
           members = 0;
-        } else if (p + 1 == p1) {
+        } else if (last) {
           open_row = row;
           open_end = end;
         }
@@ -547,119 +630,59 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
   }
 }
 
-// Partial sums of the big clusters over fixed windows of kBig list positions: slot 0 = the big cluster
-// running into the window from the left, slot 1 = the big cluster starting inside it (at most one each).
-template <int DT>
-__global__ __launch_bounds__(1024) void k_reduce_big_partial(Geo g, GatherArgs a) {
-  typedef Row<DT> R;
-  constexpr int VEC = R::VEC;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-  const int M = a.kdev[1];
-  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, M);
-  if (w0 >= M) return;
-  int beg = -1, end = -1;
-  int cell = 0;
-  if (w0 + lane < w1) {
-    const int row = a.orow[w0 + lane];
-    beg = a.seg[row];
-    end = a.seg[row + 1];
-    cell = a.order[w0 + lane];
-  }
-  const bool big = end - beg > kBig;
-  const int beg0 = __shfl(beg, 0, 64), end0 = __shfl(end, 0, 64);
-  const bool has_left = (end0 - beg0 > kBig) && beg0 < w0;
-  const unsigned long long starts = __ballot(big && beg == w0 + lane);
-  if (!has_left && starts == 0) return;
-  Slot sv = {0, 0, 0};
-  if (w0 + lane < w1) sv = describe<DT>(g, a.node_map, a.lvl, cell);
-  for (int slot = 0; slot < 2; ++slot) {
-    int pa, pb;
-    if (slot == 0) {
-      if (!has_left) continue;
-      pa = w0;
-      pb = min(end0, w1);
-    } else {
-      if (starts == 0) continue;
-      const int l = __ffsll((long long)starts) - 1;
-      pa = w0 + l;
-      pb = min(__shfl(end, l, 64), w1);
-    }
-    for (int chunk = wave; chunk < g.nC; chunk += nw) {
-      const int ch0 = chunk * g.cch + lane * VEC;
-      const bool act = ch0 < g.D;
-      float acc[VEC];
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
-      int members = 0;
-      // slots pa..pb-1 of the window, eight loads in flight; the slot of list position w0 + l sits in lane l
-      for (int q = pa; q < pb; q += 8) {
-        typename R::Raw r[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int src = min(q + j, w1 - 1) - w0;
-          const int kd = __shfl(sv.kind, src, 64), ix = __shfl(sv.idx, src, 64);
-          r[j] = R::zero();
-          if (q + j < pb && act) r[j] = load_slot<DT>(a.feats, a.nsum, g.D, ch0, kd, ix);
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int src = min(q + j, w1 - 1) - w0;
-          const int kd = __shfl(sv.kind, src, 64), wg = __shfl(sv.weight, src, 64);
-          if (q + j >= pb) continue;
-          acc_slot(r[j], kd, acc);
-          members += wg;
-        }
-      }
-      if (chunk == 0 && lane == 0) a.bigw[blockIdx.x * 2 + slot] = members;
-      if (!act) continue;
-      float* o = a.bigpart + ((size_t)blockIdx.x * 2 + slot) * g.D + ch0;
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) o[v] = acc[v];
-    }
-  }
-}
+// A fixed number of workgroups walks the list of big clusters; each cluster's partial sums are added up in
+// item order (the starting item's own, then the left-hand shares of the items after it), eight in flight.
+constexpr int kBigGrid = 256;
+constexpr int kBigBatch = 8;
 
-// The window in which a big cluster starts adds up its window partials in window order and stores the mean.
 template <int DT, int ODT>
 __global__ __launch_bounds__(1024) void k_reduce_big_combine(Geo g, GatherArgs a) {
   constexpr int VEC = Row<DT>::VEC;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-  const int M = a.kdev[1];
-  const int w0 = blockIdx.x * kBig, w1 = min(w0 + kBig, M);
-  if (w0 >= M) return;
-  int beg = -1, end = -1, row = -1;
-  if (w0 + lane < w1) {
-    row = a.orow[w0 + lane];
-    beg = a.seg[row];
-    end = a.seg[row + 1];
-  }
-  const unsigned long long starts = __ballot(end - beg > kBig && beg == w0 + lane);
-  if (starts == 0) return;
-  const int l = __ffsll((long long)starts) - 1;
-  const int e = __shfl(end, l, 64), k = __shfl(row, l, 64);
-  if (k >= a.capacity) return;
-  const int wlast = (e - 1) / kBig;
-  int members = a.bigw[blockIdx.x * 2 + 1];
-  for (int w = blockIdx.x + 1; w <= wlast; ++w) members += a.bigw[w * 2];
-  if (wave == 0 && lane == 0 && a.counts) a.counts[k] = members;
-  for (int chunk = wave; chunk < g.nC; chunk += nw) {
-    const int ch0 = chunk * g.cch + lane * VEC;
-    if (ch0 >= g.D) continue;
-    float acc[VEC];
-    const float* pp = a.bigpart + ((size_t)blockIdx.x * 2 + 1) * g.D + ch0;
+  const int nbig = *a.bigcount;
+  for (int e = blockIdx.x; e < nbig; e += gridDim.x) {
+    const int4 en = a.biglist[e];
+    const int k = en.x, it0 = en.y / kItem, it1 = (en.z - 1) / kItem;
+    if (k >= a.capacity) continue;
+    int members = 0;
+    for (int it = it0 + lane; it <= it1; it += 64) members += a.bigw[it * 2 + (it == it0 ? 1 : 0)];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) acc[v] = pp[v];
-    for (int w = blockIdx.x + 1; w <= wlast; ++w) {
-      const float* q = a.bigpart + ((size_t)w * 2) * g.D + ch0;
+    for (int o = 32; o > 0; o >>= 1) members += __shfl_xor(members, o, 64);
+    if (wave == 0 && lane == 0 && a.counts) a.counts[k] = members;
+    for (int chunk = wave; chunk < g.nC; chunk += nw) {
+      const int ch0 = chunk * g.cch + lane * VEC;
+      if (ch0 >= g.D) continue;
+      float acc[VEC];
+      const float* pp = a.bigpart + ((size_t)it0 * 2 + 1) * g.D + ch0;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[v] += q[v];
+      for (int v = 0; v < VEC; ++v) acc[v] = pp[v];
+      for (int it = it0 + 1; it <= it1; it += kBigBatch) {
+        float4 r[kBigBatch][VEC / 4];
+#pragma unroll
+        for (int u = 0; u < kBigBatch; ++u) {
+          const float4* q = reinterpret_cast<const float4*>(a.bigpart + ((size_t)min(it + u, it1) * 2) * g.D + ch0);
+#pragma unroll
+          for (int v = 0; v < VEC / 4; ++v) r[u][v] = q[v];
+        }
+#pragma unroll
+        for (int u = 0; u < kBigBatch; ++u) {
+          if (it + u > it1) continue;
+#pragma unroll
+          for (int v = 0; v < VEC / 4; ++v) {
+            acc[4 * v] += r[u][v].x; acc[4 * v + 1] += r[u][v].y;
+            acc[4 * v + 2] += r[u][v].z; acc[4 * v + 3] += r[u][v].w;
+          }
+        }
+      }
+      store_mean<DT, ODT>(a.merged, (size_t)k * g.D + ch0, acc, 1.f / (float)members);
     }
-    store_mean<DT, ODT>(a.merged, (size_t)k * g.D + ch0, acc, 1.f / (float)members);
   }
 }
 
-size_t reduce_bigpart_floats(const Geo& g) { return (size_t)((g.N + kBig - 1) / kBig) * 2 * g.D; }
-size_t reduce_bigw_entries(const Geo& g) { return (size_t)((g.N + kBig - 1) / kBig) * 2; }
+size_t reduce_items(const Geo& g) { return (size_t)(g.N + kItem - 1) / kItem; }
+size_t reduce_bigpart_floats(const Geo& g) { return reduce_items(g) * 2 * g.D; }
+size_t reduce_bigw_entries(const Geo& g) { return reduce_items(g) * 2; }
+size_t reduce_biglist_entries(const Geo& g) { return (size_t)g.N / (kBig + 1) + 1; }  // a big cluster has > kBig slots
 
 // Integer plumbing of the reduce stage: sorted element list, row of every list position, row starts.
 void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map,
@@ -670,7 +693,7 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32
   const int DIG = 1 << pl.dbits;
   const dim3 grid(pl.nb), block(kSortThreads);
   hipLaunchKernelGGL(k_reduce_prep, grid, block, 0, s, g, cluster_ids, node_map, node_level, pl.dbits, rb.key_a,
-                     rb.rank, rb.tile_roots, rb.tile_live, rb.hist);
+                     rb.rank, rb.tile_roots, rb.tile_live, rb.hist, rb.kdev + 2);
   const int32_t* kin = rb.key_a;
   const int32_t* vin = nullptr;
   int32_t* kout = rb.key_b;
@@ -706,6 +729,7 @@ static GatherArgs gather_args(const void* feats, const float* nsum, const int32_
   a.feats = feats; a.nsum = nsum; a.node_map = node_map; a.lvl = node_level; a.order = rb.order; a.orow = rb.orow;
   a.seg = rb.seg; a.kdev = rb.kdev; a.capacity = capacity; a.merged = merged; a.counts = counts;
   a.bigpart = rb.bigpart; a.bigw = rb.bigw;
+  a.biglist = reinterpret_cast<int4*>(rb.biglist); a.bigcount = rb.kdev + 2;
   return a;
 }
 
@@ -726,25 +750,21 @@ void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, co
   }
 }
 
-// ... and the clusters with more than kBig slots (two kernels that exit at once when there are none).
+// ... and the means of the clusters with more than kBig slots from the partial sums the gather left behind.
 void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                        const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
                        const ReduceBuffers& rb, hipStream_t s) {
-  const int nwin = (g.N + kBig - 1) / kBig;
+  const int nmax = (int)reduce_biglist_entries(g);
   const int nw = g.nC < 16 ? g.nC : 16;
-  dim3 gridw(nwin), block(64 * nw);
+  dim3 grid(nmax < kBigGrid ? nmax : kBigGrid), block(64 * nw);
   const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb);
-#define STTM_BIG(DT, ODT)                                                          \
-  do {                                                                             \
-    hipLaunchKernelGGL((k_reduce_big_partial<DT>), gridw, block, 0, s, g, a);      \
-    hipLaunchKernelGGL((k_reduce_big_combine<DT, ODT>), gridw, block, 0, s, g, a); \
-  } while (0)
   if (g.dtype == 1) {
-    if (out_dtype == 1) STTM_BIG(1, 1); else STTM_BIG(1, 0);
+    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce_big_combine<1, 1>), grid, block, 0, s, g, a);
+    else hipLaunchKernelGGL((k_reduce_big_combine<1, 0>), grid, block, 0, s, g, a);
   } else {
-    if (out_dtype == 1) STTM_BIG(0, 1); else STTM_BIG(0, 0);
+    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce_big_combine<0, 1>), grid, block, 0, s, g, a);
+    else hipLaunchKernelGGL((k_reduce_big_combine<0, 0>), grid, block, 0, s, g, a);
   }
-#undef STTM_BIG
 }
 
 }  // namespace sttm

@@ -293,10 +293,21 @@ __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __
     node_decode(g, idx, lvl, by, bx);
     float n = 0.f, d = 0.f;
     if (node_exists(g, lvl, by, bx)) {
-      for (int c = 0; c < g.nC; ++c) {
-        const float* p = part + (size_t)(f * g.nC + c) * 2 * g.NN;
-        if (lvl == 0) n += p[idx];
-        if (lvl < g.L) d += p[g.NN + idx];
+      const float* p = part + (size_t)f * g.nC * 2 * g.NN + idx;
+      const bool want_n = lvl == 0, want_d = lvl < g.L;
+      for (int c0 = 0; c0 < g.nC; c0 += 8) {  // eight chunks' partials in flight, added in chunk order
+        float pn[8], pd[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const bool in = c0 + u < g.nC;
+          pn[u] = in && want_n ? p[(size_t)(c0 + u) * 2 * g.NN] : 0.f;
+          pd[u] = in && want_d ? p[(size_t)(c0 + u) * 2 * g.NN + g.NN] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          n += pn[u];
+          d += pd[u];
+        }
       }
     }
     s_n[idx] = n;
@@ -451,9 +462,10 @@ void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_lev
 // order-preserving integer image of v finds the smallest value whose cumulative weight exceeds
 // target - base, then the largest value below it; tau is the midpoint of the two.
 // The level-0 histogram is filled by the statistics pass of the stage; two launches follow, grid
-// (slices, videos): every workgroup re-derives the prefix found so far from the (complete) earlier
-// histograms and bins its slice under it (the second also collects the largest key below the prefix); a
-// last small launch resolves the last digit and writes tau.
+// (slices, videos): every workgroup finds the next digit from the (complete) histogram of the level before
+// and bins its slice under the prefix (the second also collects the largest key below the prefix); a last
+// small launch resolves the last digit and writes tau. Each launch leaves what it found in the state, so the
+// next one resolves one digit only.
 // Input: keys[video][per_video] (0 = not an element), weights (NULL = 1 for every element).
 // ------------------------------------------------------------------------------------------------
 constexpr int kSelPer = 8;   // elements per thread and pass
@@ -504,9 +516,13 @@ __device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long
   __syncthreads();
   const bool found = s_found != 0;
   if (found && below) {
+    int mine = -1;  // largest non-empty bin below the found one: per thread, per wavefront, then one LDS atomic each
 #pragma unroll
     for (int j = 0; j < PER; ++j)
-      if (h[j] && tid * PER + j < (int)s_digit) atomicMax(&s_below, tid * PER + j);
+      if (h[j] && tid * PER + j < (int)s_digit) mine = tid * PER + j;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mine = max(mine, __shfl_xor(mine, o, 64));
+    if (lane == 0 && mine >= 0) atomicMax(&s_below, mine);
     __syncthreads();
     *below = s_below;
   }
@@ -534,36 +550,17 @@ __device__ inline int sel_base(const Geo& g, int b, int base_const, const int32_
   return r;
 }
 
-// Resolves the levels before `upto`: prefix of the searched key and the weight below it.
-// Returns 0 = fine, 1 = everything fits (tau = 1), 2 = even the base exceeds the target (tau = -2).
-__device__ inline int sel_resolve(const Geo& g, const SelState* st, int upto, int target, int base,
-                                  unsigned* prefix, unsigned long long* budget_out,
-                                  unsigned long long* acc_out) {
-  const long long budget = (long long)target - base;
-  *prefix = 0;
-  *budget_out = 0;
-  *acc_out = 0;
-  if (budget < 0) return 2;
-  *budget_out = (unsigned long long)budget;
-  unsigned long long acc = 0;
-  for (int p = 0; p < upto; ++p) {
-    unsigned d;
-    unsigned long long a2;
-    if (!sel_pick(st->hist[p], acc, (unsigned long long)budget, &d, &a2, nullptr)) return 1;
-    *prefix = (*prefix << sel_width(p)) | d;
-    acc = a2;
-  }
-  *acc_out = acc;
-  return 0;
-}
-
-// Clears what a search leaves behind (levels 1-2, the lower neighbour, the counter); level 0 stays.
+// Clears what a search leaves behind (levels 1-2, the lower neighbour); level 0 stays.
 __global__ __launch_bounds__(256) void k_select_reset(SelState* st) {
   SelState* s = st + blockIdx.x;
   for (int j = threadIdx.x; j < kSelBins; j += blockDim.x) s->hist[1][j] = s->hist[2][j] = 0;
   if (threadIdx.x == 0) s->lo_out = 0;
 }
 
+// One digit of the search per launch, grid (slices, videos). Every workgroup finds the digit of level
+// PASS - 1 from that level's (complete) histogram -- the first launch also works out the budget, the second
+// starts from what the first one left in the state -- and bins its slice of the keys under the prefix found
+// so far; the workgroup of slice 0 leaves the prefix for the next launch.
 template <int PASS>  // 1 or 2
 __global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32_t* __restrict__ keys,
                                                              const uint8_t* __restrict__ weights, int per_video,
@@ -573,30 +570,50 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32
   __shared__ unsigned hist[kSelBins];
   const int b = blockIdx.y, tid = threadIdx.x;
   SelState* st = states + b;
-  const int base = sel_base(g, b, base_const, node_map);
-  unsigned prefix;
-  unsigned long long budget, acc;
-  const int rc = sel_resolve(g, st, PASS, target[b], base, &prefix, &budget, &acc);
-  if (rc == 0) {
-    const uint32_t* kv = keys + (size_t)b * per_video;
-    const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
-    const int j0 = blockIdx.x * (kSelThreads * kSelPer);
-    uint32_t key[kSelPer];
-    unsigned w[kSelPer];
+  // the slice's keys do not depend on the search: their loads fly while the digit is being found
+  const uint32_t* kv = keys + (size_t)b * per_video;
+  const uint8_t* wv = weights ? weights + (size_t)b * per_video : nullptr;
+  const int j0 = blockIdx.x * (kSelThreads * kSelPer);
+  uint32_t key[kSelPer];
+  unsigned w[kSelPer];
 #pragma unroll
-    for (int u = 0; u < kSelPer; ++u) {
-      const int j = j0 + u * kSelThreads + tid;
-      key[u] = j < per_video ? kv[j] : 0u;
-      w[u] = 1u;
-      if (wv) w[u] = j < per_video ? wv[j] : 0u;
-      if (w[u] == 0) key[u] = 0;
+  for (int u = 0; u < kSelPer; ++u) {
+    const int j = j0 + u * kSelThreads + tid;
+    key[u] = j < per_video ? kv[j] : 0u;
+    w[u] = 1u;
+    if (wv) w[u] = j < per_video ? wv[j] : 0u;
+  }
+  for (int j = tid; j < kSelBins; j += kSelThreads) hist[j] = 0;
+  SelFound fd;
+  if (PASS == 1) {
+    const int base = sel_base(g, b, base_const, node_map);
+    const long long budget = (long long)target[b] - base;
+    fd.budget = budget < 0 ? 0ull : (unsigned long long)budget;
+    fd.acc = 0;
+    fd.prefix = 0;
+    fd.rc = budget < 0 ? 2 : 0;
+  } else {
+    fd = st->found[0];
+  }
+  if (fd.rc == 0) {  // uniform over the workgroup
+    unsigned d;
+    unsigned long long a2;
+    if (sel_pick(st->hist[PASS - 1], fd.acc, fd.budget, &d, &a2, nullptr)) {
+      fd.prefix = (fd.prefix << sel_width(PASS - 1)) | d;
+      fd.acc = a2;
+    } else {
+      fd.rc = 1;
     }
+  }
+  if (blockIdx.x == 0 && tid == 0) st->found[PASS - 1] = fd;
+  __syncthreads();  // the LDS histogram is clear
+  if (fd.rc == 0) {
+    const unsigned prefix = fd.prefix;
     const int shift = sel_shift(PASS), width = sel_width(PASS);
-    for (int j = tid; j < kSelBins; j += kSelThreads) hist[j] = 0;
-    __syncthreads();
     unsigned lo = 0;  // key 0 is below every real value
 #pragma unroll
     for (int u = 0; u < kSelPer; ++u) {
+      if (w[u] == 0) key[u] = 0;
       const unsigned top = key[u] >> (shift + width);
       const bool valid = key[u] != 0 && top == prefix;
       wave_hist_add(hist, valid, (key[u] >> shift) & ((1u << width) - 1u), w[u]);
@@ -613,27 +630,22 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32
   }
 }
 
-// tau = midpoint between the searched key and the largest key below it.
-__global__ __launch_bounds__(kSelThreads) void k_select_tau(Geo g, const int* __restrict__ target, int base_const,
-                                                            const int32_t* __restrict__ node_map,
-                                                            const SelState* __restrict__ states,
+// Last digit, then tau = midpoint between the searched key and the largest key below it.
+__global__ __launch_bounds__(kSelThreads) void k_select_tau(const SelState* __restrict__ states,
                                                             float* __restrict__ tau) {
   const int b = blockIdx.x;
   const SelState* st = states + b;
-  const int base = sel_base(g, b, base_const, node_map);
-  unsigned prefix;
-  unsigned long long budget, acc;
-  const int rc = sel_resolve(g, st, 2, target[b], base, &prefix, &budget, &acc);
+  const SelFound fd = st->found[1];
   float t = 1.f;
-  if (rc == 2) {
+  if (fd.rc == 2) {
     t = -2.f;
-  } else if (rc == 0) {
+  } else if (fd.rc == 0) {
     unsigned d2;
     unsigned long long a2;
     int below;
-    if (sel_pick(st->hist[2], acc, budget, &d2, &a2, &below)) {
-      const unsigned over = (prefix << 10) | d2;
-      const unsigned lo_key = below >= 0 ? ((prefix << 10) | (unsigned)below) : st->lo_out;
+    if (sel_pick(st->hist[2], fd.acc, fd.budget, &d2, &a2, &below)) {
+      const unsigned over = (fd.prefix << 10) | d2;
+      const unsigned lo_key = below >= 0 ? ((fd.prefix << 10) | (unsigned)below) : st->lo_out;
       const float hi = key_float(over);
       const float lof = lo_key ? key_float(lo_key) : -2.f;
       t = 0.5f * (lof + hi);
@@ -653,7 +665,7 @@ static void launch_select(const Geo& g, const uint32_t* keys, const uint8_t* wei
                      node_map, st);
   hipLaunchKernelGGL(k_select_pass<2>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
                      node_map, st);
-  hipLaunchKernelGGL(k_select_tau, dim3(g.B), block, 0, s, g, target, base_const, node_map, st, tau);
+  hipLaunchKernelGGL(k_select_tau, dim3(g.B), block, 0, s, st, tau);
 }
 
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
