@@ -32,8 +32,15 @@ struct Geo {
   int N;         // B*T*H*W
 };
 
+// First node index of a level: sum over the finer levels k of (P >> k)^2 = 4 (P^2 - (P >> lvl)^2) / 3. Computed, not
+// looked up: with a per-lane level the table in the kernel arguments would cost a memory access each time.
+__host__ __device__ inline int level_base(const Geo& g, int lvl) {
+  const int q = g.P >> lvl;
+  return (g.P * g.P - q * q) * 4 / 3;
+}
+
 __host__ __device__ inline int node_index(const Geo& g, int lvl, int by, int bx) {
-  return g.lvl_base[lvl] + by * (g.P >> lvl) + bx;
+  return level_base(g, lvl) + by * (g.P >> lvl) + bx;
 }
 
 __host__ __device__ inline bool node_exists(const Geo& g, int lvl, int by, int bx) {
@@ -43,11 +50,11 @@ __host__ __device__ inline bool node_exists(const Geo& g, int lvl, int by, int b
 // Decodes a per-frame node index into (level, by, bx).
 __host__ __device__ inline void node_decode(const Geo& g, int idx, int& lvl, int& by, int& bx) {
   lvl = 0;
-  while (lvl < g.L && idx >= g.lvl_base[lvl + 1]) ++lvl;
-  int r = idx - g.lvl_base[lvl];
-  int side = g.P >> lvl;
-  by = r / side;
-  bx = r - by * side;
+  while (lvl < g.L && idx >= level_base(g, lvl + 1)) ++lvl;
+  const int r = idx - level_base(g, lvl);
+  const int sh = __builtin_ctz((unsigned)g.P) - lvl;  // the level's grid side is a power of two
+  by = r >> sh;
+  bx = r & ((1 << sh) - 1);
 }
 
 // ---- feature row access: one lane owns `VEC` consecutive channels ------------------------------------

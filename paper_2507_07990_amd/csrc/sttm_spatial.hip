@@ -15,7 +15,8 @@ namespace sttm {
 // add up row r.
 // The unit is walked quadrant by quadrant: 4 tiles (4x4, level 2) of 4 level-1 blocks of 4 cells. The row
 // loads of the next tile are issued before the current one is worked on; cells and blocks beyond the
-// grid's edge cost neither loads nor arithmetic (the tests are wave-uniform).
+// grid's edge cost no arithmetic (the tests are wave-uniform) and no memory traffic (their loads hit a row
+// the tile has just fetched).
 // Scalars: the squared norm of every cell, and for every node below the root the dot product of its sum
 // with its parent's sum. (The squared norm of a parent is the sum of its children's dot products with it,
 // which the finalize kernel adds up.)
@@ -28,18 +29,32 @@ namespace sttm {
 constexpr int kTileRows = 36;    // 16 n0 + 16 d0 + 4 d1
 constexpr int kRowStride = 68;   // 64 lanes + pad, keeps 16-byte alignment of every row
 
-// Issues the row loads of the tile whose top-left cell is (ty, tx); th x tw of its 4x4 cells are valid.
+// Issues the row loads of the tile whose top-left cell is (ty, tx); th x tw of its 4x4 cells are valid
+// (th, tw >= 1). Every one of the 16 loads is issued, without a condition: a cell beyond the edge, or a lane
+// beyond the last channel, reads a valid cell of the tile again (a cache hit) and tile_mask() discards it. The
+// number of loads in flight is then known at compile time, and the wavefront can wait for this tile's rows
+// while the next tile's are still on their way.
 template <int DT>
 __device__ __forceinline__ void tile_load(typename Row<DT>::Raw (&raw)[16], const typename Row<DT>::Elem* fbase,
-                                          int W, int D, int ty, int tx, int th, int tw, bool act) {
+                                          int W, int D, int ty, int tx, int th, int tw) {
+  typedef Row<DT> R;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int q1 = i >> 2, k = i & 3;
+    const int dy = min((q1 >> 1) * 2 + (k >> 1), th - 1), dx = min((q1 & 1) * 2 + (k & 1), tw - 1);
+    raw[i] = *reinterpret_cast<const typename R::Raw*>(fbase + (size_t)((ty + dy) * W + tx + dx) * D);
+  }
+}
+
+// Zeroes what tile_load fetched for cells beyond the edge and for lanes beyond the last channel.
+template <int DT>
+__device__ __forceinline__ void tile_mask(typename Row<DT>::Raw (&raw)[16], int th, int tw, bool act) {
   typedef Row<DT> R;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int q1 = i >> 2, k = i & 3;
     const int dy = (q1 >> 1) * 2 + (k >> 1), dx = (q1 & 1) * 2 + (k & 1);
-    raw[i] = R::zero();
-    if (dy < th && dx < tw && act)
-      raw[i] = *reinterpret_cast<const typename R::Raw*>(fbase + (size_t)((ty + dy) * W + tx + dx) * D);
+    if (!(dy < th && dx < tw && act)) raw[i] = R::zero();
   }
 }
 
@@ -120,8 +135,6 @@ __device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>:
   wave_lds_fence();
 }
 
-constexpr int kFramesPerWave = 1;  // a wavefront walks the same unit of this many consecutive frames
-
 template <int DT>
 __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
                                                       float* __restrict__ part, float* __restrict__ nsum,
@@ -129,21 +142,19 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   __shared__ float tb[kTileRows * kRowStride];
-  const int chunk = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
-  const int f0 = blockIdx.z * kFramesPerWave, f1 = min(f0 + kFramesPerWave, g.F);
+  const int chunk = blockIdx.x, u = blockIdx.y, f = blockIdx.z, lane = threadIdx.x;
   const int ch0 = chunk * g.cch + lane * VEC;
   const bool act = ch0 < g.D;
   const int H = g.H, W = g.W, L = g.L;
-  const size_t frame_elems = (size_t)g.HW * g.D;
   const typename R::Elem* fbase =
-      reinterpret_cast<const typename R::Elem*>(feats_v) + (size_t)f0 * frame_elems + (act ? ch0 : 0);
+      reinterpret_cast<const typename R::Elem*>(feats_v) + (size_t)f * g.HW * g.D + (act ? ch0 : 0);
   const int UX = (W + 7) >> 3;  // units per row that hold valid cells
   const int y3 = (u / UX) * 8, x3 = (u % UX) * 8;
   const int vh = min(8, H - y3), vw = min(8, W - x3);  // valid rows / columns of the unit
 
   typename R::Raw bufA[16], bufB[16];
-  tile_load<DT>(bufA, fbase, W, g.D, y3, x3, min(vh, 4), min(vw, 4), act);
-  for (int f = f0; f < f1; ++f, fbase += frame_elems) {
+  tile_load<DT>(bufA, fbase, W, g.D, y3, x3, min(vh, 4), min(vw, 4));
+  {
     if (chunk == 0 && u == 0 && f % g.T == 0) sel_clear(sel + f / g.T);  // this video's budget search starts afresh
     float* pn = part + (size_t)(f * g.nC + chunk) * 2 * g.NN;
     float* pd = pn + g.NN;
@@ -154,14 +165,17 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
     for (int q2 = 0; q2 < 4; ++q2) {
       const int ty = y3 + (q2 >> 1) * 4, tx = x3 + (q2 & 1) * 4;
       const int th = max(0, min(4, vh - (q2 >> 1) * 4)), tw = max(0, min(4, vw - (q2 & 1) * 4));
-      {  // the next tile's rows (the first tile of the next frame after the last one) fly while this one is worked on
-        const int n = (q2 + 1) & 3;
-        const typename R::Elem* nb = q2 < 3 ? fbase : fbase + frame_elems;
-        int nh = max(0, min(4, vh - (n >> 1) * 4)), nw = max(0, min(4, vw - (n & 1) * 4));
-        if (nh == 0 || nw == 0 || (q2 == 3 && f + 1 >= f1)) nh = nw = 0;
-        tile_load<DT>((q2 & 1) ? bufA : bufB, nb, W, g.D, y3 + (n >> 1) * 4, x3 + (n & 1) * 4, nh, nw, act);
+      if (q2 < 3) {
+        // the next tile's rows fly while this one is worked on; a tile wholly beyond the edge reads the
+        // first tile again instead (nothing is done with it), so that the loads stay unconditional
+        const int n = q2 + 1;
+        const int nh = max(0, min(4, vh - (n >> 1) * 4)), nw = max(0, min(4, vw - (n & 1) * 4));
+        const bool none = nh == 0 || nw == 0;
+        tile_load<DT>((q2 & 1) ? bufA : bufB, fbase, W, g.D, none ? y3 : y3 + (n >> 1) * 4,
+                      none ? x3 : x3 + (n & 1) * 4, none ? 1 : nh, none ? 1 : nw);
       }
       if (th > 0 && tw > 0) {
+        tile_mask<DT>((q2 & 1) ? bufB : bufA, th, tw, act);
         tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, ty, tx, th, tw, pn, pd, S2[q2]);
       } else {
 #pragma unroll
@@ -259,7 +273,7 @@ __global__ __launch_bounds__(64) void k_pyramid_upper(Geo g, float* __restrict__
 void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
                           hipStream_t s) {
   const int UX = (g.W + 7) / 8, UY = (g.H + 7) / 8;
-  dim3 grid(g.nC, UX * UY, (g.F + kFramesPerWave - 1) / kFramesPerWave), block(64);
+  dim3 grid(g.nC, UX * UY, g.F), block(64);
   if (g.dtype == 1)
     hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, 0, s, g, feats, part, nsum, sel);
   else
