@@ -18,6 +18,8 @@ oracle takes the paper's steps in the paper's order:
       one towards the top-left                               (Sec. 3.3)
   O6  common root of every chain of edges                    (Sec. 3.3, union-find)
   O8  one token per connected graph: the average             (Sec. 3.1 / 3.3)
+  O10 linear order of the merged tokens and their position
+      indices under the three strategies                     (Sec. 3.4, "Token Reordering after Merging")
   O9  thresholds from a token budget                         (Sec. 4.1 tunes them by hand; Sec. 5 names the
                                                               automatic search as future work -- the rule
                                                               here is this build's own reading)
@@ -32,7 +34,16 @@ notes of the repository):
   * "towards top-left" = smallest (y0, x0) in raster order;
   * temporal similarities use the spatial node means only (frame pairs are
     independent); the final token is the mean over the original member cells;
-  * output rows are ordered by the root's (video, frame, y0, x0).
+  * output rows are ordered by the root's (video, frame, y0, x0); with order="zscan" the spatial key inside a
+    frame is the Z-shaped (Morton) rank of (y0, x0) instead of the raster one (Sec. 3.4 names a Z-shaped scan
+    and gives earlier frames precedence: read as frame first, then the spatial scan inside the frame);
+  * position indices (Sec. 3.4): "survived" = the original index of the root token, "reassigned" = the new
+    index in the video's output order, "merged" = the mean of the member tokens' original indices (the
+    index-level counterpart of averaging their rotary embeddings);
+  * destination choice (Sec. 3.3 and the "Approximated Temporal Matching" ablation): "first_passing" tests
+    every overlapping destination and takes the top-left-most passing one (default); "topleft_only" tests
+    only the destination under the source's top-left cell; "most_similar" takes the passing destination with
+    the highest similarity (ties: top-left-most).
 
 Parity pins live in tests/ (library pooling/cosine on full grids, brute-force
 enumeration of quadtree cuts, generic rectangle intersection, connected
@@ -391,13 +402,35 @@ def temporal_candidates(feats: np.ndarray, node_map: np.ndarray, node_level: np.
     return cands, ncmp
 
 
-def temporal_merge(feats: np.ndarray, node_map: np.ndarray, node_level: np.ndarray, tau_t,
-                   cands=None, decide=None) -> TemporalResult:
-    """Steps O5-O7 (Sec. 3.3): directed edges to the previous frame, top-left priority,
-    then the common root of every chain.
+MATCH_MODES = ("first_passing", "topleft_only", "most_similar")
 
+
+def best_similarity(cands, node_map: np.ndarray, mode: str = "first_passing"):
+    """e_n: the similarity that decides whether node n merges at all -- the largest one over its candidates,
+    or, when only the destination under n's top-left cell is tested, that destination's."""
+    B, T, H, W = node_map.shape
+    HW = H * W
+    flat = node_map.reshape(-1)
+    e = {}
+    for n, lst in cands.items():
+        if mode == "topleft_only":
+            d0 = int(flat[n - HW])            # the kept node of frame t-1 covering n's top-left cell
+            e[n] = dict(lst)[d0]
+        else:
+            e[n] = max(s for _, s in lst)
+    return e
+
+
+def temporal_merge(feats: np.ndarray, node_map: np.ndarray, node_level: np.ndarray, tau_t,
+                   cands=None, decide=None, mode: str = "first_passing", choose=None) -> TemporalResult:
+    """Steps O5-O7 (Sec. 3.3): directed edges to the previous frame, then the common root of every chain.
+
+    ``mode`` picks the destination among several overlapping ones (see MATCH_MODES).
     ``decide(n, d, sigma)`` is the near-threshold hook, consulted only when |sigma - tau_t| <= BAND.
+    ``choose(n, passing)`` (most_similar only) is consulted when another passing destination comes within BAND
+    of the best one; it returns the destination to take, or None.
     """
+    assert mode in MATCH_MODES
     B, T, H, W, D = feats.shape
     HW = H * W
     tau = np.broadcast_to(np.asarray(tau_t, dtype=np.float64), (B,))
@@ -405,20 +438,43 @@ def temporal_merge(feats: np.ndarray, node_map: np.ndarray, node_level: np.ndarr
     if cands is None:
         cands, res.comparisons = temporal_candidates(feats, node_map, node_level)
     res.cands = cands
-    res.e = {n: max(s for _, s in lst) for n, lst in cands.items()}
+    res.e = best_similarity(cands, node_map, mode)
     parent = np.full(B * T * HW, -1, dtype=np.int64)
+    flat_map = node_map.reshape(-1)
+
+    def passes(n, b, d, sig):
+        ok = sig > tau[b]
+        if decide is not None and abs(sig - tau[b]) <= BAND:
+            res.near += 1
+            forced = decide(n, d, sig)
+            if forced is not None:
+                ok = bool(forced)
+        return ok
+
     for n, lst in cands.items():
         b = n // (T * HW)
-        for d, sig in sorted(lst):                 # raster order = ascending flat index
-            ok = sig > tau[b]
-            if decide is not None and abs(sig - tau[b]) <= BAND:
-                res.near += 1
-                forced = decide(n, d, sig)
-                if forced is not None:
-                    ok = bool(forced)
+        ordered = sorted(lst)                      # raster order = ascending flat index
+        if mode == "first_passing":
+            for d, sig in ordered:
+                if passes(n, b, d, sig):
+                    parent[n] = d
+                    break
+        elif mode == "topleft_only":
+            d0 = int(flat_map[n - HW])
+            sig = dict(lst)[d0]
+            if passes(n, b, d0, sig):
+                parent[n] = d0
+        else:
+            ok = [(d, sig) for d, sig in ordered if passes(n, b, d, sig)]
             if ok:
-                parent[n] = d
-                break
+                top = max(sig for _, sig in ok)
+                pick = min(d for d, sig in ok if sig == top)
+                if choose is not None and sum(1 for _, sig in ok if sig >= top - BAND) > 1:
+                    res.near += 1
+                    forced = choose(n, [(d, sig) for d, sig in ok if sig >= top - BAND])
+                    if forced is not None:
+                        pick = int(forced)
+                parent[n] = pick
     res.parent = parent.reshape(B, T, H, W).astype(np.int32)
     flat_nodes = node_map.reshape(-1).astype(np.int64)
     root_of: Dict[int, int] = {}
@@ -446,13 +502,40 @@ class ReduceResult:
         self.offsets = None   # int64 [B+1]
 
 
-def reduce_clusters(feats: np.ndarray, cluster_ids: np.ndarray) -> ReduceResult:
-    """Step O8: one output token per cluster = mean over its member cells, rows in
-    ascending cluster id (video, frame, raster top-left of the root; Sec. 3.4)."""
+def zscan_rank(y: int, x: int) -> int:
+    """Rank of cell (y, x) in the Z-shaped scan of a power-of-two grid (Sec. 3.4): quadrant by quadrant,
+    top-left, top-right, bottom-left, bottom-right, recursively -- the bits of y and x interleaved, x lowest."""
+    z = 0
+    bit = 0
+    while (y >> bit) or (x >> bit):
+        z |= ((x >> bit) & 1) << (2 * bit)
+        z |= ((y >> bit) & 1) << (2 * bit + 1)
+        bit += 1
+    return z
+
+
+def output_order(out_ids, shape, order: str = "raster"):
+    """Permutation of the clusters (given by their ids = flat index of the root's top-left cell) into the
+    linear order of Sec. 3.4: earlier frames first, inside a frame the spatial scan of the root's top-left."""
+    B, T, H, W = shape
+    assert order in ("raster", "zscan")
+
+    def key(cid):
+        f, c = divmod(int(cid), H * W)
+        y, x = divmod(c, W)
+        return (f, y * W + x) if order == "raster" else (f, zscan_rank(y, x))
+
+    return sorted(range(len(out_ids)), key=lambda k: key(out_ids[k]))
+
+
+def reduce_clusters(feats: np.ndarray, cluster_ids: np.ndarray, order: str = "raster") -> ReduceResult:
+    """Step O8: one output token per cluster = mean over its member cells, rows in the order of Sec. 3.4
+    (video, frame, spatial scan of the root's top-left; raster = ascending cluster id)."""
     B, T, H, W, D = feats.shape
     N = B * T * H * W
     flat = cluster_ids.reshape(-1).astype(np.int64)
     out_ids = np.unique(flat)
+    out_ids = out_ids[output_order(out_ids, (B, T, H, W), order)]
     members: Dict[int, List[int]] = {int(k): [] for k in out_ids}
     for i in range(N):
         members[int(flat[i])].append(i)
@@ -465,7 +548,45 @@ def reduce_clusters(feats: np.ndarray, cluster_ids: np.ndarray) -> ReduceResult:
         res.merged[k] = widen(rows[cells]).sum(axis=0) / len(cells)
         res.counts[k] = len(cells)
     res.out_ids = out_ids.astype(np.int32)
-    res.offsets = np.searchsorted(out_ids, np.arange(B + 1) * (T * H * W)).astype(np.int64)
+    res.offsets = np.array([int((out_ids < b * T * H * W).sum()) for b in range(B + 1)], dtype=np.int64)
+    return res
+
+
+class PositionResult:
+    def __init__(self):
+        self.survived = None    # int32 [K]: original index (within the video) of the surviving root token
+        self.reassigned = None  # int32 [K]: index of the row in the video's output sequence
+        self.merged = None      # float64 [K]: mean original index of the member tokens
+        self.root = None        # int32 [K, 4]: (t, y0, x0, level) of the root node
+
+
+def positions(cluster_ids: np.ndarray, node_level: np.ndarray, order: str = "raster") -> PositionResult:
+    """Step O10 (Sec. 3.4): position indices of the output rows under the three strategies the paper
+    evaluates, plus the root's (t, y, x) for encodings built on those coordinates."""
+    B, T, H, W = cluster_ids.shape
+    N1 = T * H * W
+    flat = cluster_ids.reshape(-1).astype(np.int64)
+    out_ids = np.unique(flat)
+    out_ids = out_ids[output_order(out_ids, (B, T, H, W), order)]
+    res = PositionResult()
+    K = len(out_ids)
+    res.survived = np.empty(K, dtype=np.int32)
+    res.reassigned = np.empty(K, dtype=np.int32)
+    res.merged = np.empty(K, dtype=np.float64)
+    res.root = np.empty((K, 4), dtype=np.int32)
+    seen = [0] * B
+    lv = node_level.reshape(-1)
+    for k, cid in enumerate(out_ids):
+        cid = int(cid)
+        b, loc = divmod(cid, N1)
+        t, c = divmod(loc, H * W)
+        y0, x0 = divmod(c, W)
+        res.survived[k] = loc
+        res.reassigned[k] = seen[b]
+        seen[b] += 1
+        cells = np.nonzero(flat == cid)[0]
+        res.merged[k] = float((cells - b * N1).sum()) / len(cells)
+        res.root[k] = (t, y0, x0, int(lv[cid]))
     return res
 
 
@@ -488,19 +609,21 @@ def spatial_budget_inputs(stats, B: int, T: int):
     return out
 
 
-def temporal_budget_inputs(cands, node_map: np.ndarray):
+def temporal_budget_inputs(cands, node_map: np.ndarray, mode: str = "first_passing"):
     """Per video: (values e_n over nodes of frames >= 1, weights 1, base = nodes of frame 0)."""
     B, T, H, W = node_map.shape
     out = []
+    e = best_similarity(cands, node_map, mode)
     for b in range(B):
         n_nodes = len(np.unique(node_map[b]))
         lo, hi = b * T * H * W, (b + 1) * T * H * W
-        vals = [max(s for _, s in lst) for n, lst in cands.items() if lo <= n < hi]
+        vals = [e[n] for n in cands if lo <= n < hi]
         out.append((vals, [1] * len(vals), n_nodes - len(vals)))
     return out
 
 
-def sttm(feats: np.ndarray, tau_s=None, tau_t=None, keep=None, root_grid: int = 1):
+def sttm(feats: np.ndarray, tau_s=None, tau_t=None, keep=None, root_grid: int = 1, mode: str = "first_passing",
+         order: str = "raster"):
     """The whole path.  Either fixed thresholds, or ``keep`` (fraction of each video's
     T*H*W tokens to retain): sqrt(keep) after the spatial stage, keep after the temporal one."""
     B, T, H, W, D = feats.shape
@@ -518,11 +641,11 @@ def sttm(feats: np.ndarray, tau_s=None, tau_t=None, keep=None, root_grid: int = 
     if tau_t is None:
         keep_b = np.broadcast_to(np.asarray(keep, dtype=np.float64), (B,))
         tau_t = []
-        for b, (vals, wts, base) in enumerate(temporal_budget_inputs(cands, sp.node_map)):
+        for b, (vals, wts, base) in enumerate(temporal_budget_inputs(cands, sp.node_map, mode)):
             target = int(math.floor(keep_b[b] * T * H * W))
             tau_t.append(budget_threshold(vals, wts, base, target)[0])
         info["tau_t"] = list(tau_t)
-    tm = temporal_merge(feats, sp.node_map, sp.node_level, tau_t, cands=cands)
+    tm = temporal_merge(feats, sp.node_map, sp.node_level, tau_t, cands=cands, mode=mode)
     tm.comparisons = ncmp
-    rd = reduce_clusters(feats, tm.cluster_ids)
+    rd = reduce_clusters(feats, tm.cluster_ids, order)
     return sp, tm, rd, info

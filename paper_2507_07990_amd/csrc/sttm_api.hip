@@ -205,8 +205,8 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
     launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum),
                          at<SelState>(c, c->lay.sel_s), c->stream);
   }
-  launch_pyramid_upper(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum), c->stream);
-  launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nrm2), at<float>(c, c->lay.sim),
+  launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum), at<float>(c, c->lay.nrm2),
+                          at<float>(c, c->lay.sim),
                           at<float>(c, c->lay.m), at<uint32_t>(c, c->lay.sel_key_s), at<uint8_t>(c, c->lay.sel_w_s),
                           at<SelState>(c, c->lay.sel_s), c->stream);
   int rc = after_launch(c);

@@ -130,8 +130,13 @@ struct SelFound {
   unsigned prefix;            // leading digits of the searched key found so far
   int rc;                     // 0 = searching, 1 = everything fits (tau = 1), 2 = the base alone exceeds the target
 };
+// The level-0 histogram is fed by hundreds of workgroups whose values fall into a handful of bins; it is kept
+// in kSelCopies copies, one per accelerator die (workgroups go to the dies round-robin by their index), so that
+// the hot counters stay in one die's L2 instead of travelling between the dies with every atomic.
+constexpr int kSelCopies = 8;
 struct SelState {
-  unsigned hist[3][kSelBins];  // weight per digit: level 0 over all elements, levels 1-2 under the found prefix
+  unsigned hist0[kSelCopies][kSelBins];  // weight per leading digit over all elements; the copies add up
+  unsigned hist[2][kSelBins];            // second and third digit under the found prefix
   unsigned lo_out;             // largest key whose leading 22 bits are below the found prefix (0 = none)
   unsigned pad0[3];
   SelFound found[2];           // after the first / second digit
@@ -164,8 +169,9 @@ __device__ inline void wave_hist_add(unsigned* hist, bool valid, unsigned digit,
 
 // Adds a workgroup's LDS histogram of leading digits to the state's level-0 histogram (call after a barrier).
 __device__ inline void sel_flush_level0(SelState* st, const unsigned* lds_hist) {
+  unsigned* dst = st->hist0[blockIdx.x % kSelCopies];
   for (int j = threadIdx.x; j < kSelBins; j += blockDim.x)
-    if (lds_hist[j]) atomicAdd(&st->hist[0][j], lds_hist[j]);
+    if (lds_hist[j]) atomicAdd(&dst[j], lds_hist[j]);
 }
 
 // ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
@@ -173,9 +179,8 @@ __device__ inline void sel_flush_level0(SelState* st, const unsigned* lds_hist) 
 // `sel`: the spatial search states [B]; cleared by the statistics pass, level 0 filled by the finalize kernel.
 void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
                           hipStream_t s);
-// Levels above an 8x8 unit from the stored unit sums (nothing to do when the pyramid is no taller).
-void launch_pyramid_upper(const Geo& g, float* part, float* nsum, hipStream_t s);
-void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
+// Also works out the levels above an 8x8 unit from the stored unit sums (extends `part` and `nsum`).
+void launch_spatial_finalize(const Geo& g, float* part, float* nsum, float* nrm2, float* sim, float* m,
                              uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s);
 void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
                            uint8_t* node_level, hipStream_t s);

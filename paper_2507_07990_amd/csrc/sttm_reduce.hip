@@ -390,7 +390,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
     }
   }
 #pragma unroll
-  for (int r = 0; r < kSortPer; ++r) {
+  for (int r = 0; r < kSortPer; ++r) {  // the stores of one round travel while the next round's cursors are read
     const int digit = (key[r] >> a.shift) & (DIG - 1);
     if (ok[r]) {
       const int dst = mycur[digit] + __popcll(same[r] & below);

@@ -219,13 +219,12 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_pyramid_upper: levels 4..L from the stored level-3 sums, one wavefront per (chunk, frame); a lane owns
-// four channels (the chunk is covered in VEC/4 sweeps). For every node: the sum of its existing children
-// (stored next to the level-3 sums) and the partial dot product of every child with it, in the same
-// per-chunk tables as above.
+// pyramid_upper: levels 4..L of one frame from the stored level-3 sums, for one chunk, by one wavefront; a
+// lane owns four channels (the chunk is covered in VEC/4 sweeps). For every node: the sum of its existing
+// children (stored next to the level-3 sums) and the partial dot product of every child with it, in the same
+// per-chunk tables as above. Runs at the head of the finalize kernel.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_pyramid_upper(Geo g, float* __restrict__ part, float* __restrict__ nsum) {
-  const int chunk = blockIdx.x, f = blockIdx.y, lane = threadIdx.x;
+__device__ inline void pyramid_upper(const Geo& g, float* part, float* nsum, int chunk, int f, int lane) {
   const int NB = g.NN - g.lvl_base[3];
   float* pd = part + (size_t)(f * g.nC + chunk) * 2 * g.NN + g.NN;
   float* rows = nsum + (size_t)f * NB * g.D;
@@ -280,16 +279,13 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* n
     hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, 0, s, g, feats, part, nsum, sel);
 }
 
-void launch_pyramid_upper(const Geo& g, float* part, float* nsum, hipStream_t s) {
-  if (g.L > 3) hipLaunchKernelGGL(k_pyramid_upper, dim3(g.nC, g.F), dim3(64), 0, s, g, part, nsum);
-}
-
 // ------------------------------------------------------------------------------------------------
-// k_spatial_finalize: one workgroup per frame. Sums the per-chunk partials in chunk order, turns
+// k_spatial_finalize: one workgroup per frame. First the levels above the 8x8 units (one wavefront per chunk,
+// see pyramid_upper), then it sums the per-chunk partials in chunk order, turns
 // them into sigma(parent, child) (Sec. 3.2: cosine between a level's nodes and their children),
 // m_n = min over existing children, and the split score s_n = max of m along the path from the root.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __restrict__ part,
+__global__ __launch_bounds__(1024) void k_spatial_finalize(Geo g, float* part, float* __restrict__ nsum,
                                                           float* __restrict__ nrm2, float* __restrict__ sim,
                                                           float* __restrict__ m, uint32_t* __restrict__ sel_key,
                                                           uint8_t* __restrict__ sel_w,
@@ -302,6 +298,11 @@ __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __
   float* s_m = sm + 2 * g.NN;
   const int f = blockIdx.x;
   const size_t fo = (size_t)f * g.NN;
+  if (g.L > 3) {
+    const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    for (int chunk = wave; chunk < g.nC; chunk += nwaves) pyramid_upper(g, part, nsum, chunk, f, threadIdx.x & 63);
+    __syncthreads();  // the dot products written above are read below by other threads of this workgroup
+  }
   for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
     int lvl, by, bx;
     node_decode(g, idx, lvl, by, bx);
@@ -408,9 +409,11 @@ __global__ __launch_bounds__(256) void k_spatial_finalize(Geo g, const float* __
   sel_flush_level0(sel + f / g.T, h0);
 }
 
-void launch_spatial_finalize(const Geo& g, const float* part, float* nrm2, float* sim, float* m,
+void launch_spatial_finalize(const Geo& g, float* part, float* nsum, float* nrm2, float* sim, float* m,
                              uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s) {
-  hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(256), 3 * g.NN * sizeof(float), s, g, part, nrm2, sim,
+  const int threads = g.NN <= 256 ? 256 : (g.NN <= 512 ? 512 : 1024);  // one node per thread where it fits
+  hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(threads), 3 * g.NN * sizeof(float), s, g, part, nsum, nrm2,
+                     sim,
                      m, sel_key, sel_w, sel);
 }
 
@@ -491,6 +494,8 @@ __device__ inline int sel_width(int pass) { return pass == 2 ? 10 : 11; }
 // Workgroup-wide (256 threads): the first bin of `hist` at which acc + running weight exceeds `budget`.
 // Returns false when the whole histogram fits. All threads get the same answer.
 // *below = largest non-empty bin before the found one, or -1.
+// The histogram is the sum of `copies` arrays of kSelBins counters.
+template <int COPIES>
 __device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long long acc,
                                 unsigned long long budget, unsigned* digit, unsigned long long* acc_out,
                                 int* below) {
@@ -503,10 +508,13 @@ __device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long
   unsigned h[PER];
   unsigned long long tot = 0;
 #pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    h[j] = hist[tid * PER + j];
-    tot += h[j];
-  }
+  for (int j = 0; j < PER; ++j) h[j] = 0;
+#pragma unroll
+  for (int c = 0; c < COPIES; ++c)  // all loads at once
+#pragma unroll
+    for (int j = 0; j < PER; ++j) h[j] += hist[c * kSelBins + tid * PER + j];
+#pragma unroll
+  for (int j = 0; j < PER; ++j) tot += h[j];
   unsigned long long inc = tot;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
@@ -567,7 +575,7 @@ __device__ inline int sel_base(const Geo& g, int b, int base_const, const int32_
 // Clears what a search leaves behind (levels 1-2, the lower neighbour); level 0 stays.
 __global__ __launch_bounds__(256) void k_select_reset(SelState* st) {
   SelState* s = st + blockIdx.x;
-  for (int j = threadIdx.x; j < kSelBins; j += blockDim.x) s->hist[1][j] = s->hist[2][j] = 0;
+  for (int j = threadIdx.x; j < kSelBins; j += blockDim.x) s->hist[0][j] = s->hist[1][j] = 0;
   if (threadIdx.x == 0) s->lo_out = 0;
 }
 
@@ -612,7 +620,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32
   if (fd.rc == 0) {  // uniform over the workgroup
     unsigned d;
     unsigned long long a2;
-    if (sel_pick(st->hist[PASS - 1], fd.acc, fd.budget, &d, &a2, nullptr)) {
+    const bool hit = PASS == 1 ? sel_pick<kSelCopies>(st->hist0[0], fd.acc, fd.budget, &d, &a2, nullptr)
+                               : sel_pick<1>(st->hist[0], fd.acc, fd.budget, &d, &a2, nullptr);
+    if (hit) {
       fd.prefix = (fd.prefix << sel_width(PASS - 1)) | d;
       fd.acc = a2;
     } else {
@@ -640,7 +650,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32
     }
     __syncthreads();
     for (int j = tid; j < kSelBins; j += kSelThreads)
-      if (hist[j]) atomicAdd(&st->hist[PASS][j], hist[j]);
+      if (hist[j]) atomicAdd(&st->hist[PASS - 1][j], hist[j]);
   }
 }
 
@@ -657,7 +667,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_tau(const SelState* __re
     unsigned d2;
     unsigned long long a2;
     int below;
-    if (sel_pick(st->hist[2], fd.acc, fd.budget, &d2, &a2, &below)) {
+    if (sel_pick<1>(st->hist[1], fd.acc, fd.budget, &d2, &a2, &below)) {
       const unsigned over = (fd.prefix << 10) | d2;
       const unsigned lo_key = below >= 0 ? ((fd.prefix << 10) | (unsigned)below) : st->lo_out;
       const float hi = key_float(over);

@@ -400,10 +400,18 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* 
     const int a = pf.lvl_t[c], b = pf.lvl_p[c];
     const int n = pf.rep_t[c], d = pf.rep_p[c];
     if ((a <= b ? n : d) != c) continue;  // not the top-left cell of the finer node
-    float dot = 0.f;
-    for (int k = 0; k < g.nC; ++k) dot += pd_part[(size_t)(f * g.nC + k) * HW + c];
+    // the two norms and the per-chunk partial dot products, eight chunks in flight, added in chunk order
     const float nn = nrm2[(size_t)f * g.NN + node_idx_of(g, a, n / W, n % W)];
     const float nd = nrm2[(size_t)(f - 1) * g.NN + node_idx_of(g, b, d / W, d % W)];
+    float dot = 0.f;
+    const float* pp = pd_part + (size_t)f * g.nC * HW + c;
+    for (int k0 = 0; k0 < g.nC; k0 += 8) {
+      float pv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) pv[u] = k0 + u < g.nC ? pp[(size_t)(k0 + u) * HW] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) dot += pv[u];
+    }
     const float v = cosine_from(dot, nn, nd);
     sig[(size_t)f * HW + c] = v;
     if (v == v) atomicMax(&ekey[n], float_key(v));

@@ -506,3 +506,161 @@ def test_widen_is_exact():
     got = O.widen(bits)
     assert list(got[:2]) == [1.0, -1.0] and got[2] == 3.140625 and got[3] == 0.0
     assert got[4] == float(np.float32(3.3895313892515355e38))
+
+
+# ------------------------------------------------------------- O10: order ----
+def _zscan_recursive(P):
+    """Independent statement of the Z-shaped scan: visit the quadrants top-left, top-right, bottom-left,
+    bottom-right, each one recursively."""
+    if P == 1:
+        return [(0, 0)]
+    h = P // 2
+    sub = _zscan_recursive(h)
+    out = []
+    for qy, qx in ((0, 0), (0, 1), (1, 0), (1, 1)):
+        out += [(qy * h + y, qx * h + x) for y, x in sub]
+    return out
+
+
+def test_zscan_rank_matches_recursive_quadrant_walk_and_golden():
+    for P in (1, 2, 4, 8, 16, 32):
+        walk = _zscan_recursive(P)
+        assert [O.zscan_rank(y, x) for y, x in walk] == list(range(P * P))
+    rows = [tuple(int(v) for v in ln.split()) for ln in open(os.path.join(GOLDEN, "zscan_4x4.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    for rank, y, x in rows:
+        assert O.zscan_rank(y, x) == rank
+
+
+def test_output_order_is_frame_major_then_spatial_scan():
+    rng = np.random.default_rng(5)
+    B, T, H, W = 2, 3, 5, 6
+    ids = np.sort(rng.choice(B * T * H * W, size=40, replace=False))
+    for order in ("raster", "zscan"):
+        perm = O.output_order(ids, (B, T, H, W), order)
+        got = ids[perm]
+        # brute force: walk videos, frames, then the cells of the padded grid in scan order
+        P = 8
+        scan = [(y, x) for y in range(P) for x in range(P)] if order == "raster" else _zscan_recursive(P)
+        want = [f * H * W + y * W + x for f in range(B * T) for (y, x) in scan
+                if y < H and x < W and f * H * W + y * W + x in set(ids.tolist())]
+        assert got.tolist() == want
+    assert ids[O.output_order(ids, (B, T, H, W), "raster")].tolist() == ids.tolist()   # raster = ascending id
+
+
+def test_positions_hand_worked_golden():
+    cl = np.array([[[[0, 0], [2, 3]], [[0, 0], [6, 3]]]], dtype=np.int32)
+    lv = np.zeros_like(cl, dtype=np.uint8)
+    pr = O.positions(cl, lv)
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "positions_hand_2x2x2.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == len(pr.survived)
+    for k, (cid, sv, ra, mg) in enumerate(rows):
+        assert pr.survived[k] == int(sv) and pr.reassigned[k] == int(ra)
+        assert pr.merged[k] == pytest.approx(float(mg), abs=1e-12)
+    assert pr.root.tolist() == [[0, 0, 0, 0], [0, 1, 0, 0], [0, 1, 1, 0], [1, 1, 0, 0]]
+
+
+def test_positions_coincide_when_nothing_merges_and_collapse_to_the_centre_when_everything_does():
+    feats = _rand_video(21, 3, 4, 4, 8)
+    sp, tm, rd, _ = O.sttm(feats, tau_s=1.0, tau_t=1.0)
+    pr = O.positions(tm.cluster_ids, sp.node_level)
+    n = 3 * 16
+    assert pr.survived.tolist() == list(range(n)) == pr.reassigned.tolist()
+    np.testing.assert_array_equal(pr.merged, np.arange(n, dtype=np.float64))
+    sp, tm, rd, _ = O.sttm(feats, tau_s=-2.0, tau_t=-2.0)
+    pr = O.positions(tm.cluster_ids, sp.node_level)
+    assert pr.survived.tolist() == [0] and pr.reassigned.tolist() == [0]
+    assert pr.merged[0] == pytest.approx((n - 1) / 2)
+    assert pr.root.tolist() == [[0, 0, 0, 2]]
+
+
+def test_zscan_rows_are_a_permutation_of_raster_rows_within_each_frame():
+    feats = _rand_video(22, 4, 8, 8, 8)
+    sp, tm, rd, _ = O.sttm(feats, tau_s=0.7, tau_t=0.7)
+    rz = O.reduce_clusters(feats, tm.cluster_ids, "zscan")
+    assert sorted(rz.out_ids.tolist()) == rd.out_ids.tolist()
+    assert (rz.offsets == rd.offsets).all()
+    back = {int(c): k for k, c in enumerate(rd.out_ids)}
+    for k, c in enumerate(rz.out_ids):
+        np.testing.assert_array_equal(rz.merged[k], rd.merged[back[int(c)]])
+        assert rz.counts[k] == rd.counts[back[int(c)]]
+    frames = rz.out_ids // 64
+    assert (np.diff(frames) >= 0).all()                          # earlier frames first
+    pz = O.positions(tm.cluster_ids, sp.node_level, "zscan")
+    assert pz.reassigned.tolist() == list(range(len(rz.out_ids)))
+    assert pz.survived.tolist() == rz.out_ids.tolist()
+
+
+# ------------------------------------------------- O5: destination choice ----
+def _hand_candidates():
+    """One video, 2 frames of 2x2 cells. Frame 1 is ONE node (cells 4..7, top-left 4); frame 0 is four cells.
+    Candidate similarities of node 4 towards cells 0..3 are given directly."""
+    node_map = np.array([[[[0, 1], [2, 3]], [[4, 4], [4, 4]]]], dtype=np.int32)
+    node_level = np.array([[[[0, 0], [0, 0]], [[1, 1], [1, 1]]]], dtype=np.uint8)
+    feats = np.zeros((1, 2, 2, 2, 4), dtype=np.float32)
+    cands = {4: [(0, 0.50), (1, 0.90), (2, 0.95), (3, 0.70)]}
+    return feats, node_map, node_level, cands
+
+
+def test_destination_choice_hand_case():
+    """Sec. 3.3: several passing destinations -> the one towards the top-left; the ablation's alternatives are
+    the single top-left destination and the most similar one."""
+    feats, nm, nl, cands = _hand_candidates()
+    want = {"first_passing": 1, "topleft_only": -1, "most_similar": 2}
+    for mode, d in want.items():
+        tm = O.temporal_merge(feats, nm, nl, 0.8, cands=cands, mode=mode)
+        assert tm.parent[0, 1, 0, 0] == d
+        assert tm.cluster_ids[0, 1].tolist() == [[d if d >= 0 else 4] * 2] * 2
+    e = O.best_similarity(cands, nm, "topleft_only")
+    assert e[4] == 0.50 and O.best_similarity(cands, nm, "most_similar")[4] == 0.95
+    tm = O.temporal_merge(feats, nm, nl, 0.4, cands=cands, mode="topleft_only")
+    assert tm.parent[0, 1, 0, 0] == 0
+
+
+def _brute_parent(cands, node_map, tau, mode):
+    """The three rules stated once more, from the definitions, over explicit candidate lists."""
+    B, T, H, W = node_map.shape
+    flat = node_map.reshape(-1)
+    out = {}
+    for n, lst in cands.items():
+        passing = [(d, s) for d, s in lst if s > tau]
+        if mode == "first_passing":
+            out[n] = min((d for d, _ in passing), default=-1)
+        elif mode == "topleft_only":
+            d0 = int(flat[n - H * W])
+            out[n] = d0 if any(d == d0 for d, _ in passing) else -1
+        else:
+            out[n] = -1
+            if passing:
+                best = max(s for _, s in passing)
+                out[n] = min(d for d, s in passing if s == best)
+    return out
+
+
+@pytest.mark.parametrize("mode", O.MATCH_MODES)
+def test_destination_choice_against_restated_rules_and_relations(mode):
+    feats = _rand_video(31, 4, 8, 8, 16)
+    sp = O.spatial_quadtree(feats, 0.6)
+    cands, _ = O.temporal_candidates(feats, sp.node_map, sp.node_level)
+    tau = 0.55
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, tau, cands=cands, mode=mode)
+    want = _brute_parent(cands, sp.node_map, tau, mode)
+    par = tm.parent.reshape(-1)
+    assert {n: int(par[n]) for n in cands} == want
+    base = O.temporal_merge(feats, sp.node_map, sp.node_level, tau, cands=cands, mode="first_passing")
+    bpar = base.parent.reshape(-1)
+    merged, bmerged = {n for n in cands if par[n] >= 0}, {n for n in cands if bpar[n] >= 0}
+    if mode == "most_similar":
+        assert merged == bmerged                                   # a node merges iff any destination passes
+        for n in merged:
+            sims = dict(cands[n])
+            assert sims[int(par[n])] >= sims[int(bpar[n])]
+    if mode == "topleft_only":
+        assert merged <= bmerged
+        assert any(len(lst) > 1 for lst in cands.values())         # the case is not vacuous
+    for n, lst in cands.items():                                   # one candidate: every rule agrees
+        if len(lst) == 1:
+            assert par[n] == bpar[n]
+    # the number of clusters equals nodes minus edges under every rule
+    assert len(np.unique(tm.cluster_ids)) == len(np.unique(sp.node_map)) - len(merged)
