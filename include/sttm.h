@@ -57,6 +57,21 @@ typedef enum {
 typedef enum { STTM_F32 = 0, STTM_BF16 = 1 } sttm_dtype;
 typedef enum { STTM_STAGE_SPATIAL = 0, STTM_STAGE_TEMPORAL = 1 } sttm_stage;
 
+/* Which destination a node of frame t takes when it overlaps several kept nodes of frame t-1 (Sec. 3.3; the
+ * "Approximated Temporal Matching" ablation of Sec. 4.3 compares the top-left rule with the most similar one). */
+typedef enum {
+  STTM_MATCH_FIRST_PASSING = 0, /* every overlapping destination is tested; of those above tau_T the one towards
+                                   the top-left (smallest raster index) wins -- the rule of Sec. 3.3, the default */
+  STTM_MATCH_TOPLEFT_ONLY = 1,  /* only the destination under the node's own top-left cell is tested */
+  STTM_MATCH_MOST_SIMILAR = 2   /* of those above tau_T the most similar wins (ties: towards the top-left) */
+} sttm_match;
+
+/* Linear order of the output rows (Sec. 3.4): earlier frames first; inside a frame by the root's top-left cell. */
+typedef enum {
+  STTM_ORDER_RASTER = 0, /* (y0, x0) row by row = ascending cluster id; the default */
+  STTM_ORDER_ZSCAN = 1   /* Z-shaped scan: quadrants top-left, top-right, bottom-left, bottom-right, recursively */
+} sttm_order;
+
 /* Tables sttm_export() can copy out (parity tests compare them with the CPU oracle). F = B*T frames,
  * NN = nodes per frame over all levels of the P x P pyramid (see sttm_nodes_per_frame). */
 typedef enum {
@@ -89,6 +104,12 @@ size_t sttm_workspace_bytes(int B, int T, int H, int W, int D, int dtype, int ro
 /* Hands the library a device buffer (256-byte aligned) it may overwrite at will until the next
  * sttm_set_workspace / sttm_destroy. Tables of earlier stages live there between calls. */
 int sttm_set_workspace(sttm_ctx* ctx, void* workspace_dev, size_t bytes);
+
+/* Destination rule of the temporal stage (sttm_match); applies to the temporal calls that follow. With
+ * STTM_MATCH_TOPLEFT_ONLY the table BEST_SIM and the temporal budget use the similarity to that one destination. */
+int sttm_set_match_mode(sttm_ctx* ctx, int mode);
+/* Row order of sttm_reduce and sttm_positions (sttm_order); applies to the calls that follow. */
+int sttm_set_output_order(sttm_ctx* ctx, int order);
 
 /* ---- stage 1: spatial quadtree (Sec. 3.2) ------------------------------------------------------------- */
 
@@ -135,10 +156,10 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
 
 /* ---- stage 3: gather / average (Sec. 3.1, 3.3, 3.4) ---------------------------------------------------- */
 
-/* One output row per cluster, in ascending cluster id: merged [capacity, D] of out_dtype = mean of the member
+/* One output row per cluster, in ascending cluster id (see sttm_set_output_order): merged [capacity, D] of out_dtype = mean of the member
  * cells' features (fp32 accumulation in a fixed order); counts int32 [capacity] = members; out_ids int32 [capacity]
  * = cluster id; offsets int64 [B+1] = first row of each video, offsets[B] = K (all device, counts/out_ids may be
- * NULL). Rows beyond capacity are not written. n_out: host pointer or NULL; when non-NULL the stream is
+ * NULL). With STTM_ORDER_ZSCAN the rows of a frame follow the Z-shaped scan of their roots instead. Rows beyond capacity are not written. n_out: host pointer or NULL; when non-NULL the stream is
  * synchronised, *n_out = K and STTM_ERR_CAPACITY is returned if K > capacity. Uses the shape bound by stage 1;
  * cluster_ids may be any labelling in which a cluster's id is its smallest member's flat index.
  * node_map / node_level (device, both or neither): the stage-1 partition the cluster ids were built on, as
@@ -150,6 +171,23 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
                 const int32_t* node_map_dev, const uint8_t* node_level_dev, int out_dtype, int64_t capacity,
                 void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev, int64_t* offsets_dev,
                 int64_t* n_out_host);
+
+/* ---- position indices of the output rows (Sec. 3.4) ---------------------------------------------------------- */
+
+/* For the rows the preceding sttm_reduce call on the same cluster_ids produced (same order), all device, each may
+ * be NULL, rows beyond capacity are not written:
+ *   survived   int32 [capacity]: index, within its video, of the surviving (root) token: t*H*W + y0*W + x0
+ *                                ("survived" strategy: the root keeps its original position);
+ *   reassigned int32 [capacity]: index of the row within its video's output sequence ("reassigned" strategy);
+ *   merged_pos float [capacity]: mean of the member tokens' original indices (the index-level form of the
+ *                                "merged" strategy, which averages the members' rotary embeddings);
+ *   root_tyxl  int32 [capacity, 4]: (t, y0, x0, level) of the root node, for encodings built on (t, y, x);
+ *                                level is -1 when node_level is NULL.
+ * cluster_ids / node_level as given to sttm_temporal_merge; offsets as written by sttm_reduce. Asynchronous.
+ * STTM_ERR_STATE unless sttm_reduce ran last on this context with these cluster_ids. */
+int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const uint8_t* node_level_dev,
+                   const int64_t* offsets_dev, int64_t capacity, int32_t* survived_dev, int32_t* reassigned_dev,
+                   float* merged_pos_dev, int32_t* root_tyxl_dev);
 
 /* ---- inspection ---------------------------------------------------------------------------------------- */
 

@@ -28,8 +28,10 @@ EXPORTS = [
     "sttm_create", "sttm_destroy", "sttm_last_error", "sttm_nodes_per_frame", "sttm_node_index",
     "sttm_workspace_bytes", "sttm_set_workspace", "sttm_spatial_stats", "sttm_spatial_quadtree",
     "sttm_temporal_stats", "sttm_temporal_merge", "sttm_budget_threshold", "sttm_reduce", "sttm_export",
-    "sttm_profile_enable", "sttm_profile_read",
+    "sttm_profile_enable", "sttm_profile_read", "sttm_set_match_mode", "sttm_set_output_order", "sttm_positions",
 ]
+STTM_MATCH_FIRST_PASSING, STTM_MATCH_TOPLEFT_ONLY, STTM_MATCH_MOST_SIMILAR = 0, 1, 2
+STTM_ORDER_RASTER, STTM_ORDER_ZSCAN = 0, 1
 STTM_KERNEL_PYRAMID_STATS, STTM_KERNEL_TEMPORAL_DOTS, STTM_KERNEL_REDUCE_GATHER = 0, 1, 2
 
 
@@ -58,6 +60,9 @@ def _load() -> C.CDLL:
     lib.sttm_export.argtypes = [vp, i, vp, sz]
     lib.sttm_profile_enable.argtypes = [vp, i]
     lib.sttm_profile_read.argtypes = [vp, i, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.sttm_set_match_mode.argtypes = [vp, i]
+    lib.sttm_set_output_order.argtypes = [vp, i]
+    lib.sttm_positions.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, vp]
     return lib
 
 
@@ -170,6 +175,17 @@ class Sttm:
                               C.byref(n) if want_n else None)
         self._check(rc)
         return int(n.value) if want_n else None
+
+    def sttm_set_match_mode(self, mode: int):
+        self._check(_lib.sttm_set_match_mode(self._h, mode))
+
+    def sttm_set_output_order(self, order: int):
+        self._check(_lib.sttm_set_output_order(self._h, order))
+
+    def sttm_positions(self, cluster_ids, node_level, offsets, capacity, survived=None, reassigned=None,
+                       merged_pos=None, root_tyxl=None):
+        self._check(_lib.sttm_positions(self._h, _ptr(cluster_ids), _ptr(node_level), _ptr(offsets), capacity,
+                                        _ptr(survived), _ptr(reassigned), _ptr(merged_pos), _ptr(root_tyxl)))
 
     def sttm_export(self, table, dst):
         self._check(_lib.sttm_export(self._h, table, _ptr(dst), dst.numel() * dst.element_size()))

@@ -20,7 +20,7 @@ struct Layout {
   size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_s, sel_t, lvl,
       pd_part, sig, e, parent, ptr_a, ptr_b;
   size_t rank, key_a, val_a, key_b, val_b, order, orow, hist, tot, tile_roots, tile_live, seg, kdev,
-      bigpart, bigw, biglist;
+      bigpart, bigw, biglist, zpos, possum, poscnt;
   size_t total;
 };
 
@@ -93,6 +93,9 @@ Layout make_layout(const Geo& g) {
   l.bigpart = take(reduce_bigpart_floats(g) * sizeof(float));
   l.bigw = take(reduce_bigw_entries(g) * sizeof(int32_t));
   l.biglist = take(reduce_biglist_entries(g) * 4 * sizeof(int32_t));
+  l.zpos = take(N * sizeof(int32_t));
+  l.possum = take(N * sizeof(unsigned long long));
+  l.poscnt = take(N * sizeof(unsigned));
   l.total = off;
   return l;
 }
@@ -108,6 +111,9 @@ struct sttm_ctx {
   Geo g{};
   Layout lay{};
   bool have_spatial = false, have_tau_s = false, have_temporal = false, have_tau_t = false;
+  int match_mode = STTM_MATCH_FIRST_PASSING, order = STTM_ORDER_RASTER;
+  const int32_t* cluster_ids_reduced = nullptr;  // cluster ids of the last reduce call (NULL: none since the shape was bound)
+  bool reduced_zscan = false;
   const void* feats_spatial = nullptr;
   const int32_t* node_map_temporal = nullptr;  // caller's node map of the last temporal statistics pass
   std::vector<float> h_tau_s, h_tau_t;         // host staging that outlives the asynchronous uploads
@@ -161,6 +167,7 @@ int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int ro
   c->lay = l;
   c->bound = true;
   c->have_spatial = c->have_tau_s = c->have_temporal = c->have_tau_t = false;
+  c->cluster_ids_reduced = nullptr;
   if (!same) c->target_s_on_device = c->target_t_on_device = false;  // the layout moved: upload targets again
   return STTM_OK;
 }
@@ -225,7 +232,7 @@ int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, 
     launch_temporal_dots(c->g, feats, node_level, at<float>(c, c->lay.nsum), at<float>(c, c->lay.pd_part),
                          at<SelState>(c, c->lay.sel_t), c->stream);
   }
-  launch_temporal_resolve(c->g, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
+  launch_temporal_resolve(c->g, c->match_mode, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
                           at<float>(c, c->lay.sig), at<float>(c, c->lay.e), at<uint32_t>(c, c->lay.sel_key_t),
                           at<SelState>(c, c->lay.sel_t), c->stream);
   int rc = after_launch(c);
@@ -303,6 +310,23 @@ int sttm_set_workspace(sttm_ctx* ctx, void* workspace_dev, size_t bytes) {
   ctx->ws_bytes = bytes;
   ctx->bound = false;
   ctx->have_spatial = ctx->have_tau_s = ctx->have_temporal = ctx->have_tau_t = false;
+  ctx->cluster_ids_reduced = nullptr;
+  return STTM_OK;
+}
+
+int sttm_set_match_mode(sttm_ctx* ctx, int mode) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (mode != STTM_MATCH_FIRST_PASSING && mode != STTM_MATCH_TOPLEFT_ONLY && mode != STTM_MATCH_MOST_SIMILAR)
+    return fail(ctx, STTM_ERR_ARG, "unknown match mode");
+  if (mode != ctx->match_mode) ctx->have_temporal = ctx->have_tau_t = false;  // e_n depends on the rule
+  ctx->match_mode = mode;
+  return STTM_OK;
+}
+
+int sttm_set_output_order(sttm_ctx* ctx, int order) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (order != STTM_ORDER_RASTER && order != STTM_ORDER_ZSCAN) return fail(ctx, STTM_ERR_ARG, "unknown output order");
+  ctx->order = order;
   return STTM_OK;
 }
 
@@ -389,7 +413,7 @@ int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* nod
     if (!ctx->have_tau_t)
       return fail(ctx, STTM_ERR_STATE, "no temporal threshold chosen (call sttm_budget_threshold first)");
   }
-  launch_temporal_parent(ctx->g, node_map_dev, node_level_dev, at<float>(ctx, ctx->lay.sig),
+  launch_temporal_parent(ctx->g, ctx->match_mode, node_map_dev, node_level_dev, at<float>(ctx, ctx->lay.sig),
                          at<float>(ctx, ctx->lay.tau_t), at<int32_t>(ctx, ctx->lay.parent),
                          at<int32_t>(ctx, ctx->lay.ptr_a), ctx->stream);
   launch_roots(ctx->g, at<int32_t>(ctx, ctx->lay.ptr_a), at<int32_t>(ctx, ctx->lay.ptr_b), node_map_dev,
@@ -484,17 +508,22 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
   rb.bigpart = at<float>(ctx, ctx->lay.bigpart);
   rb.bigw = at<int32_t>(ctx, ctx->lay.bigw);
   rb.biglist = at<int32_t>(ctx, ctx->lay.biglist);
+  rb.zpos = at<int32_t>(ctx, ctx->lay.zpos);
+  const bool zscan = ctx->order == STTM_ORDER_ZSCAN;
+  ctx->cluster_ids_reduced = nullptr;
   launch_reduce_prepare(ctx->g, cluster_ids_dev, node_map_dev, node_level_dev, capacity, out_ids_dev, offsets_dev,
-                        rb, ctx->stream);
+                        rb, zscan, ctx->stream);
   {
     Timed t(ctx, STTM_KERNEL_REDUCE_GATHER);
     launch_reduce_gather(ctx->g, feats_dev, at<float>(ctx, ctx->lay.nsum), node_map_dev, node_level_dev, out_dtype,
-                         capacity, merged_dev, counts_dev, rb, ctx->stream);
+                         capacity, merged_dev, counts_dev, rb, zscan, ctx->stream);
   }
   launch_reduce_big(ctx->g, feats_dev, at<float>(ctx, ctx->lay.nsum), node_map_dev, node_level_dev, out_dtype,
-                    capacity, merged_dev, counts_dev, rb, ctx->stream);
+                    capacity, merged_dev, counts_dev, rb, zscan, ctx->stream);
   rc = after_launch(ctx);
   if (rc) return rc;
+  ctx->cluster_ids_reduced = cluster_ids_dev;
+  ctx->reduced_zscan = zscan;
   if (n_out_host) {
     int32_t k = 0;
     STTM_HIP(ctx, hipMemcpyAsync(&k, rb.kdev, sizeof k, hipMemcpyDeviceToHost, ctx->stream));
@@ -507,6 +536,30 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
     }
   }
   return STTM_OK;
+}
+
+int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const uint8_t* node_level_dev,
+                   const int64_t* offsets_dev, int64_t capacity, int32_t* survived_dev, int32_t* reassigned_dev,
+                   float* merged_pos_dev, int32_t* root_tyxl_dev) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!cluster_ids_dev || !offsets_dev) return fail(ctx, STTM_ERR_NULL, "cluster_ids and offsets are required");
+  if (capacity < 0) return fail(ctx, STTM_ERR_ARG, "capacity < 0");
+  if (!ctx->bound || !ctx->cluster_ids_reduced || ctx->cluster_ids_reduced != cluster_ids_dev)
+    return fail(ctx, STTM_ERR_STATE, "sttm_positions follows sttm_reduce on the same cluster_ids");
+  if (ctx->reduced_zscan != (ctx->order == STTM_ORDER_ZSCAN))
+    return fail(ctx, STTM_ERR_STATE, "the output order was changed after sttm_reduce");
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  ReduceBuffers rb;
+  std::memset(&rb, 0, sizeof rb);
+  rb.rank = at<int32_t>(ctx, ctx->lay.rank);
+  rb.order = at<int32_t>(ctx, ctx->lay.order);
+  rb.seg = at<int32_t>(ctx, ctx->lay.seg);
+  rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
+  rb.zpos = at<int32_t>(ctx, ctx->lay.zpos);
+  launch_positions(ctx->g, cluster_ids_dev, node_level_dev, offsets_dev, capacity, rb, ctx->reduced_zscan,
+                   at<unsigned long long>(ctx, ctx->lay.possum), at<unsigned>(ctx, ctx->lay.poscnt), survived_dev,
+                   reassigned_dev, merged_pos_dev, root_tyxl_dev, ctx->stream);
+  return after_launch(ctx);
 }
 
 int sttm_export(sttm_ctx* ctx, int table, void* dst_dev, size_t bytes) {

@@ -195,11 +195,12 @@ void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_l
                           float* pd_part, SelState* sel, hipStream_t s);
 // fp32 sums of the pyramid nodes at levels >= 3: [F][nsum_nodes][D]
 inline size_t nsum_nodes(const Geo& g) { return g.L >= 3 ? (size_t)(g.NN - g.lvl_base[3]) : 0; }
-void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
+// `match`: destination rule (0 = top-left-most passing, 1 = the one under the top-left cell only, 2 = most similar).
+void launch_temporal_resolve(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
                              const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
                              SelState* sel, hipStream_t s);
-void launch_temporal_parent(const Geo& g, const int32_t* node_map, const uint8_t* node_level, const float* sig,
-                            const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s);
+void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
+                            const float* sig, const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s);
 void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* node_map, int32_t* cluster_ids,
                   hipStream_t s);
 void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_level, hipStream_t s);
@@ -218,6 +219,7 @@ struct ReduceBuffers {
   int32_t* tile_live;   // [tiles]
   int32_t* seg;         // [N+1] first list position of every output row
   int32_t* kdev;        // [4] number of clusters, length of the live list, length of the big-cluster list
+  int32_t* zpos;        // [N] output row of every cluster rank under the Z-shaped scan
   int32_t* biglist;     // [big clusters][4] output row, first list position, end of the list, unused
   float* bigpart;       // [gather items][2][D] partial sums of clusters with more than 64 list slots
   int32_t* bigw;        // [gather items][2] member cells behind those partial sums
@@ -225,13 +227,18 @@ struct ReduceBuffers {
 // node_map / node_level: the stage-1 partition, or both NULL (every cell is its own list element).
 void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map,
                            const uint8_t* node_level, int64_t capacity, int32_t* out_ids, int64_t* offsets,
-                           const ReduceBuffers& rb, hipStream_t s);
+                           const ReduceBuffers& rb, bool zscan, hipStream_t s);
 void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                           const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
-                          const ReduceBuffers& rb, hipStream_t s);
+                          const ReduceBuffers& rb, bool zscan, hipStream_t s);
 void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                        const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
-                       const ReduceBuffers& rb, hipStream_t s);
+                       const ReduceBuffers& rb, bool zscan, hipStream_t s);
+// Position indices of the rows of the reduce call that has just run (its list, ranks and row map are still in `rb`).
+void launch_positions(const Geo& g, const int32_t* cluster_ids, const uint8_t* node_level, const int64_t* offsets,
+                      int64_t capacity, const ReduceBuffers& rb, bool zscan, unsigned long long* possum,
+                      unsigned* poscnt, int32_t* survived, int32_t* reassigned, float* merged_pos,
+                      int32_t* root_tyxl, hipStream_t s);
 size_t reduce_bigpart_floats(const Geo& g);
 size_t reduce_bigw_entries(const Geo& g);
 size_t reduce_biglist_entries(const Geo& g);

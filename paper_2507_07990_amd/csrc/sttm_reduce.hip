@@ -522,6 +522,7 @@ struct GatherArgs {
   int32_t* bigw;      // [items][2] member cells behind them
   int4* biglist;      // one entry per big cluster: output row, first list position, end of its list
   int32_t* bigcount;  // length of that list
+  const int32_t* zpos;  // output row of every cluster rank when the rows follow the Z-shaped scan, else NULL
 };
 
 template <int VEC>
@@ -543,9 +544,10 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
   int row_v = -1, beg_v = 0, end_v = 0;
   if (lane < kItem && p0 + lane < p1) {
     sv = describe<DT>(g, a.node_map, a.lvl, a.order[p0 + lane]);
-    row_v = a.orow[p0 + lane];
-    beg_v = a.seg[row_v];
-    end_v = a.seg[row_v + 1];
+    const int rank = a.orow[p0 + lane];  // clusters are listed in ascending id; the output row may differ
+    beg_v = a.seg[rank];
+    end_v = a.seg[rank + 1];
+    row_v = a.zpos ? a.zpos[rank] : rank;
   }
   for (int chunk = wave; chunk < g.nC; chunk += nw) {
     const int ch0 = chunk * g.cch + lane * VEC;
@@ -684,10 +686,128 @@ size_t reduce_bigpart_floats(const Geo& g) { return reduce_items(g) * 2 * g.D; }
 size_t reduce_bigw_entries(const Geo& g) { return reduce_items(g) * 2; }
 size_t reduce_biglist_entries(const Geo& g) { return (size_t)g.N / (kBig + 1) + 1; }  // a big cluster has > kBig slots
 
+// ------------------------------------------------------------------------------------------------
+// Z-shaped scan (Sec. 3.4): inside a frame the rows follow the Morton rank of the root's top-left cell
+// instead of its raster index. The clusters stay listed by ascending id (rank); this kernel, one workgroup per
+// frame, gives every rank of the frame its output row: the frame's rows are the same range either way, only
+// permuted. Needs the global ranks (after the first sort pass). Also writes out_ids in the new order.
+// ------------------------------------------------------------------------------------------------
+__device__ inline int morton_rank(int y, int x) {
+  int z = 0;
+#pragma unroll
+  for (int b = 0; b < kMaxLevels; ++b) z |= (((x >> b) & 1) << (2 * b)) | (((y >> b) & 1) << (2 * b + 1));
+  return z;
+}
+
+__global__ __launch_bounds__(256) void k_zorder(Geo g, const int32_t* __restrict__ cluster_ids,
+                                                const int32_t* __restrict__ rank, int64_t capacity,
+                                                int32_t* __restrict__ zpos, int32_t* __restrict__ out_ids) {
+  __shared__ int flag[1024];  // root cells of the frame at their Morton slot, then their exclusive count
+  const int f = blockIdx.x, tid = threadIdx.x, PP = g.P * g.P;
+  for (int z = tid; z < 1024; z += 256) flag[z] = 0;
+  __syncthreads();
+  for (int c = tid; c < g.HW; c += 256) {
+    const int i = f * g.HW + c;
+    if (cluster_ids[i] == i) flag[morton_rank(c / g.W, c % g.W)] = 1;
+  }
+  __syncthreads();
+  // exclusive scan over the (up to 1024) Morton slots: four consecutive slots per thread
+  int v[4], sum = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    v[j] = tid * 4 + j < PP ? flag[tid * 4 + j] : 0;
+    sum += v[j];
+  }
+  int total;
+  int ex = block_exclusive_scan(sum, &total);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (tid * 4 + j < PP) flag[tid * 4 + j] = ex;
+    ex += v[j];
+  }
+  __syncthreads();
+  const int r0 = rank[f * g.HW];  // roots before this frame
+  for (int c = tid; c < g.HW; c += 256) {
+    const int i = f * g.HW + c;
+    if (cluster_ids[i] != i) continue;
+    const int row = r0 + flag[morton_rank(c / g.W, c % g.W)];
+    zpos[rank[i]] = row;
+    if (out_ids && row < capacity) out_ids[row] = i;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Position indices of the output rows (Sec. 3.4). k_positions_cells adds every cell's original index (within
+// its video) to its row's integer sum; k_positions_rows turns the sums into means and writes the root's
+// own index, the row's index in its video's output, and the root's (t, y0, x0, level).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_positions_clear(int n, unsigned long long* __restrict__ possum,
+                                                         unsigned* __restrict__ poscnt) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    possum[i] = 0ull;
+    poscnt[i] = 0u;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_positions_cells(Geo g, const int32_t* __restrict__ cluster_ids,
+                                                         const int32_t* __restrict__ rank,
+                                                         unsigned long long* __restrict__ possum,
+                                                         unsigned* __restrict__ poscnt) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= g.N) return;
+  const int r = rank[cluster_ids[i]];
+  atomicAdd(&possum[r], (unsigned long long)(i % (g.T * g.HW)));
+  atomicAdd(&poscnt[r], 1u);
+}
+
+__global__ __launch_bounds__(256) void k_positions_rows(Geo g, const int32_t* __restrict__ kdev,
+                                                        const int32_t* __restrict__ order,
+                                                        const int32_t* __restrict__ seg,
+                                                        const int32_t* __restrict__ zpos,
+                                                        const uint8_t* __restrict__ node_level,
+                                                        const int64_t* __restrict__ offsets,
+                                                        const unsigned long long* __restrict__ possum,
+                                                        const unsigned* __restrict__ poscnt, int64_t capacity,
+                                                        int32_t* __restrict__ survived,
+                                                        int32_t* __restrict__ reassigned,
+                                                        float* __restrict__ merged_pos,
+                                                        int32_t* __restrict__ root_tyxl) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;  // cluster rank (ascending id)
+  if (r >= kdev[0]) return;
+  const int root = order[seg[r]];  // the root is the first element of its cluster's list
+  const int row = zpos ? zpos[r] : r;
+  if (row >= capacity) return;
+  const int per_video = g.T * g.HW, b = root / per_video, loc = root - b * per_video;
+  if (survived) survived[row] = loc;
+  if (reassigned) reassigned[row] = row - (int)offsets[b];
+  if (merged_pos) merged_pos[row] = (float)((double)possum[r] / (double)poscnt[r]);
+  if (root_tyxl) {
+    const int t = loc / g.HW, c = loc - t * g.HW;
+    root_tyxl[4 * row + 0] = t;
+    root_tyxl[4 * row + 1] = c / g.W;
+    root_tyxl[4 * row + 2] = c % g.W;
+    root_tyxl[4 * row + 3] = node_level ? (int)node_level[root] : -1;
+  }
+}
+
+void launch_positions(const Geo& g, const int32_t* cluster_ids, const uint8_t* node_level, const int64_t* offsets,
+                      int64_t capacity, const ReduceBuffers& rb, bool zscan, unsigned long long* possum,
+                      unsigned* poscnt, int32_t* survived, int32_t* reassigned, float* merged_pos,
+                      int32_t* root_tyxl, hipStream_t s) {
+  const dim3 grid((g.N + 255) / 256), block(256);
+  if (merged_pos) {
+    hipLaunchKernelGGL(k_positions_clear, grid, block, 0, s, g.N, possum, poscnt);
+    hipLaunchKernelGGL(k_positions_cells, grid, block, 0, s, g, cluster_ids, rb.rank, possum, poscnt);
+  }
+  hipLaunchKernelGGL(k_positions_rows, grid, block, 0, s, g, rb.kdev, rb.order, rb.seg, zscan ? rb.zpos : nullptr,
+                     node_level, offsets, possum, poscnt, capacity, survived, reassigned, merged_pos, root_tyxl);
+}
+
 // Integer plumbing of the reduce stage: sorted element list, row of every list position, row starts.
 void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map,
                            const uint8_t* node_level, int64_t capacity, int32_t* out_ids, int64_t* offsets,
-                           const ReduceBuffers& rb, hipStream_t s) {
+                           const ReduceBuffers& rb, bool zscan, hipStream_t s) {
   const int N = g.N;
   const SortPlan pl = sort_plan(N);
   const int DIG = 1 << pl.dbits;
@@ -709,7 +829,7 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32
     a.keys = kin; a.vals = vin; a.keys_out = kout; a.vals_out = last ? rb.order : vout;
     a.hist = rb.hist; a.tot = rb.tot;
     a.cluster_ids = cluster_ids; a.rank = rb.rank; a.tile_roots = rb.tile_roots; a.tile_live = rb.tile_live;
-    a.kdev = rb.kdev; a.out_ids = out_ids; a.offsets = offsets; a.capacity = capacity;
+    a.kdev = rb.kdev; a.out_ids = zscan ? nullptr : out_ids; a.offsets = offsets; a.capacity = capacity;
     a.per_video = g.T * g.HW; a.B = g.B;
     a.orow = rb.orow; a.seg = rb.seg;
     if (first && last) hipLaunchKernelGGL((k_sort_pass<true, true>), grid, block, 0, s, a);
@@ -720,27 +840,30 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32
     vin = vout;
     if (kout == rb.key_b) { kout = rb.key_a; vout = rb.val_a; } else { kout = rb.key_b; vout = rb.val_b; }
   }
+  if (zscan)
+    hipLaunchKernelGGL(k_zorder, dim3(g.F), dim3(256), 0, s, g, cluster_ids, rb.rank, capacity, rb.zpos, out_ids);
 }
 
 static GatherArgs gather_args(const void* feats, const float* nsum, const int32_t* node_map,
                               const uint8_t* node_level, int64_t capacity, void* merged, int32_t* counts,
-                              const ReduceBuffers& rb) {
+                              const ReduceBuffers& rb, bool zscan) {
   GatherArgs a;
   a.feats = feats; a.nsum = nsum; a.node_map = node_map; a.lvl = node_level; a.order = rb.order; a.orow = rb.orow;
   a.seg = rb.seg; a.kdev = rb.kdev; a.capacity = capacity; a.merged = merged; a.counts = counts;
   a.bigpart = rb.bigpart; a.bigw = rb.bigw;
   a.biglist = reinterpret_cast<int4*>(rb.biglist); a.bigcount = rb.kdev + 2;
+  a.zpos = zscan ? rb.zpos : nullptr;
   return a;
 }
 
 // The feature pass of the reduce stage: the gather over the whole list (clusters of up to kBig slots) ...
 void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                           const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
-                          const ReduceBuffers& rb, hipStream_t s) {
+                          const ReduceBuffers& rb, bool zscan, hipStream_t s) {
   const int nitems = (g.N + kItem - 1) / kItem;
   const int nw = g.nC < 16 ? g.nC : 16;
   dim3 grid(nitems), block(64 * nw);
-  const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb);
+  const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb, zscan);
   if (g.dtype == 1) {
     if (out_dtype == 1) hipLaunchKernelGGL((k_reduce<1, 1>), grid, block, 0, s, g, a);
     else hipLaunchKernelGGL((k_reduce<1, 0>), grid, block, 0, s, g, a);
@@ -753,11 +876,11 @@ void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, co
 // ... and the means of the clusters with more than kBig slots from the partial sums the gather left behind.
 void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                        const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
-                       const ReduceBuffers& rb, hipStream_t s) {
+                       const ReduceBuffers& rb, bool zscan, hipStream_t s) {
   const int nmax = (int)reduce_biglist_entries(g);
   const int nw = g.nC < 16 ? g.nC : 16;
   dim3 grid(nmax < kBigGrid ? nmax : kBigGrid), block(64 * nw);
-  const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb);
+  const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb, zscan);
   if (g.dtype == 1) {
     if (out_dtype == 1) hipLaunchKernelGGL((k_reduce_big_combine<1, 1>), grid, block, 0, s, g, a);
     else hipLaunchKernelGGL((k_reduce_big_combine<1, 0>), grid, block, 0, s, g, a);

@@ -376,8 +376,10 @@ __device__ inline void load_pair_frame(const Geo& g, int f, const int32_t* node_
 // the per-chunk partial dots in chunk order, divides by the norms from the spatial stage and stores the
 // similarity; e_n = max over n's destinations is collected with an integer max in LDS (order-free).
 // Also writes the order-preserving integer image of e_n for the budget search (0 = not a candidate).
+// match = 1 (only the destination under n's top-left cell counts): that pair always lives at n's own top-left
+// cell -- n is the finer node, or the destination there is and shares the corner -- so e_n is that one entry.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* __restrict__ node_map,
+__global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, int match, const int32_t* __restrict__ node_map,
                                                           const uint8_t* __restrict__ node_level,
                                                           const float* __restrict__ pd_part,
                                                           const float* __restrict__ nrm2,
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* 
     }
     const float v = cosine_from(dot, nn, nd);
     sig[(size_t)f * HW + c] = v;
-    if (v == v) atomicMax(&ekey[n], float_key(v));
+    if (v == v && (match != 1 || c == n)) atomicMax(&ekey[n], float_key(v));
   }
   __syncthreads();
   for (int c0 = 0; c0 < HW; c0 += blockDim.x) {  // uniform trip count: the histogram update is wave-wide
@@ -435,25 +437,28 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, const int32_t* 
   sel_flush_level0(sel + f / g.T, h0);
 }
 
-void launch_temporal_resolve(const Geo& g, const int32_t* node_map, const uint8_t* node_level,
+void launch_temporal_resolve(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
                              const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
                              SelState* sel, hipStream_t s) {
-  hipLaunchKernelGGL(k_temporal_resolve, dim3(g.F), dim3(256), 0, s, g, node_map, node_level, pd_part, nrm2, sig,
+  hipLaunchKernelGGL(k_temporal_resolve, dim3(g.F), dim3(256), 0, s, g, match, node_map, node_level, pd_part, nrm2, sig,
                      e, sel_key, sel);
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_temporal_parent: directed edge of every kept node (Sec. 3.3): among the destinations whose similarity
-// exceeds tau_T the one towards the top-left (smallest raster index; integer min in LDS). Also seeds the
+// k_temporal_parent: directed edge of every kept node (Sec. 3.3). Among the destinations whose similarity
+// exceeds tau_T: the one towards the top-left (smallest raster index; integer min in LDS) -- or, by `match`,
+// only the one under the node's top-left cell, or the most similar one (64-bit integer max in LDS over
+// (similarity image, reversed raster index), so ties go towards the top-left). Also seeds the
 // pointer-jumping array.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_temporal_parent(Geo g, const int32_t* __restrict__ node_map,
+__global__ __launch_bounds__(256) void k_temporal_parent(Geo g, int match, const int32_t* __restrict__ node_map,
                                                          const uint8_t* __restrict__ node_level,
                                                          const float* __restrict__ sig,
                                                          const float* __restrict__ tau,
                                                          int32_t* __restrict__ parent, int32_t* __restrict__ ptr) {
   __shared__ PairFrame pf;
   __shared__ int par[1024];
+  __shared__ unsigned long long best[1024];
   const int f = blockIdx.x, HW = g.HW;
   if (f % g.T == 0) {
     for (int c = threadIdx.x; c < HW; c += blockDim.x) {
@@ -463,28 +468,42 @@ __global__ __launch_bounds__(256) void k_temporal_parent(Geo g, const int32_t* _
     return;
   }
   load_pair_frame(g, f, node_map, node_level, pf);
-  for (int c = threadIdx.x; c < HW; c += blockDim.x) par[c] = 0x7fffffff;
+  for (int c = threadIdx.x; c < HW; c += blockDim.x) {
+    par[c] = 0x7fffffff;
+    best[c] = 0ull;
+  }
   __syncthreads();
   const float th = tau[f / g.T];
   for (int c = threadIdx.x; c < HW; c += blockDim.x) {
     const int a = pf.lvl_t[c], b = pf.lvl_p[c];
     const int n = pf.rep_t[c], d = pf.rep_p[c];
     if ((a <= b ? n : d) != c) continue;
-    if (sig[(size_t)f * HW + c] > th) atomicMin(&par[n], d);
+    const float v = sig[(size_t)f * HW + c];
+    if (!(v > th)) continue;
+    if (match == 2)
+      atomicMax(&best[n], ((unsigned long long)float_key(v) << 32) | (unsigned)(0x7fffffff - d));
+    else if (match == 0 || c == n)
+      atomicMin(&par[n], d);
   }
   __syncthreads();
   for (int c = threadIdx.x; c < HW; c += blockDim.x) {
     const int i = f * HW + c;
     int p = -1;
-    if (pf.rep_t[c] == c && par[c] != 0x7fffffff) p = (f - 1) * HW + par[c];
+    if (pf.rep_t[c] == c) {
+      if (match == 2) {
+        if (best[c] != 0ull) p = (f - 1) * HW + (0x7fffffff - (int)(best[c] & 0xffffffffull));
+      } else if (par[c] != 0x7fffffff) {
+        p = (f - 1) * HW + par[c];
+      }
+    }
     parent[i] = p;
     ptr[i] = p >= 0 ? p : i;
   }
 }
 
-void launch_temporal_parent(const Geo& g, const int32_t* node_map, const uint8_t* node_level, const float* sig,
-                            const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s) {
-  hipLaunchKernelGGL(k_temporal_parent, dim3(g.F), dim3(256), 0, s, g, node_map, node_level, sig, tau, parent,
+void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
+                            const float* sig, const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s) {
+  hipLaunchKernelGGL(k_temporal_parent, dim3(g.F), dim3(256), 0, s, g, match, node_map, node_level, sig, tau, parent,
                      ptr);
 }
 

@@ -195,6 +195,22 @@ def generate(cfg: Workload, *, return_leaf_maps: bool = False):
     return feats
 
 
+def generate_alternating(cfg: Workload, sigma_fine: float) -> np.ndarray:
+    """The features of ``cfg`` with the noise of every odd frame raised to ``sigma_fine``.
+
+    With a spatial threshold between the two noise levels the even frames merge into coarse nodes and the odd
+    frames stay fine, so consecutive frames meet at different granularities in both directions (a coarse node
+    over several fine destinations and the reverse) and the similarities of one coarse node to its fine
+    destinations spread out: the inputs on which the destination-choice rules of the temporal stage differ."""
+    base = generate(dataclasses.replace(cfg, sigma=0.0, sigma_hi=None, dtype="f32"))
+    rng = np.random.Generator(np.random.Philox(cfg.seed + 7919))
+    out = np.empty_like(base)
+    for t in range(cfg.T):
+        s = np.float32(sigma_fine if t % 2 else cfg.sigma)
+        out[:, t] = base[:, t] + s * rng.standard_normal(base[:, t].shape, dtype=np.float32)
+    return out if cfg.dtype == "f32" else f32_to_bf16_bits(out)
+
+
 def small_variant(cfg: Workload, **over) -> Workload:
     """Same recipe at other sizes (used by parity tests for tiles and ragged tails)."""
     return dataclasses.replace(cfg, **over)

@@ -37,7 +37,8 @@ def load():
     return lib
 
 
-def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, lib=None, use_nodes=True):
+def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, lib=None, use_nodes=True,
+            match=0, order=0, positions=False):
     lib = lib or load()
     B, T, H, W, D = feats.shape
     dt = STTM_BF16 if feats.dtype == np.uint16 else STTM_F32
@@ -49,6 +50,8 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     def chk(rc):
         assert rc == 0, (rc, lib.sttm_last_error(h))
 
+    chk(lib.sttm_set_match_mode(h, match))
+    chk(lib.sttm_set_output_order(h, order))
     need = lib.sttm_workspace_bytes(B, T, H, W, D, dt, root_grid)
     ws = _aligned(need, garbage=True)
     chk(lib.sttm_set_workspace(h, _p(ws), C.c_size_t(need)))
@@ -115,5 +118,12 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     r.counts = counts[:K].copy()
     r.out_ids = out_ids[:K].copy()
     r.offsets = offsets.copy()
+    if positions:
+        sv, ra = np.zeros(N, np.int32), np.zeros(N, np.int32)
+        mp, rt = np.zeros(N, np.float32), np.zeros(4 * N, np.int32)
+        chk(lib.sttm_positions(h, _p(cluster), _p(node_level), _p(offsets), C.c_int64(N), _p(sv), _p(ra), _p(mp),
+                               _p(rt)))
+        r.survived, r.reassigned, r.merged_pos = sv[:K].copy(), ra[:K].copy(), mp[:K].copy()
+        r.root_tyxl = rt[:4 * K].reshape(K, 4).copy()
     lib.sttm_destroy(h)
     return r

@@ -44,9 +44,14 @@ def _to_dev(feats: np.ndarray):
     return torch.from_numpy(feats).cuda()
 
 
+MODES = {"first_passing": 0, "topleft_only": 1, "most_similar": 2}
+ORDERS = {"raster": 0, "zscan": 1}
+
+
 def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_grid: int = 1,
             out_dtype: Optional[int] = None, node_map_override=None, ctx=None, feats_dev=None,
-            use_nodes: bool = True) -> GpuResult:
+            use_nodes: bool = True, mode: str = "first_passing", order: str = "raster",
+            positions: bool = False) -> GpuResult:
     """Whole path through the C ABI. Fixed thresholds, or `keep` (budget mode)."""
     import torch
     B, T, H, W, D = feats.shape
@@ -55,6 +60,8 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
         out_dtype = dt
     x = _to_dev(feats) if feats_dev is None else feats_dev
     s = ctx or lib.Sttm(0)
+    s.sttm_set_match_mode(MODES[mode])
+    s.sttm_set_output_order(ORDERS[order])
     s.ensure_workspace(B, T, H, W, D, dt, root_grid)
     N = B * T * H * W
     NN = lib.sttm_nodes_per_frame(H, W, root_grid)
@@ -114,6 +121,15 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     r.counts = counts[:K].cpu().numpy()
     r.out_ids = out_ids[:K].cpu().numpy()
     r.offsets = offsets.cpu().numpy()
+    if positions:
+        sv = torch.zeros(N, dtype=torch.int32, device=dev)
+        ra = torch.zeros(N, dtype=torch.int32, device=dev)
+        mp = torch.zeros(N, dtype=torch.float32, device=dev)
+        rt = torch.zeros(N, 4, dtype=torch.int32, device=dev)
+        s.sttm_positions(cluster, node_level, offsets, N, sv, ra, mp, rt)
+        _trace("positions")
+        r.survived, r.reassigned = sv[:K].cpu().numpy(), ra[:K].cpu().numpy()
+        r.merged_pos, r.root_tyxl = mp[:K].cpu().numpy(), rt[:K].cpu().numpy()
     r.ctx = s
     r.feats_dev = x
     return r
@@ -154,7 +170,7 @@ def check_spatial(lib, feats, r: GpuResult, tau_s, root_grid=1, stats=None):
     return sp, worst
 
 
-def check_temporal(lib, feats, r: GpuResult, sp, tau_t, cands=None):
+def check_temporal(lib, feats, r: GpuResult, sp, tau_t, cands=None, mode: str = "first_passing"):
     B, T, H, W, D = feats.shape
     if cands is None:
         cands, _ = O.temporal_candidates(feats, sp.node_map, sp.node_level)
@@ -167,27 +183,54 @@ def check_temporal(lib, feats, r: GpuResult, sp, tau_t, cands=None):
             # slot = top-left cell of the finer node, in frame f's table
             q = n if lvl_flat[n] <= lvl_flat[d] else d + HW
             worst = max(worst, abs(float(r.pair_sim[q]) - sig))
-        worst = max(worst, abs(float(r.best_sim[n]) - max(s for _, s in lst)))
+    best = O.best_similarity(cands, sp.node_map, mode)
+    for n in cands:
+        worst = max(worst, abs(float(r.best_sim[n]) - best[n]))
     assert worst <= SIM_TOL, f"temporal similarity error {worst}"
     gpar = r.parent.reshape(-1)
+    tau_b = np.broadcast_to(np.asarray(tau_t, dtype=np.float64), (B,))
 
     def decide(n, d, sig):
+        # inside the band the oracle goes with what the GPU did, as far as its edge tells
         p = int(gpar[n])
         if d == p:
             return True
-        if p < 0 or d < p:
+        if mode == "first_passing":
+            if p < 0 or d < p:
+                return False
+            return None
+        if mode == "topleft_only":
+            return False if p < 0 else None
+        if p < 0:
             return False
+        # most similar: a band candidate the GPU did not take may or may not have passed there; it lost either
+        # way unless it beats the GPU's choice by more than the band, which the oracle's own ranking settles
         return None
 
-    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, tau_t, cands=cands, decide=decide)
+    def choose(n, near_best):
+        p = int(gpar[n])
+        return p if any(d == p for d, _ in near_best) else None
+
+    tm = O.temporal_merge(feats, sp.node_map, sp.node_level, tau_t, cands=cands, decide=decide, mode=mode,
+                          choose=choose)
     nodes = np.unique(sp.node_map)
     assert (tm.parent.reshape(-1)[nodes] == gpar[nodes]).all(), "parent differs outside the threshold band"
     assert (tm.cluster_ids == r.cluster_ids).all(), "cluster_ids differ"
     return tm, worst
 
 
-def check_reduce(feats, r: GpuResult, tm, out_is_bf16: bool):
-    rd = O.reduce_clusters(feats, tm.cluster_ids)
+def check_positions(r: GpuResult, sp, tm, order: str = "raster"):
+    pr = O.positions(tm.cluster_ids, sp.node_level, order)
+    assert (r.survived == pr.survived).all() and (r.reassigned == pr.reassigned).all()
+    assert (r.root_tyxl == pr.root).all()
+    err = float(np.abs(r.merged_pos.astype(np.float64) - pr.merged).max()) if r.K else 0.0
+    # fp32 output of an exact integer mean: half an ulp of the largest index
+    assert err <= max(1.0, float(pr.merged.max())) * 2.0 ** -23, f"merged position error {err}"
+    return err
+
+
+def check_reduce(feats, r: GpuResult, tm, out_is_bf16: bool, order: str = "raster"):
+    rd = O.reduce_clusters(feats, tm.cluster_ids, order)
     assert r.K == len(rd.counts)
     assert (r.counts == rd.counts).all() and (r.out_ids == rd.out_ids).all()
     assert (r.offsets == rd.offsets).all()
@@ -199,7 +242,7 @@ def check_reduce(feats, r: GpuResult, tm, out_is_bf16: bool):
 
 
 def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None, root_grid=1,
-                 out_is_bf16=None):
+                 out_is_bf16=None, mode: str = "first_passing", order: str = "raster"):
     """Full comparison; returns a dict with the error figures and near-threshold counts."""
     B, T, H, W, D = feats.shape
     if out_is_bf16 is None:
@@ -224,7 +267,7 @@ def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None,
     if tau_t is None:
         tt = r.tau_t.astype(np.float64)
         N1 = T * H * W
-        for b, (vals, wts, base) in enumerate(O.temporal_budget_inputs(cands, sp.node_map)):
+        for b, (vals, wts, base) in enumerate(O.temporal_budget_inputs(cands, sp.node_map, mode)):
             keep_b = float(np.broadcast_to(np.asarray(keep, dtype=np.float64), (B,))[b])
             target = int(math.floor(keep_b * N1))
             tau, lo, hi, K = O.budget_threshold(vals, wts, base, target)
@@ -232,8 +275,10 @@ def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None,
                 f"tau_t {tt[b]} outside the oracle's interval [{lo}, {hi})"
             assert len(np.unique(r.cluster_ids[b])) <= target or base > target
         info["tau_t"] = tt
-    tm, e2 = check_temporal(lib, feats, r, sp, tt, cands)
-    rd, e3 = check_reduce(feats, r, tm, out_is_bf16)
+    tm, e2 = check_temporal(lib, feats, r, sp, tt, cands, mode)
+    rd, e3 = check_reduce(feats, r, tm, out_is_bf16, order)
+    if hasattr(r, "survived"):
+        info["merged_pos_err"] = check_positions(r, sp, tm, order)
     info.update(spatial_sim_err=e1, temporal_sim_err=e2, merged_err=e3, near_spatial=sp.near,
                 near_temporal=tm.near, K=r.K, N=B * T * H * W, n_spatial=len(np.unique(sp.node_map)))
     return info

@@ -48,3 +48,15 @@ def test_emulated_kernels_match_the_oracle(emul, seed, B, T, H, W, D, dtype, kw)
     r = run_cpu.run_cpu(feats, **kw)
     info = P.check_parity(fake, feats, r, **kw)
     assert info["K"] == r.K and int(r.counts.sum()) == feats[..., 0].size
+
+
+@pytest.mark.parametrize("mode,order", [("topleft_only", "zscan"), ("most_similar", "raster"), ("first_passing", "zscan")])
+def test_emulated_destination_rules_orders_and_positions(emul, mode, order):
+    """Alternating coarse / fine frames (the rules differ there), rows in either scan, position indices."""
+    run_cpu, fake = emul
+    cfg = wl.Workload("v", 95, 1, 5, 8, 8, 16, "f32", 2, 0.05, 0.9)
+    feats = wl.generate_alternating(cfg, 0.7)
+    kw = dict(tau_s=0.9, tau_t=0.8)
+    r = run_cpu.run_cpu(feats, match=P.MODES[mode], order=P.ORDERS[order], positions=True, **kw)
+    info = P.check_parity(fake, feats, r, mode=mode, order=order, **kw)
+    assert "merged_pos_err" in info

@@ -232,6 +232,71 @@ def test_error_paths(lib):
     np.testing.assert_array_equal(merged.cpu().numpy(), x.view(128, 16)[:4].cpu().numpy())
 
 
+# ---- destination rules (Sec. 3.3 and its ablation), row order and position indices (Sec. 3.4) ------------
+@pytest.mark.parametrize("mode", ["first_passing", "topleft_only", "most_similar"])
+@pytest.mark.parametrize("order", ["raster", "zscan"])
+@pytest.mark.parametrize("seed,T,H,W,D,dtype", [
+    (95, 5, 8, 8, 16, "f32"),          # the rules pick different destinations here (oracle pins say so)
+    (97, 6, 13, 13, 520, "bf16"),      # padded grid, two chunks
+])
+def test_destination_rules_orders_and_positions(lib, mode, order, seed, T, H, W, D, dtype):
+    cfg = wl.Workload("alt", seed, 1, T, H, W, D, dtype, 2, 0.05, 0.9)
+    feats = wl.generate_alternating(cfg, 0.7)
+    kw = dict(tau_s=0.9, tau_t=0.8)
+    print(f"case alternating seed={seed} shape={feats.shape} mode={mode} order={order}", flush=True)
+    r = P.run_gpu(lib, feats, mode=mode, order=order, positions=True, **kw)
+    info = P.check_parity(lib, feats, r, mode=mode, order=order, **kw)
+    print("  ", {k: v for k, v in info.items() if k in ("K", "near_temporal", "merged_err", "merged_pos_err")}, flush=True)
+    if seed == 95:   # the case is not vacuous: the three rules give three different sets of edges
+        base = P.run_gpu(lib, feats, mode="first_passing", **kw)
+        assert mode == "first_passing" or (base.parent != r.parent).any()
+
+
+def test_budget_mode_under_the_single_destination_rule(lib):
+    """With only the top-left destination tested, e_n and hence the temporal budget threshold change."""
+    cfg = wl.Workload("alt", 97, 2, 6, 13, 13, 264, "bf16", 2, 0.05, 0.9)
+    feats = wl.generate_alternating(cfg, 0.7)
+    print(f"case alternating budget shape={feats.shape}", flush=True)
+    r = P.run_gpu(lib, feats, keep=0.4, mode="topleft_only", order="zscan", positions=True)
+    info = P.check_parity(lib, feats, r, keep=0.4, mode="topleft_only", order="zscan")
+    assert info["K"] <= int(0.4 * 6 * 169) * 2
+
+
+def test_positions_and_settings_error_paths(lib):
+    import torch
+    s = lib.Sttm(0)
+    with pytest.raises(lib.SttmError) as e:
+        s.sttm_set_match_mode(3)
+    assert e.value.code == lib.STTM_ERR_ARG
+    with pytest.raises(lib.SttmError) as e:
+        s.sttm_set_output_order(-1)
+    assert e.value.code == lib.STTM_ERR_ARG
+    cfg = wl.CONFIGS[0]
+    feats = wl.generate(cfg)
+    r = P.run_gpu(lib, feats, tau_s=cfg.tau_s, tau_t=cfg.tau_t, ctx=s)
+    N = cfg.n_tokens
+    cl = torch.from_numpy(r.cluster_ids.reshape(-1)).cuda()       # same ids, another buffer
+    off = torch.from_numpy(r.offsets).cuda()
+    sv = torch.zeros(N, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(lib.SttmError) as e:                        # not the buffer the reduce call saw
+        s.sttm_positions(cl, None, off, N, sv)
+    assert e.value.code == lib.STTM_ERR_STATE
+    with pytest.raises(lib.SttmError) as e:
+        s.sttm_positions(None, None, off, N, sv)
+    assert e.value.code == lib.STTM_ERR_NULL
+
+
+def test_config3_long_video_most_similar_zscan_positions(lib):
+    """The bench workload once more under the alternative rule and scan, with position indices."""
+    cfg = wl.CONFIGS[3]
+    feats = wl.generate(cfg)
+    print(f"case {cfg.name} shape={feats.shape} most_similar zscan", flush=True)
+    r = P.run_gpu(lib, feats, keep=0.5, mode="most_similar", order="zscan", positions=True)
+    info = P.check_parity(lib, feats, r, keep=0.5, mode="most_similar", order="zscan")
+    print("  ", {k: (float(v) if isinstance(v, (float, np.floating)) else v) for k, v in info.items()
+                 if k not in ("tau_s", "tau_t")}, flush=True)
+
+
 # ---- the five configurations at full size, in the launch configuration bench.py times ------------------
 def test_config1_short_clip_budget(lib):
     cfg = wl.CONFIGS[1]
