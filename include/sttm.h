@@ -54,7 +54,7 @@ typedef enum {
   STTM_ERR_HIP = 8        /* a HIP runtime call failed; message holds hipGetErrorString */
 } sttm_status;
 
-typedef enum { STTM_F32 = 0, STTM_BF16 = 1 } sttm_dtype;
+typedef enum { STTM_F32 = 0, STTM_BF16 = 1, STTM_F16 = 2 } sttm_dtype;
 typedef enum { STTM_STAGE_SPATIAL = 0, STTM_STAGE_TEMPORAL = 1 } sttm_stage;
 
 /* Which destination a node of frame t takes when it overlaps several kept nodes of frame t-1 (Sec. 3.3; the
@@ -156,12 +156,14 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
 
 /* ---- stage 3: gather / average (Sec. 3.1, 3.3, 3.4) ---------------------------------------------------- */
 
-/* One output row per cluster, in ascending cluster id (see sttm_set_output_order): merged [capacity, D] of out_dtype = mean of the member
+/* One output row per cluster, in ascending cluster id (or, with STTM_ORDER_ZSCAN, the rows of a frame in the
+ * Z-shaped scan of their roots; see sttm_set_output_order): merged [capacity, D] of out_dtype = mean of the member
  * cells' features (fp32 accumulation in a fixed order); counts int32 [capacity] = members; out_ids int32 [capacity]
  * = cluster id; offsets int64 [B+1] = first row of each video, offsets[B] = K (all device, counts/out_ids may be
- * NULL). With STTM_ORDER_ZSCAN the rows of a frame follow the Z-shaped scan of their roots instead. Rows beyond capacity are not written. n_out: host pointer or NULL; when non-NULL the stream is
- * synchronised, *n_out = K and STTM_ERR_CAPACITY is returned if K > capacity. Uses the shape bound by stage 1;
- * cluster_ids may be any labelling in which a cluster's id is its smallest member's flat index.
+ * NULL). out_dtype: any sttm_dtype for fp32 input; the input's own type or fp32 for bf16 / fp16 input
+ * (STTM_ERR_DTYPE otherwise). Rows beyond capacity are not written. n_out: host pointer or NULL; when non-NULL
+ * the stream is synchronised, *n_out = K and STTM_ERR_CAPACITY is returned if K > capacity. Uses the shape bound
+ * by stage 1; cluster_ids may be any labelling in which a cluster's id is its smallest member's flat index.
  * node_map / node_level (device, both or neither): the stage-1 partition the cluster ids were built on, as
  * sttm_temporal_merge received it -- all cells of a node must carry the same cluster id, and the workspace must
  * still hold the stage-1 statistics of these (unchanged) feats (STTM_ERR_STATE otherwise). Nodes at level >= 3 are

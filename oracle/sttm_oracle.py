@@ -64,11 +64,11 @@ BAND = 1e-5  # similarities this close to a threshold may be decided either way
 # input handling
 # ----------------------------------------------------------------------------
 def widen(feats: np.ndarray) -> np.ndarray:
-    """Exact widening of the stored input bits to float64 (float32, or uint16 = bfloat16 bits)."""
+    """Exact widening of the stored input bits to float64 (float32, float16, or uint16 = bfloat16 bits)."""
     if feats.dtype == np.uint16:
         f32 = (feats.astype(np.uint32) << np.uint32(16)).view(np.float32)
         return f32.astype(np.float64)
-    if feats.dtype in (np.float32, np.float64):
+    if feats.dtype in (np.float16, np.float32, np.float64):
         return feats.astype(np.float64)
     raise TypeError(f"unsupported input dtype {feats.dtype}")
 

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsttm.so")
 STTM_OK = 0
 STTM_ERR_NULL, STTM_ERR_SHAPE, STTM_ERR_DTYPE, STTM_ERR_ARG = 1, 2, 3, 4
 STTM_ERR_WORKSPACE, STTM_ERR_STATE, STTM_ERR_CAPACITY, STTM_ERR_HIP = 5, 6, 7, 8
-STTM_F32, STTM_BF16 = 0, 1
+STTM_F32, STTM_BF16, STTM_F16 = 0, 1, 2
 STTM_STAGE_SPATIAL, STTM_STAGE_TEMPORAL = 0, 1
 STTM_TBL_CHILD_SIM, STTM_TBL_MIN_SIM, STTM_TBL_NORM2 = 0, 1, 2
 STTM_TBL_PAIR_SIM, STTM_TBL_BEST_SIM, STTM_TBL_PARENT = 3, 4, 5

@@ -26,7 +26,7 @@ struct Layout {
 
 bool make_geo(int B, int T, int H, int W, int D, int dtype, int root_grid, Geo* g) {
   if (B < 1 || T < 1 || H < 1 || W < 1 || D < 8 || H > 32 || W > 32 || (D % 8) != 0) return false;
-  if (dtype != STTM_F32 && dtype != STTM_BF16) return false;
+  if (dtype != STTM_F32 && dtype != STTM_BF16 && dtype != STTM_F16) return false;
   long long n = (long long)B * T * H * W;
   if (n >= (1ll << 31) - 1) return false;
   if ((long long)B * T > 65535) return false;  // frames index a grid dimension
@@ -44,7 +44,7 @@ bool make_geo(int B, int T, int H, int W, int D, int dtype, int root_grid, Geo* 
   }
   g->NN = base;
   g->dtype = dtype;
-  g->vec = dtype == STTM_BF16 ? 8 : 4;
+  g->vec = dtype == STTM_F32 ? 4 : 8;
   g->cch = 64 * g->vec;
   g->nC = (D + g->cch - 1) / g->cch;
   g->N = (int)n;
@@ -149,7 +149,8 @@ int hip_check(sttm_ctx* c, hipError_t e, const char* what) {
 template <class T> T* at(sttm_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
 
 int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int root_grid) {
-  if (dtype != STTM_F32 && dtype != STTM_BF16) return fail(c, STTM_ERR_DTYPE, "dtype must be STTM_F32 or STTM_BF16");
+  if (dtype != STTM_F32 && dtype != STTM_BF16 && dtype != STTM_F16)
+    return fail(c, STTM_ERR_DTYPE, "dtype must be STTM_F32, STTM_BF16 or STTM_F16");
   Geo g;
   std::memset(&g, 0, sizeof g);
   if (!make_geo(B, T, H, W, D, dtype, root_grid, &g))
@@ -481,9 +482,12 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
     return fail(ctx, STTM_ERR_NULL, "cluster_ids, merged and offsets are required");
   if ((node_map_dev == nullptr) != (node_level_dev == nullptr))
     return fail(ctx, STTM_ERR_NULL, "node_map and node_level go together (both or neither)");
-  if (out_dtype != STTM_F32 && out_dtype != STTM_BF16) return fail(ctx, STTM_ERR_DTYPE, "bad out_dtype");
+  if (out_dtype != STTM_F32 && out_dtype != STTM_BF16 && out_dtype != STTM_F16)
+    return fail(ctx, STTM_ERR_DTYPE, "bad out_dtype");
   if (capacity < 0) return fail(ctx, STTM_ERR_ARG, "capacity < 0");
   if (!ctx->bound) return fail(ctx, STTM_ERR_STATE, "no shape bound (run the spatial stage first)");
+  if (!reduce_io_supported(ctx->g.dtype, out_dtype))
+    return fail(ctx, STTM_ERR_DTYPE, "a 16-bit input is written out in its own type or in fp32");
   int rc = check_feats(ctx, feats_dev);
   if (rc) return rc;
   if (node_map_dev && (!ctx->have_spatial || ctx->feats_spatial != feats_dev))

@@ -1,6 +1,7 @@
 // Shared declarations of the HIP kernels behind libsttm (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 
 // Dynamic LDS of a kernel. (The second form serves the host-thread build used by the CPU tests.)
@@ -25,8 +26,8 @@ struct Geo {
   int F;         // frames = B*T
   int NN;        // pyramid nodes per frame (levels 0..L of the P x P grid)
   int lvl_base[kMaxLevels + 1];
-  int dtype;     // 0 = f32, 1 = bf16
-  int vec;       // channels per lane per 16-byte load: 4 (f32) / 8 (bf16)
+  int dtype;     // 0 = f32, 1 = bf16, 2 = f16
+  int vec;       // channels per lane per 16-byte load: 4 (f32) / 8 (bf16, f16)
   int cch;       // channels per chunk = 64 * vec (one wavefront spans one chunk of a token row)
   int nC;        // chunks per row = ceil(D / cch)
   int N;         // B*T*H*W
@@ -58,7 +59,7 @@ __host__ __device__ inline void node_decode(const Geo& g, int idx, int& lvl, int
 }
 
 // ---- feature row access: one lane owns `VEC` consecutive channels ------------------------------------
-template <int DT> struct Row;  // DT: 0 = f32, 1 = bf16
+template <int DT> struct Row;  // DT: 0 = f32, 1 = bf16, 2 = f16
 
 template <> struct Row<0> {
   static constexpr int VEC = 4;
@@ -82,6 +83,21 @@ template <> struct Row<1> {
     x[6] = __uint_as_float(r.w << 16); x[7] = __uint_as_float(r.w & 0xffff0000u);
   }
 };
+
+template <> struct Row<2> {
+  static constexpr int VEC = 8;
+  typedef uint4 Raw;
+  typedef uint16_t Elem;
+  __device__ static inline Raw zero() { return make_uint4(0u, 0u, 0u, 0u); }
+  __device__ static inline float lo(uint32_t w) { return __half2float(__ushort_as_half((unsigned short)(w & 0xffffu))); }
+  __device__ static inline float hi(uint32_t w) { return __half2float(__ushort_as_half((unsigned short)(w >> 16))); }
+  __device__ static inline void unpack(const Raw& r, float (&x)[8]) {
+    x[0] = lo(r.x); x[1] = hi(r.x); x[2] = lo(r.y); x[3] = hi(r.y);
+    x[4] = lo(r.z); x[5] = hi(r.z); x[6] = lo(r.w); x[7] = hi(r.w);
+  }
+};
+
+__device__ inline uint32_t f32_to_f16_rne(float f) { return (uint32_t)__half_as_ushort(__float2half_rn(f)); }
 
 __device__ inline uint32_t f32_to_bf16_rne(float f) {
   uint32_t u = __float_as_uint(f);
@@ -241,6 +257,7 @@ void launch_positions(const Geo& g, const int32_t* cluster_ids, const uint8_t* n
                       int32_t* root_tyxl, hipStream_t s);
 size_t reduce_bigpart_floats(const Geo& g);
 size_t reduce_bigw_entries(const Geo& g);
+bool reduce_io_supported(int in_dtype, int out_dtype);
 size_t reduce_biglist_entries(const Geo& g);
 size_t reduce_hist_entries(int N);
 size_t reduce_tiles(int N);

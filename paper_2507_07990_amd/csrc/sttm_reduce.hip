@@ -464,13 +464,15 @@ __device__ inline typename Row<DT>::Raw load_slot(const void* feats, const float
   return *reinterpret_cast<const typename R::Raw*>(nsum + (size_t)idx * D + ch0 + (kind - 1) * 4);
 }
 
+template <int DT>
 __device__ inline void acc_slot(const float4& r, int, float (&acc)[4]) {  // fp32 rows and node sums share a layout
   acc[0] += r.x; acc[1] += r.y; acc[2] += r.z; acc[3] += r.w;
 }
+template <int DT>
 __device__ inline void acc_slot(const uint4& r, int kind, float (&acc)[8]) {
   if (kind == 0) {
     float t[8];
-    Row<1>::unpack(r, t);
+    Row<DT>::unpack(r, t);
 #pragma unroll
     for (int v = 0; v < 8; ++v) acc[v] += t[v];
   } else {
@@ -498,7 +500,8 @@ __device__ inline void store_mean(void* merged_v, size_t elem_off, const float (
     uint32_t w[VEC / 2];
 #pragma unroll
     for (int v = 0; v < VEC; v += 2)
-      w[v / 2] = f32_to_bf16_rne(acc[v] * inv) | (f32_to_bf16_rne(acc[v + 1] * inv) << 16);
+      w[v / 2] = ODT == 1 ? (f32_to_bf16_rne(acc[v] * inv) | (f32_to_bf16_rne(acc[v + 1] * inv) << 16))
+                          : (f32_to_f16_rne(acc[v] * inv) | (f32_to_f16_rne(acc[v + 1] * inv) << 16));
     if (VEC == 8)
       *reinterpret_cast<uint4*>(o) = make_uint4(w[0], w[1], w[2 % (VEC / 2)], w[3 % (VEC / 2)]);
     else
@@ -573,7 +576,7 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
       const bool big = end - beg > kBig;
       const bool use = p0 + j < p1 && (beg >= p0 || big);
       if (use) {
-        acc_slot(raw[j], kind, acc);
+        acc_slot<DT>(raw[j], kind, acc);
         members += wgt;
         const int p = p0 + j;
         const bool closes = p + 1 == end, last = p + 1 == p1;
@@ -619,7 +622,7 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
         for (int u = 0; u < kTail; ++u) {
           const int kd = __shfl(ts.kind, u, 64), wg = __shfl(ts.weight, u, 64);
           if (q + u < open_end) {
-            acc_slot(tr[u], kd, acc);
+            acc_slot<DT>(tr[u], kd, acc);
             members += wg;
           }
         }
@@ -856,6 +859,25 @@ static GatherArgs gather_args(const void* feats, const float* nsum, const int32_
   return a;
 }
 
+// Input / output element types a gather kernel is built for: fp32 in with any output type; a 16-bit input with
+// the same type or fp32 out (reduce_io_supported() says which pairs exist).
+#define STTM_DISPATCH_IO(KERNEL, IN, OUT, GRID, BLOCK, STREAM, ...)                                      \
+  do {                                                                                                   \
+    const int io_ = (IN) * 3 + (OUT);                                                                    \
+    if (io_ == 0) hipLaunchKernelGGL((KERNEL<0, 0>), GRID, BLOCK, 0, STREAM, __VA_ARGS__);               \
+    else if (io_ == 1) hipLaunchKernelGGL((KERNEL<0, 1>), GRID, BLOCK, 0, STREAM, __VA_ARGS__);          \
+    else if (io_ == 2) hipLaunchKernelGGL((KERNEL<0, 2>), GRID, BLOCK, 0, STREAM, __VA_ARGS__);          \
+    else if (io_ == 3) hipLaunchKernelGGL((KERNEL<1, 0>), GRID, BLOCK, 0, STREAM, __VA_ARGS__);          \
+    else if (io_ == 4) hipLaunchKernelGGL((KERNEL<1, 1>), GRID, BLOCK, 0, STREAM, __VA_ARGS__);          \
+    else if (io_ == 6) hipLaunchKernelGGL((KERNEL<2, 0>), GRID, BLOCK, 0, STREAM, __VA_ARGS__);          \
+    else if (io_ == 8) hipLaunchKernelGGL((KERNEL<2, 2>), GRID, BLOCK, 0, STREAM, __VA_ARGS__);          \
+  } while (0)
+
+bool reduce_io_supported(int in_dtype, int out_dtype) {
+  if (in_dtype < 0 || in_dtype > 2 || out_dtype < 0 || out_dtype > 2) return false;
+  return in_dtype == 0 || out_dtype == 0 || out_dtype == in_dtype;
+}
+
 // The feature pass of the reduce stage: the gather over the whole list (clusters of up to kBig slots) ...
 void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, const int32_t* node_map,
                           const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
@@ -864,13 +886,7 @@ void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, co
   const int nw = g.nC < 16 ? g.nC : 16;
   dim3 grid(nitems), block(64 * nw);
   const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb, zscan);
-  if (g.dtype == 1) {
-    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce<1, 1>), grid, block, 0, s, g, a);
-    else hipLaunchKernelGGL((k_reduce<1, 0>), grid, block, 0, s, g, a);
-  } else {
-    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce<0, 1>), grid, block, 0, s, g, a);
-    else hipLaunchKernelGGL((k_reduce<0, 0>), grid, block, 0, s, g, a);
-  }
+  STTM_DISPATCH_IO(k_reduce, g.dtype, out_dtype, grid, block, s, g, a);
 }
 
 // ... and the means of the clusters with more than kBig slots from the partial sums the gather left behind.
@@ -881,13 +897,7 @@ void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const
   const int nw = g.nC < 16 ? g.nC : 16;
   dim3 grid(nmax < kBigGrid ? nmax : kBigGrid), block(64 * nw);
   const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb, zscan);
-  if (g.dtype == 1) {
-    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce_big_combine<1, 1>), grid, block, 0, s, g, a);
-    else hipLaunchKernelGGL((k_reduce_big_combine<1, 0>), grid, block, 0, s, g, a);
-  } else {
-    if (out_dtype == 1) hipLaunchKernelGGL((k_reduce_big_combine<0, 1>), grid, block, 0, s, g, a);
-    else hipLaunchKernelGGL((k_reduce_big_combine<0, 0>), grid, block, 0, s, g, a);
-  }
+  STTM_DISPATCH_IO(k_reduce_big_combine, g.dtype, out_dtype, grid, block, s, g, a);
 }
 
 }  // namespace sttm

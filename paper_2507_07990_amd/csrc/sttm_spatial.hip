@@ -275,6 +275,8 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* n
   dim3 grid(g.nC, UX * UY, g.F), block(64);
   if (g.dtype == 1)
     hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, 0, s, g, feats, part, nsum, sel);
+  else if (g.dtype == 2)
+    hipLaunchKernelGGL(k_pyramid_stats<2>, grid, block, 0, s, g, feats, part, nsum, sel);
   else
     hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, 0, s, g, feats, part, nsum, sel);
 }

@@ -345,6 +345,8 @@ void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_l
   const size_t lds = g.L >= 3 ? (size_t)U * U * g.cch * sizeof(float) : 0;
   if (g.dtype == 1)
     hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
+  else if (g.dtype == 2)
+    hipLaunchKernelGGL(k_temporal_dots<2>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
   else
     hipLaunchKernelGGL(k_temporal_dots<0>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
 }

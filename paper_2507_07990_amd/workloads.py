@@ -19,7 +19,7 @@ Recipe (per video)
   in the same frame their parent block is regrown instead (this lets the
   partition coarsen).  A scene cut regrows the whole frame from the root.
 * dtype "bf16": values are rounded to bfloat16 (round-to-nearest-even) and
-  returned as raw uint16 bit patterns; "f32": float32.
+  returned as raw uint16 bit patterns; "f16": numpy float16; "f32": float32.
 """
 from __future__ import annotations
 
@@ -38,7 +38,7 @@ class Workload:
     H: int
     W: int
     D: int
-    dtype: str                 # "f32" | "bf16"
+    dtype: str                 # "f32" | "bf16" | "f16"
     max_depth: int
     sigma: float               # noise std (per-video range if sigma_hi set)
     persist: float             # leaf persistence prob (range if persist_hi set)
@@ -50,13 +50,16 @@ class Workload:
     tau_s: Optional[float] = None     # fixed thresholds, or None => budget mode
     tau_t: Optional[float] = None
     budgets: Tuple[float, ...] = ()   # target keep fractions in budget mode
+    root_grid: int = 1                # root nodes per side of the quadtree
 
     @property
     def n_tokens(self) -> int:
         return self.B * self.T * self.H * self.W
 
 
-# The five configurations this build is measured and parity-tested on.
+# The configurations this build is measured and parity-tested on: the five the benchmark definition names, then
+# two shapes taken from the paper's own set-up (Sec. 4.1 / 4.3): its 14 x 14 grid with 4 x 4 root nodes at up to
+# 180 frames, and a wide-channel, non-square grid (a 72B host model's hidden width on a dynamic-resolution encoder).
 CONFIGS: List[Workload] = [
     Workload("tiny", 0, 1, 8, 8, 8, 64, "f32", 3, 0.05, 0.7, tau_s=0.8, tau_t=0.8),
     Workload("short_clip", 1, 1, 64, 13, 13, 3584, "bf16", 4, 0.1, 0.8, budgets=(0.5,)),
@@ -66,6 +69,10 @@ CONFIGS: List[Workload] = [
              cut_mean_gap=64.0, budgets=(0.5, 0.3)),
     Workload("batched_unpooled", 4, 32, 32, 27, 27, 1152, "bf16", 5, 0.05, 0.3,
              sigma_hi=0.3, persist_hi=0.95, tau_s=0.9, tau_t=0.85),
+    Workload("paper_grid", 5, 1, 180, 14, 14, 3584, "bf16", 4, 0.1, 0.9, cut_mean_gap=64.0,
+             budgets=(0.5, 0.3), root_grid=4),
+    Workload("wide_nonsquare", 6, 1, 180, 18, 24, 8192, "bf16", 5, 0.1, 0.9, cut_mean_gap=64.0,
+             budgets=(0.5, 0.3)),
 ]
 
 
@@ -154,7 +161,7 @@ def generate(cfg: Workload, *, return_leaf_maps: bool = False):
     """
     rng = np.random.Generator(np.random.Philox(cfg.seed))
     P = pow2_ceil(max(cfg.H, cfg.W))
-    out_dtype = np.float32 if cfg.dtype == "f32" else np.uint16
+    out_dtype = {"f32": np.float32, "bf16": np.uint16, "f16": np.float16}[cfg.dtype]
     feats = np.empty((cfg.B, cfg.T, cfg.H, cfg.W, cfg.D), dtype=out_dtype)
     leaf_maps = np.empty((cfg.B, cfg.T, cfg.H, cfg.W), dtype=np.int32) if return_leaf_maps else None
     for b in range(cfg.B):
@@ -187,7 +194,7 @@ def generate(cfg: Workload, *, return_leaf_maps: bool = False):
             remap = np.searchsorted(uniq, ids)
             frame = base_rows[remap]                                   # [H, W, D] float32
             frame = frame + np.float32(sigma) * rng.standard_normal(frame.shape, dtype=np.float32)
-            feats[b, t] = frame if cfg.dtype == "f32" else f32_to_bf16_bits(frame)
+            feats[b, t] = f32_to_bf16_bits(frame) if cfg.dtype == "bf16" else frame   # (float16: numpy rounds)
             if leaf_maps is not None:
                 leaf_maps[b, t] = ids
     if return_leaf_maps:
@@ -208,7 +215,9 @@ def generate_alternating(cfg: Workload, sigma_fine: float) -> np.ndarray:
     for t in range(cfg.T):
         s = np.float32(sigma_fine if t % 2 else cfg.sigma)
         out[:, t] = base[:, t] + s * rng.standard_normal(base[:, t].shape, dtype=np.float32)
-    return out if cfg.dtype == "f32" else f32_to_bf16_bits(out)
+    if cfg.dtype == "bf16":
+        return f32_to_bf16_bits(out)
+    return out.astype(np.float16) if cfg.dtype == "f16" else out
 
 
 def small_variant(cfg: Workload, **over) -> Workload:

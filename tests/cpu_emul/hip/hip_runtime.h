@@ -126,6 +126,52 @@ inline int atomicMin(int* p, int v) {
   return old;
 }
 
+// ---- half precision (what <hip/hip_fp16.h> provides on the GPU), bit-exact conversions ---------------
+struct __half { unsigned short x; };
+inline __half __ushort_as_half(unsigned short u) { return __half{u}; }
+inline unsigned short __half_as_ushort(__half h) { return h.x; }
+inline float __half2float(__half h) {
+  const unsigned s = (h.x >> 15) & 1u, e = (h.x >> 10) & 31u, m = h.x & 1023u;
+  unsigned u;
+  if (e == 0) {
+    if (m == 0) { u = s << 31; }
+    else {  // subnormal: value = m * 2^-24
+      float f = (float)m * 5.9604644775390625e-08f;
+      return s ? -f : f;
+    }
+  } else if (e == 31) {
+    u = (s << 31) | 0x7f800000u | (m << 13);
+  } else {
+    u = (s << 31) | ((e + 112u) << 23) | (m << 13);
+  }
+  float f;
+  __builtin_memcpy(&f, &u, 4);
+  return f;
+}
+inline __half __float2half_rn(float f) {  // round to nearest even
+  unsigned u;
+  __builtin_memcpy(&u, &f, 4);
+  const unsigned s = (u >> 16) & 0x8000u;
+  const unsigned a = u & 0x7fffffffu;
+  if (a > 0x7f800000u) return __half{(unsigned short)(s | 0x7e00u)};           // NaN
+  if (a >= 0x47800000u) return __half{(unsigned short)(s | 0x7c00u)};          // >= 65536 (rounds to inf); inf
+  if (a < 0x33000000u) return __half{(unsigned short)s};                       // < 2^-25: zero
+  if (a < 0x38800000u) {                                                        // subnormal half
+    const float af = f < 0 ? -f : f;
+    const float scaled = af * 16777216.0f;                                      // / 2^-24: exact
+    unsigned q = (unsigned)scaled;
+    const float rem = scaled - (float)q;
+    if (rem > 0.5f || (rem == 0.5f && (q & 1u))) ++q;
+    return __half{(unsigned short)(s | q)};
+  }
+  unsigned r = a - 0x38000000u;                                                 // rebias exponent
+  const unsigned lsb = (r >> 13) & 1u;
+  r += 0xfffu + lsb;
+  r >>= 13;
+  if (r >= 0x7c00u) r = 0x7c00u;
+  return __half{(unsigned short)(s | r)};
+}
+
 // ---- host API subset -------------------------------------------------------------------------------
 typedef int hipError_t;
 constexpr hipError_t hipSuccess = 0;

@@ -10,7 +10,7 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libsttm_cpu.so")
 
-STTM_F32, STTM_BF16 = 0, 1
+STTM_F32, STTM_BF16, STTM_F16 = 0, 1, 2
 
 
 class Result:
@@ -41,7 +41,7 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
             match=0, order=0, positions=False):
     lib = lib or load()
     B, T, H, W, D = feats.shape
-    dt = STTM_BF16 if feats.dtype == np.uint16 else STTM_F32
+    dt = STTM_BF16 if feats.dtype == np.uint16 else (STTM_F16 if feats.dtype == np.float16 else STTM_F32)
     out_dtype = dt if out_dtype is None else out_dtype
     N = B * T * H * W
     h = C.c_void_p()
@@ -99,7 +99,7 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     chk(lib.sttm_export(h, 5, _p(ti), C.c_size_t(ti.nbytes)))
     r.parent = ti.reshape(B, T, H, W).copy()
     r.cluster_ids = cluster.reshape(B, T, H, W).copy()
-    esz = 2 if out_dtype == STTM_BF16 else 4
+    esz = 4 if out_dtype == STTM_F32 else 2
     merged = _aligned(N * D * esz, 16)
     counts = np.zeros(N, np.int32)
     out_ids = np.zeros(N, np.int32)
@@ -113,6 +113,8 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     if out_dtype == STTM_BF16:
         bits = merged.view(np.uint16)[:K * D].astype(np.uint32) << 16
         r.merged = bits.view(np.float32).reshape(K, D).copy()
+    elif out_dtype == STTM_F16:
+        r.merged = merged.view(np.float16)[:K * D].astype(np.float32).reshape(K, D).copy()
     else:
         r.merged = merged.view(np.float32)[:K * D].reshape(K, D).copy()
     r.counts = counts[:K].copy()

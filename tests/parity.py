@@ -22,6 +22,7 @@ BAND = O.BAND
 SIM_TOL = 1e-5          # |sigma_gpu(fp32) - sigma_oracle(fp64)|
 TOL_F32 = 1e-3          # merged features, fp32 in / fp32 out
 TOL_BF16 = 2e-2         # bf16 in, fp32 accumulate
+TOL_F16 = 5e-3          # fp16 in / out: half an ulp of the output, 2^-11 |x| <= 3.9e-3 for |x| < 8, plus fp32 sums
 
 
 class GpuResult:
@@ -44,6 +45,10 @@ def _to_dev(feats: np.ndarray):
     return torch.from_numpy(feats).cuda()
 
 
+def lib_dtype(lib, feats: np.ndarray) -> int:
+    return {np.dtype(np.uint16): lib.STTM_BF16, np.dtype(np.float16): lib.STTM_F16}.get(feats.dtype, lib.STTM_F32)
+
+
 MODES = {"first_passing": 0, "topleft_only": 1, "most_similar": 2}
 ORDERS = {"raster": 0, "zscan": 1}
 
@@ -55,7 +60,7 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     """Whole path through the C ABI. Fixed thresholds, or `keep` (budget mode)."""
     import torch
     B, T, H, W, D = feats.shape
-    dt = lib.STTM_BF16 if feats.dtype == np.uint16 else lib.STTM_F32
+    dt = lib_dtype(lib, feats)
     if out_dtype is None:
         out_dtype = dt
     x = _to_dev(feats) if feats_dev is None else feats_dev
@@ -108,7 +113,7 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     s.sttm_export(lib.STTM_TBL_PARENT, ti)
     r.parent = ti.cpu().numpy().reshape(B, T, H, W)
     r.cluster_ids = cluster.cpu().numpy().reshape(B, T, H, W)
-    odt = torch.bfloat16 if out_dtype == lib.STTM_BF16 else torch.float32
+    odt = {lib.STTM_BF16: torch.bfloat16, lib.STTM_F16: torch.float16}.get(out_dtype, torch.float32)
     merged = torch.zeros(N, D, dtype=odt, device=dev)
     counts = torch.zeros(N, dtype=torch.int32, device=dev)
     out_ids = torch.zeros(N, dtype=torch.int32, device=dev)
@@ -229,20 +234,25 @@ def check_positions(r: GpuResult, sp, tm, order: str = "raster"):
     return err
 
 
-def check_reduce(feats, r: GpuResult, tm, out_is_bf16: bool, order: str = "raster"):
+def check_reduce(feats, r: GpuResult, tm, out_is_bf16: bool, order: str = "raster", out_is_f16: bool = False):
     rd = O.reduce_clusters(feats, tm.cluster_ids, order)
     assert r.K == len(rd.counts)
     assert (r.counts == rd.counts).all() and (r.out_ids == rd.out_ids).all()
     assert (r.offsets == rd.offsets).all()
     assert int(r.counts.sum()) == feats.shape[0] * feats.shape[1] * feats.shape[2] * feats.shape[3]
-    tol = TOL_BF16 if (feats.dtype == np.uint16 or out_is_bf16) else TOL_F32
+    if feats.dtype == np.uint16 or out_is_bf16:
+        tol = TOL_BF16
+    elif feats.dtype == np.float16 or out_is_f16:
+        tol = TOL_F16
+    else:
+        tol = TOL_F32
     err = float(np.abs(r.merged.astype(np.float64) - rd.merged).max()) if r.K else 0.0
     assert err <= tol, f"merged feature error {err} > {tol}"
     return rd, err
 
 
 def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None, root_grid=1,
-                 out_is_bf16=None, mode: str = "first_passing", order: str = "raster"):
+                 out_is_bf16=None, mode: str = "first_passing", order: str = "raster", out_is_f16: bool = False):
     """Full comparison; returns a dict with the error figures and near-threshold counts."""
     B, T, H, W, D = feats.shape
     if out_is_bf16 is None:
@@ -276,7 +286,7 @@ def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None,
             assert len(np.unique(r.cluster_ids[b])) <= target or base > target
         info["tau_t"] = tt
     tm, e2 = check_temporal(lib, feats, r, sp, tt, cands, mode)
-    rd, e3 = check_reduce(feats, r, tm, out_is_bf16, order)
+    rd, e3 = check_reduce(feats, r, tm, out_is_bf16, order, out_is_f16)
     if hasattr(r, "survived"):
         info["merged_pos_err"] = check_positions(r, sp, tm, order)
     info.update(spatial_sim_err=e1, temporal_sim_err=e2, merged_err=e3, near_spatial=sp.near,

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.skipif(shutil.which("g++") is None, reason="needs g++")
 
 
 class _EmulLib:
-    STTM_BF16, STTM_F32 = 1, 0
+    STTM_BF16, STTM_F32, STTM_F16 = 1, 0, 2
 
     def __init__(self, rc):
         self._lib = rc.load()
@@ -41,6 +41,7 @@ def _variant(seed, B, T, H, W, D, dtype):
     (90, 1, 3, 8, 8, 16, "f32", dict(tau_s=0.8, tau_t=0.8)),
     (91, 2, 3, 5, 6, 24, "bf16", dict(keep=0.5)),
     (92, 1, 2, 9, 9, 16, "bf16", dict(tau_s=0.2, tau_t=0.2)),   # nodes that the reduce takes from stored sums
+    (93, 1, 3, 8, 8, 24, "f16", dict(tau_s=0.7, tau_t=0.7)),    # half-precision input and output
 ])
 def test_emulated_kernels_match_the_oracle(emul, seed, B, T, H, W, D, dtype, kw):
     run_cpu, fake = emul

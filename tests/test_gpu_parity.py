@@ -26,7 +26,7 @@ def _run_and_check(lib, cfg, *, tau_s=None, tau_t=None, keep=None, root_grid=1, 
     r = P.run_gpu(lib, feats, tau_s=tau_s, tau_t=tau_t, keep=keep, root_grid=root_grid, out_dtype=out_dtype)
     out_bf16 = (out_dtype == lib.STTM_BF16) if out_dtype is not None else None
     info = P.check_parity(lib, feats, r, tau_s=tau_s, tau_t=tau_t, keep=keep, root_grid=root_grid,
-                          out_is_bf16=out_bf16)
+                          out_is_bf16=out_bf16, out_is_f16=out_dtype == lib.STTM_F16)
     print("  ", {k: (float(v) if isinstance(v, (float, np.floating)) else v) for k, v in info.items()
                  if k not in ("tau_s", "tau_t")}, flush=True)
     return feats, r, info
@@ -51,6 +51,10 @@ def test_config0_tiny_fixed_thresholds(lib):
     (17, 1, 1, 1, 1, 16, "bf16", 0.5, 0.5, 1),        # a single token
     (18, 1, 9, 32, 32, 1032, "bf16", 0.9, 0.9, 1),    # full 32x32, three chunks
     (19, 2, 3, 8, 8, 256, "f32", 0.6, 0.95, 8),       # root_grid == P: nothing to merge spatially
+    (20, 1, 5, 13, 13, 200, "f16", 0.9, 0.8, 1),      # half-precision input, ragged chunk
+    (21, 2, 3, 14, 14, 1032, "f16", 0.8, 0.85, 4),    # half precision, three chunks, 4x4 roots
+    (22, 1, 3, 18, 24, 8192, "bf16", 0.9, 0.8, 1),    # 16 chunks (the widest row one workgroup covers), non-square
+    (23, 1, 2, 7, 30, 8200, "f32", 0.8, 0.8, 1),      # fp32, 33 chunks: more chunks than wavefronts per workgroup
 ])
 def test_small_shapes_fixed_thresholds(lib, seed, B, T, H, W, D, dtype, tau_s, tau_t, R):
     cfg = _variant(seed, B, T, H, W, D, dtype)
@@ -72,6 +76,17 @@ def test_small_shapes_budget_mode(lib, seed, H, W, D, dtype, keep, R):
         kb = r.offsets[b + 1] - r.offsets[b]
         if r.tau_t[b] > -2:
             assert kb <= math.floor(k * N1)
+
+
+def test_half_precision_budget_and_output_types(lib):
+    cfg = _variant(24, 1, 6, 13, 13, 520, "f16")
+    _run_and_check(lib, cfg, keep=0.5)
+    _run_and_check(lib, cfg, tau_s=0.9, tau_t=0.8, out_dtype=lib.STTM_F32)
+    _run_and_check(lib, _variant(25, 1, 4, 8, 8, 64, "f32"), tau_s=0.9, tau_t=0.8, out_dtype=lib.STTM_F16)
+    feats = wl.generate(_variant(26, 1, 2, 8, 8, 64, "bf16"))
+    with pytest.raises(lib.SttmError) as e:                       # a 16-bit input is not converted to the other one
+        P.run_gpu(lib, feats, tau_s=0.9, tau_t=0.8, out_dtype=lib.STTM_F16)
+    assert e.value.code == lib.STTM_ERR_DTYPE
 
 
 def test_mixed_output_dtypes(lib):
@@ -312,6 +327,14 @@ def test_config2_encoder_width_budget(lib):
 def test_config3_long_video_budget(lib, keep):
     cfg = wl.CONFIGS[3]
     _run_and_check(lib, cfg, keep=keep)
+
+
+@pytest.mark.parametrize("index,keep,frames", [(5, 0.3, 180), (6, 0.5, 40)])
+def test_paper_shapes_budget(lib, index, keep, frames):
+    """The paper's own grid (14 x 14, 4 x 4 roots, 180 frames) and a wide non-square one (its first 40 frames:
+    the oracle needs a minute for all 180), in budget mode."""
+    cfg = wl.small_variant(wl.CONFIGS[index], T=frames)
+    _run_and_check(lib, cfg, keep=keep, root_grid=cfg.root_grid)
 
 
 def test_config4_batched_fixed_thresholds_sampled_videos(lib):
