@@ -49,6 +49,10 @@ def main() -> int:
     ap.add_argument("--keep", type=float, default=None, help="token budget (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=512, help="frames of the workload the oracle is timed on")
+    ap.add_argument("--match", choices=["first_passing", "topleft_only", "most_similar"], default="first_passing",
+                    help="destination rule of the temporal stage (default: the paper's top-left-most passing one)")
+    ap.add_argument("--order", choices=["raster", "zscan"], default="raster", help="row order of the output")
+    ap.add_argument("--positions", action="store_true", help="also emit the position indices of the rows each step")
     ap.add_argument("--no-node-sums", action="store_true",
                     help="reduce stage without the stage-1 partition: every cell is read again")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -73,8 +77,9 @@ def main() -> int:
     gen_s = time.time() - t0
     B, T, H, W, D = feats.shape
     N = B * T * H * W
-    dt = lib.STTM_BF16 if feats.dtype == np.uint16 else lib.STTM_F32
-    esz = 2 if dt == lib.STTM_BF16 else 4
+    dt = {np.dtype(np.uint16): lib.STTM_BF16, np.dtype(np.float16): lib.STTM_F16}.get(feats.dtype, lib.STTM_F32)
+    esz = 4 if dt == lib.STTM_F32 else 2
+    R = cfg.root_grid
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if feats.dtype == np.uint16:
@@ -83,7 +88,9 @@ def main() -> int:
         x = torch.from_numpy(feats).to(dev)
 
     s = lib.Sttm(0)
-    s.ensure_workspace(B, T, H, W, D, dt, 1)
+    s.sttm_set_match_mode({"first_passing": 0, "topleft_only": 1, "most_similar": 2}[args.match])
+    s.sttm_set_output_order({"raster": 0, "zscan": 1}[args.order])
+    s.ensure_workspace(B, T, H, W, D, dt, R)
     node_map = torch.empty(N, dtype=torch.int32, device=dev)
     node_level = torch.empty(N, dtype=torch.uint8, device=dev)
     cluster = torch.empty(N, dtype=torch.int32, device=dev)
@@ -91,20 +98,27 @@ def main() -> int:
     counts = torch.empty(N, dtype=torch.int32, device=dev)
     out_ids = torch.empty(N, dtype=torch.int32, device=dev)
     offsets = torch.zeros(B + 1, dtype=torch.int64, device=dev)
+    if args.positions:
+        pos_sv = torch.empty(N, dtype=torch.int32, device=dev)
+        pos_ra = torch.empty(N, dtype=torch.int32, device=dev)
+        pos_mg = torch.empty(N, dtype=torch.float32, device=dev)
+        pos_rt = torch.empty(N, 4, dtype=torch.int32, device=dev)
 
     def step():
         if budget_mode:
-            s.sttm_spatial_stats(x, dt, B, T, H, W, D, 1)
+            s.sttm_spatial_stats(x, dt, B, T, H, W, D, R)
             s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, keep, want_tau=False)
-            s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, 1, None, node_map, node_level)
+            s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, R, None, node_map, node_level)
             s.sttm_temporal_stats(x, node_map, node_level)
             s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, keep, want_tau=False)
             s.sttm_temporal_merge(x, node_map, node_level, None, cluster)
         else:
-            s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, 1, [cfg.tau_s], node_map, node_level)
+            s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, R, [cfg.tau_s], node_map, node_level)
             s.sttm_temporal_merge(x, node_map, node_level, [cfg.tau_t], cluster)
         s.sttm_reduce(x, cluster, None if args.no_node_sums else node_map,
                       None if args.no_node_sums else node_level, dt, N, merged, counts, out_ids, offsets, want_n=False)
+        if args.positions:
+            s.sttm_positions(cluster, node_map, node_level, offsets, N, pos_sv, pos_ra, pos_mg, pos_rt)
 
     for _ in range(args.warmup):
         step()
@@ -151,10 +165,14 @@ def main() -> int:
         "unit": "Mtok/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if dt == lib.STTM_BF16 else "f32", "data": "synthetic",
+        "dtype": {lib.STTM_BF16: "bf16", lib.STTM_F16: "f16"}.get(dt, "f32"), "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: B={B} T={T} grid={H}x{W} D={D} "
                                f"{cfg.dtype}, " + (f"budget keep={keep}" if budget_mode else
-                                                   f"tau_s={cfg.tau_s} tau_t={cfg.tau_t}"),
+                                                   f"tau_s={cfg.tau_s} tau_t={cfg.tau_t}")
+                               + (f", root_grid={R}" if R != 1 else "")
+                               + (f", match={args.match}" if args.match != "first_passing" else "")
+                               + (f", order={args.order}" if args.order != "raster" else "")
+                               + (", with position indices" if args.positions else ""),
                    "tokens": N, "kept_tokens": K, "kept_fraction": rho, "generate_s": gen_s},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": traffic.get(dom),
@@ -173,13 +191,13 @@ def main() -> int:
             limiter = threadpool_limits(limits=1)
         except Exception:  # pragma: no cover
             limiter = None
-        nf = min(T, args.cpu_frames)
+        nf = min(T, args.cpu_frames, max(2, int(3.2e8 // (H * W * D))))   # bounds the oracle's work to tens of seconds
         sample = feats[:1, :nf]
         t0 = time.perf_counter()
         if budget_mode:
-            O.sttm(sample, keep=keep)
+            O.sttm(sample, keep=keep, root_grid=R, mode=args.match, order=args.order)
         else:
-            O.sttm(sample, tau_s=cfg.tau_s, tau_t=cfg.tau_t)
+            O.sttm(sample, tau_s=cfg.tau_s, tau_t=cfg.tau_t, root_grid=R, mode=args.match, order=args.order)
         cpu_s = time.perf_counter() - t0
         if limiter is not None:
             limiter.restore_original_limits()

@@ -185,10 +185,11 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
  *                                "merged" strategy, which averages the members' rotary embeddings);
  *   root_tyxl  int32 [capacity, 4]: (t, y0, x0, level) of the root node, for encodings built on (t, y, x);
  *                                level is -1 when node_level is NULL.
- * cluster_ids / node_level as given to sttm_temporal_merge; offsets as written by sttm_reduce. Asynchronous.
- * STTM_ERR_STATE unless sttm_reduce ran last on this context with these cluster_ids. */
-int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const uint8_t* node_level_dev,
-                   const int64_t* offsets_dev, int64_t capacity, int32_t* survived_dev, int32_t* reassigned_dev,
+ * cluster_ids / node_map / node_level as given to sttm_temporal_merge (node_map and node_level may be NULL; with
+ * both, every node is counted in one step instead of cell by cell); offsets as written by sttm_reduce.
+ * Asynchronous. STTM_ERR_STATE unless sttm_reduce ran last on this context with these cluster_ids. */
+int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const int32_t* node_map_dev,
+                   const uint8_t* node_level_dev, const int64_t* offsets_dev, int64_t capacity, int32_t* survived_dev, int32_t* reassigned_dev,
                    float* merged_pos_dev, int32_t* root_tyxl_dev);
 
 /* ---- inspection ---------------------------------------------------------------------------------------- */

@@ -62,7 +62,7 @@ def _load() -> C.CDLL:
     lib.sttm_profile_read.argtypes = [vp, i, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.sttm_set_match_mode.argtypes = [vp, i]
     lib.sttm_set_output_order.argtypes = [vp, i]
-    lib.sttm_positions.argtypes = [vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.sttm_positions.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     return lib
 
 
@@ -182,9 +182,10 @@ class Sttm:
     def sttm_set_output_order(self, order: int):
         self._check(_lib.sttm_set_output_order(self._h, order))
 
-    def sttm_positions(self, cluster_ids, node_level, offsets, capacity, survived=None, reassigned=None,
+    def sttm_positions(self, cluster_ids, node_map, node_level, offsets, capacity, survived=None, reassigned=None,
                        merged_pos=None, root_tyxl=None):
-        self._check(_lib.sttm_positions(self._h, _ptr(cluster_ids), _ptr(node_level), _ptr(offsets), capacity,
+        self._check(_lib.sttm_positions(self._h, _ptr(cluster_ids), _ptr(node_map), _ptr(node_level), _ptr(offsets),
+                                        capacity,
                                         _ptr(survived), _ptr(reassigned), _ptr(merged_pos), _ptr(root_tyxl)))
 
     def sttm_export(self, table, dst):

@@ -19,7 +19,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_s, sel_t, lvl,
       pd_part, sig, e, parent, ptr_a, ptr_b;
-  size_t rank, key_a, val_a, key_b, val_b, order, orow, hist, tot, tile_roots, tile_live, seg, kdev,
+  size_t rank, key_a, val_a, key_b, val_b, order, orow, hist, tot, gsum, tile_roots, tile_live, seg, kdev,
       bigpart, bigw, biglist, zpos, possum, poscnt;
   size_t total;
 };
@@ -86,6 +86,7 @@ Layout make_layout(const Geo& g) {
   l.orow = take(N * sizeof(int32_t));
   l.hist = take(reduce_hist_entries(g.N) * sizeof(int32_t));
   l.tot = take(2048 * sizeof(int32_t));
+  l.gsum = take(reduce_gsum_entries() * sizeof(int32_t));
   l.tile_roots = take(reduce_tiles(g.N) * sizeof(int32_t));
   l.tile_live = take(reduce_tiles(g.N) * sizeof(int32_t));
   l.seg = take((N + 1) * sizeof(int32_t));
@@ -505,6 +506,7 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
   rb.orow = at<int32_t>(ctx, ctx->lay.orow);
   rb.hist = at<int32_t>(ctx, ctx->lay.hist);
   rb.tot = at<int32_t>(ctx, ctx->lay.tot);
+  rb.gsum = at<int32_t>(ctx, ctx->lay.gsum);
   rb.tile_roots = at<int32_t>(ctx, ctx->lay.tile_roots);
   rb.tile_live = at<int32_t>(ctx, ctx->lay.tile_live);
   rb.seg = at<int32_t>(ctx, ctx->lay.seg);
@@ -542,8 +544,8 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
   return STTM_OK;
 }
 
-int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const uint8_t* node_level_dev,
-                   const int64_t* offsets_dev, int64_t capacity, int32_t* survived_dev, int32_t* reassigned_dev,
+int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const int32_t* node_map_dev,
+                   const uint8_t* node_level_dev, const int64_t* offsets_dev, int64_t capacity, int32_t* survived_dev, int32_t* reassigned_dev,
                    float* merged_pos_dev, int32_t* root_tyxl_dev) {
   if (!ctx) return STTM_ERR_NULL;
   if (!cluster_ids_dev || !offsets_dev) return fail(ctx, STTM_ERR_NULL, "cluster_ids and offsets are required");
@@ -560,7 +562,8 @@ int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const uint8_t*
   rb.seg = at<int32_t>(ctx, ctx->lay.seg);
   rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
   rb.zpos = at<int32_t>(ctx, ctx->lay.zpos);
-  launch_positions(ctx->g, cluster_ids_dev, node_level_dev, offsets_dev, capacity, rb, ctx->reduced_zscan,
+  launch_positions(ctx->g, cluster_ids_dev, node_map_dev, node_level_dev, offsets_dev, capacity, rb,
+                   ctx->reduced_zscan,
                    at<unsigned long long>(ctx, ctx->lay.possum), at<unsigned>(ctx, ctx->lay.poscnt), survived_dev,
                    reassigned_dev, merged_pos_dev, root_tyxl_dev, ctx->stream);
   return after_launch(ctx);

@@ -230,7 +230,8 @@ struct ReduceBuffers {
   int32_t* order;       // [N] sorted element list (live part first)
   int32_t* orow;        // [N] output row of every list position
   int32_t* hist;        // [tiles][digits] radix histogram of the running pass
-  int32_t* tot;         // [digits] column totals (large inputs)
+  int32_t* tot;         // [digits] column totals (very large inputs)
+  int32_t* gsum;        // [groups of tiles][digits] partial column sums (medium inputs)
   int32_t* tile_roots;  // [tiles]
   int32_t* tile_live;   // [tiles]
   int32_t* seg;         // [N+1] first list position of every output row
@@ -251,7 +252,8 @@ void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const
                        const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
                        const ReduceBuffers& rb, bool zscan, hipStream_t s);
 // Position indices of the rows of the reduce call that has just run (its list, ranks and row map are still in `rb`).
-void launch_positions(const Geo& g, const int32_t* cluster_ids, const uint8_t* node_level, const int64_t* offsets,
+void launch_positions(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map, const uint8_t* node_level,
+                      const int64_t* offsets,
                       int64_t capacity, const ReduceBuffers& rb, bool zscan, unsigned long long* possum,
                       unsigned* poscnt, int32_t* survived, int32_t* reassigned, float* merged_pos,
                       int32_t* root_tyxl, hipStream_t s);
@@ -261,5 +263,6 @@ bool reduce_io_supported(int in_dtype, int out_dtype);
 size_t reduce_biglist_entries(const Geo& g);
 size_t reduce_hist_entries(int N);
 size_t reduce_tiles(int N);
+size_t reduce_gsum_entries();
 
 }  // namespace sttm

@@ -18,11 +18,17 @@ constexpr int kItem = 16;  // list positions per gather item
 constexpr int kBig = 64;   // clusters with more list slots than this are summed window by window
 constexpr int kTail = 8;
 constexpr int kMaxDigits = 1 << kMaxDigitBits;
-constexpr int kInKernelColumns = 256;  // up to this many tiles a scatter workgroup sums the histogram columns itself
+// How a scatter workgroup gets its start offsets from hist[tile][digit]: up to kDirectTiles tiles it adds up all
+// rows itself; up to kGroupTiles * kMaxGroups tiles a small kernel first adds the rows in groups of kGroupTiles
+// and the workgroup adds the group sums and the rows of its own group; beyond that k_sort_colscan turns the
+// columns into running sums in place.
+constexpr int kDirectTiles = 64;
+constexpr int kGroupTiles = 32;
+constexpr int kMaxGroups = 256;
 
 struct SortPlan {
   int passes, dbits, nb;
-  bool prescan;
+  int mode;  // 0 = direct, 1 = grouped, 2 = column scan
 };
 
 static SortPlan sort_plan(int N) {
@@ -33,11 +39,12 @@ static SortPlan sort_plan(int N) {
   p.dbits = (bits + p.passes - 1) / p.passes;
   if (p.dbits < 2) p.dbits = 2;  // a histogram row is read in pieces of four digits
   p.nb = (N + kSortTile - 1) / kSortTile;
-  p.prescan = p.nb > kInKernelColumns;
+  p.mode = p.nb <= kDirectTiles ? 0 : (p.nb <= kGroupTiles * kMaxGroups ? 1 : 2);
   return p;
 }
 
 size_t reduce_tiles(int N) { return (size_t)(N + kSortTile - 1) / kSortTile; }
+size_t reduce_gsum_entries() { return (size_t)kMaxGroups * kMaxDigits; }
 size_t reduce_hist_entries(int N) { return (size_t)kMaxDigits * reduce_tiles(N); }
 
 // Exclusive prefix of v over the 256 threads of the workgroup; *total = sum over all threads.
@@ -184,6 +191,58 @@ __global__ __launch_bounds__(256) void k_sort_colscan(int nb, int DIG, int32_t* 
   tot[d] = run;
 }
 
+// Medium inputs: gsum[group][digit] = sum of the group's rows of hist[tile][digit]; one thread per digit, the
+// group's rows in two batches of loads.
+__global__ __launch_bounds__(256) void k_sort_groupsum(int nb, int DIG, const int32_t* __restrict__ hist,
+                                                       int32_t* __restrict__ gsum) {
+  const int d = blockIdx.x * blockDim.x + threadIdx.x, grp = blockIdx.y;
+  if (d >= DIG) return;
+  const int t0 = grp * kGroupTiles;
+  int run = 0;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    int v[kGroupTiles / 2];
+#pragma unroll
+    for (int u = 0; u < kGroupTiles / 2; ++u) {
+      const int t = t0 + h * (kGroupTiles / 2) + u;
+      v[u] = t < nb ? hist[(size_t)t * DIG + d] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < kGroupTiles / 2; ++u) run += v[u];
+  }
+  gsum[(size_t)grp * DIG + d] = run;
+}
+
+// Adds rows [r0, r1) of a table of 2^dbits-int rows to at[] (if to_total) and, for the rows below `limit`, to
+// am[]. The table is read as 16-byte pieces, consecutive threads next to each other, sixteen loads in flight per
+// thread; the four digits a thread sees do not change from load to load (two sets when a row has more pieces
+// than the workgroup has threads).
+__device__ inline void sort_add_rows(const int32_t* __restrict__ table, int r0, int r1, int dbits, int limit,
+                                     bool to_total, int (&at)[2][4], int (&am)[2][4]) {
+  const int vshift = dbits - 2;  // log2 of the 16-byte pieces per row
+  const int first = r0 << vshift, last = r1 << vshift;
+  const int4* h4 = reinterpret_cast<const int4*>(table);
+  for (int q0 = first + (int)threadIdx.x; q0 < last; q0 += 16 * kSortThreads) {
+    int4 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int q = q0 + u * kSortThreads;
+      v[u] = q < last ? h4[q] : make_int4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int q = q0 + u * kSortThreads;
+      const bool before = (q >> vshift) < limit;
+      const int e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (to_total) at[u & 1][i] += e[i];
+        if (before) am[u & 1][i] += e[i];
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // k_sort_pass: one stable scatter pass, one workgroup per tile of 2048 elements. The workgroup first turns
 // the histogram into its own start offset for every digit (summing the columns over the tiles before it
@@ -196,7 +255,8 @@ __global__ __launch_bounds__(256) void k_sort_colscan(int nb, int DIG, int32_t* 
 //          position of every row (the root is the smallest index of its cluster, hence first in its list).
 // ------------------------------------------------------------------------------------------------
 struct SortArgs {
-  int n, shift, dbits, nb, prescan;
+  int n, shift, dbits, nb, mode;  // mode: how the start offsets are found (see kDirectTiles)
+  const int32_t* gsum;
   const int32_t* keys;
   const int32_t* vals;
   int32_t* keys_out;
@@ -260,35 +320,18 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
   // ---- start offset of every digit for this tile
   int* tot = cur[0];   // column totals and the part of them that lies in the tiles before this one
   int* mine = cur[1];  // (the cursors are not in use yet)
-  if (!a.prescan) {
-    // hist[tile][digit] is read as 16-byte pieces, consecutive threads next to each other, sixteen loads in
-    // flight per thread; the four digits a thread sees do not change from load to load (two sets when a row
-    // has more pieces than the workgroup has threads)
+  if (a.mode != 2) {
     for (int d = tid; d < DIG; d += kSortThreads) tot[d] = mine[d] = 0;
     __syncthreads();
-    const int vshift = a.dbits - 2, VC = 1 << vshift;  // 16-byte pieces per tile row
-    const int total4 = a.nb << vshift;
-    const int4* h4 = reinterpret_cast<const int4*>(a.hist);
     int at[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, am[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
-    for (int q0 = tid; q0 < total4; q0 += 16 * kSortThreads) {
-      int4 v[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int q = q0 + u * kSortThreads;
-        v[u] = q < total4 ? h4[q] : make_int4(0, 0, 0, 0);
-      }
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int q = q0 + u * kSortThreads;
-        const bool before = (q >> vshift) < b;  // the piece's tile
-        const int e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          at[u & 1][i] += e[i];
-          if (before) am[u & 1][i] += e[i];
-        }
-      }
+    if (a.mode == 0) {
+      sort_add_rows(a.hist, 0, a.nb, a.dbits, b, true, at, am);
+    } else {  // the sums of all groups, then the rows of this tile's own group up to the tile
+      const int grp = b / kGroupTiles, ngrp = (a.nb + kGroupTiles - 1) / kGroupTiles;
+      sort_add_rows(a.gsum, 0, ngrp, a.dbits, grp, true, at, am);
+      sort_add_rows(a.hist, grp * kGroupTiles, min(a.nb, (grp + 1) * kGroupTiles), a.dbits, b, false, at, am);
     }
+    const int VC = 1 << (a.dbits - 2);
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
       const int vc = (tid + k * kSortThreads) & (VC - 1);
@@ -314,8 +357,8 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_pass(SortArgs a) {
       const int d = tid * dpt + j;
       tv[j] = cv[j] = 0;
       if (j < dpt && d < DIG) {
-        tv[j] = a.prescan ? a.tot[d] : tot[d];
-        cv[j] = a.prescan ? a.hist[(size_t)b * DIG + d] : mine[d];
+        tv[j] = a.mode == 2 ? a.tot[d] : tot[d];
+        cv[j] = a.mode == 2 ? a.hist[(size_t)b * DIG + d] : mine[d];
       }
       s += tv[j];
     }
@@ -753,15 +796,32 @@ __global__ __launch_bounds__(256) void k_positions_clear(int n, unsigned long lo
   }
 }
 
+// With the stage-1 partition at hand a whole node is added at once, by its top-left cell: the sum of the indices
+// of its valid cells has a closed form, and a cluster made of a few large nodes costs a few atomics instead of
+// hundreds on one address.
 __global__ __launch_bounds__(256) void k_positions_cells(Geo g, const int32_t* __restrict__ cluster_ids,
+                                                         const int32_t* __restrict__ node_map,
+                                                         const uint8_t* __restrict__ node_level,
                                                          const int32_t* __restrict__ rank,
                                                          unsigned long long* __restrict__ possum,
                                                          unsigned* __restrict__ poscnt) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= g.N) return;
+  const int loc = i % (g.T * g.HW);
+  unsigned long long sum = (unsigned long long)loc;
+  unsigned cnt = 1u;
+  if (node_map) {
+    if (node_map[i] != i) return;
+    const int c = loc % g.HW, y0 = c / g.W, x0 = c - y0 * g.W, s = 1 << node_level[i];
+    const int ny = min(y0 + s, g.H) - y0, nx = min(x0 + s, g.W) - x0;
+    // sum over y0 <= y < y0+ny, x0 <= x < x0+nx of (loc + (y - y0) * W + (x - x0))
+    cnt = (unsigned)(ny * nx);
+    sum = (unsigned long long)cnt * loc + (unsigned long long)nx * g.W * (ny * (ny - 1) / 2) +
+          (unsigned long long)ny * (nx * (nx - 1) / 2);
+  }
   const int r = rank[cluster_ids[i]];
-  atomicAdd(&possum[r], (unsigned long long)(i % (g.T * g.HW)));
-  atomicAdd(&poscnt[r], 1u);
+  atomicAdd(&possum[r], sum);
+  atomicAdd(&poscnt[r], cnt);
 }
 
 __global__ __launch_bounds__(256) void k_positions_rows(Geo g, const int32_t* __restrict__ kdev,
@@ -794,14 +854,16 @@ __global__ __launch_bounds__(256) void k_positions_rows(Geo g, const int32_t* __
   }
 }
 
-void launch_positions(const Geo& g, const int32_t* cluster_ids, const uint8_t* node_level, const int64_t* offsets,
+void launch_positions(const Geo& g, const int32_t* cluster_ids, const int32_t* node_map, const uint8_t* node_level,
+                      const int64_t* offsets,
                       int64_t capacity, const ReduceBuffers& rb, bool zscan, unsigned long long* possum,
                       unsigned* poscnt, int32_t* survived, int32_t* reassigned, float* merged_pos,
                       int32_t* root_tyxl, hipStream_t s) {
   const dim3 grid((g.N + 255) / 256), block(256);
   if (merged_pos) {
     hipLaunchKernelGGL(k_positions_clear, grid, block, 0, s, g.N, possum, poscnt);
-    hipLaunchKernelGGL(k_positions_cells, grid, block, 0, s, g, cluster_ids, rb.rank, possum, poscnt);
+    hipLaunchKernelGGL(k_positions_cells, grid, block, 0, s, g, cluster_ids, node_level ? node_map : nullptr,
+                       node_level, rb.rank, possum, poscnt);
   }
   hipLaunchKernelGGL(k_positions_rows, grid, block, 0, s, g, rb.kdev, rb.order, rb.seg, zscan ? rb.zpos : nullptr,
                      node_level, offsets, possum, poscnt, capacity, survived, reassigned, merged_pos, root_tyxl);
@@ -825,10 +887,13 @@ void launch_reduce_prepare(const Geo& g, const int32_t* cluster_ids, const int32
     const bool first = pass == 0, last = pass == pl.passes - 1;
     if (!first)
       hipLaunchKernelGGL(k_sort_hist, grid, block, 0, s, rb.kdev, pass * pl.dbits, pl.dbits, kin, rb.hist);
-    if (pl.prescan)
+    if (pl.mode == 2)
       hipLaunchKernelGGL(k_sort_colscan, dim3((DIG + 255) / 256), dim3(256), 0, s, pl.nb, DIG, rb.hist, rb.tot);
+    else if (pl.mode == 1)
+      hipLaunchKernelGGL(k_sort_groupsum, dim3((DIG + 255) / 256, (pl.nb + kGroupTiles - 1) / kGroupTiles), dim3(256), 0,
+                         s, pl.nb, DIG, rb.hist, rb.gsum);
     SortArgs a;
-    a.n = N; a.shift = pass * pl.dbits; a.dbits = pl.dbits; a.nb = pl.nb; a.prescan = pl.prescan ? 1 : 0;
+    a.n = N; a.shift = pass * pl.dbits; a.dbits = pl.dbits; a.nb = pl.nb; a.mode = pl.mode; a.gsum = rb.gsum;
     a.keys = kin; a.vals = vin; a.keys_out = kout; a.vals_out = last ? rb.order : vout;
     a.hist = rb.hist; a.tot = rb.tot;
     a.cluster_ids = cluster_ids; a.rank = rb.rank; a.tile_roots = rb.tile_roots; a.tile_live = rb.tile_live;

@@ -123,7 +123,8 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     if positions:
         sv, ra = np.zeros(N, np.int32), np.zeros(N, np.int32)
         mp, rt = np.zeros(N, np.float32), np.zeros(4 * N, np.int32)
-        chk(lib.sttm_positions(h, _p(cluster), _p(node_level), _p(offsets), C.c_int64(N), _p(sv), _p(ra), _p(mp),
+        chk(lib.sttm_positions(h, _p(cluster), _p(node_map) if use_nodes else None, _p(node_level), _p(offsets),
+                               C.c_int64(N), _p(sv), _p(ra), _p(mp),
                                _p(rt)))
         r.survived, r.reassigned, r.merged_pos = sv[:K].copy(), ra[:K].copy(), mp[:K].copy()
         r.root_tyxl = rt[:4 * K].reshape(K, 4).copy()

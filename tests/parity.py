@@ -131,7 +131,7 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
         ra = torch.zeros(N, dtype=torch.int32, device=dev)
         mp = torch.zeros(N, dtype=torch.float32, device=dev)
         rt = torch.zeros(N, 4, dtype=torch.int32, device=dev)
-        s.sttm_positions(cluster, node_level, offsets, N, sv, ra, mp, rt)
+        s.sttm_positions(cluster, node_map if use_nodes else None, node_level, offsets, N, sv, ra, mp, rt)
         _trace("positions")
         r.survived, r.reassigned = sv[:K].cpu().numpy(), ra[:K].cpu().numpy()
         r.merged_pos, r.root_tyxl = mp[:K].cpu().numpy(), rt[:K].cpu().numpy()

@@ -247,6 +247,47 @@ def test_error_paths(lib):
     np.testing.assert_array_equal(merged.cpu().numpy(), x.view(128, 16)[:4].cpu().numpy())
 
 
+@pytest.mark.parametrize("B,T,H,W", [
+    (1, 20, 16, 16),        # 5 k tokens: the scatter workgroups add up the histogram rows themselves
+    (4, 64, 27, 27),        # 187 k tokens: rows added up in groups first
+    (16, 1030, 32, 32),     # 16.9 M tokens: columns turned into running sums in place
+])
+def test_identity_at_every_size_class_of_the_list_sort(lib, B, T, H, W):
+    """Thresholds of 1 merge nothing (the clamp makes every similarity <= 1 and the test is strict): the output
+    is the input, row for row, whatever path the element sort takes for its start offsets."""
+    import torch
+    D, N = 8, B * T * H * W
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(1234 + N)
+    x = torch.randn(N, D, device="cuda:0", generator=gen)
+    print(f"case identity B={B} T={T} grid={H}x{W} N={N}", flush=True)
+    s = lib.Sttm(0)
+    s.ensure_workspace(B, T, H, W, D, lib.STTM_F32, 1)
+    nm = torch.empty(N, dtype=torch.int32, device="cuda:0")
+    nl = torch.empty(N, dtype=torch.uint8, device="cuda:0")
+    cl = torch.empty(N, dtype=torch.int32, device="cuda:0")
+    s.sttm_spatial_quadtree(x, lib.STTM_F32, B, T, H, W, D, 1, [1.0] * B, nm, nl)
+    s.sttm_temporal_merge(x, nm, nl, [1.0] * B, cl)
+    ar = torch.arange(N, dtype=torch.int32, device="cuda:0")
+    assert torch.equal(nm, ar) and torch.equal(cl, ar) and int(nl.max().item()) == 0
+    merged = torch.zeros(N, D, device="cuda:0")
+    counts = torch.zeros(N, dtype=torch.int32, device="cuda:0")
+    out_ids = torch.zeros(N, dtype=torch.int32, device="cuda:0")
+    off = torch.zeros(B + 1, dtype=torch.int64, device="cuda:0")
+    K = s.sttm_reduce(x, cl, nm, nl, lib.STTM_F32, N, merged, counts, out_ids, off)
+    assert K == N and torch.equal(out_ids, ar) and int(counts.min().item()) == 1 and int(counts.max().item()) == 1
+    assert torch.equal(off, torch.arange(B + 1, dtype=torch.int64, device="cuda:0") * (T * H * W))
+    assert torch.equal(merged, x)
+
+
+def test_positions_without_the_partition(lib):
+    cfg = wl.Workload("alt", 95, 2, 5, 8, 8, 16, "f32", 2, 0.05, 0.9)
+    feats = wl.generate_alternating(cfg, 0.7)
+    r = P.run_gpu(lib, feats, tau_s=0.9, tau_t=0.8, positions=True, use_nodes=False)
+    info = P.check_parity(lib, feats, r, tau_s=0.9, tau_t=0.8)
+    assert "merged_pos_err" in info
+
+
 # ---- destination rules (Sec. 3.3 and its ablation), row order and position indices (Sec. 3.4) ------------
 @pytest.mark.parametrize("mode", ["first_passing", "topleft_only", "most_similar"])
 @pytest.mark.parametrize("order", ["raster", "zscan"])
@@ -294,10 +335,10 @@ def test_positions_and_settings_error_paths(lib):
     off = torch.from_numpy(r.offsets).cuda()
     sv = torch.zeros(N, dtype=torch.int32, device="cuda:0")
     with pytest.raises(lib.SttmError) as e:                        # not the buffer the reduce call saw
-        s.sttm_positions(cl, None, off, N, sv)
+        s.sttm_positions(cl, None, None, off, N, sv)
     assert e.value.code == lib.STTM_ERR_STATE
     with pytest.raises(lib.SttmError) as e:
-        s.sttm_positions(None, None, off, N, sv)
+        s.sttm_positions(None, None, None, off, N, sv)
     assert e.value.code == lib.STTM_ERR_NULL
 
 
