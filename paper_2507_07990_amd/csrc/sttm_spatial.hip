@@ -219,53 +219,49 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
 }
 
 // ------------------------------------------------------------------------------------------------
-// pyramid_upper: levels 4..L of one frame from the stored level-3 sums, for one chunk, by one wavefront; a
-// lane owns four channels (the chunk is covered in VEC/4 sweeps). For every node: the sum of its existing
-// children (stored next to the level-3 sums) and the partial dot product of every child with it, in the same
-// per-chunk tables as above. Runs at the head of the finalize kernel.
+// pyramid_upper_node: one node of a level >= 4 of one frame from the stored sums of its children, for one
+// chunk, by one wavefront; a lane owns four channels (the chunk is covered in VEC/4 sweeps). Stores the node's
+// sum next to the level-3 sums and the partial dot product of every child with it in the same per-chunk
+// tables as above. Runs at the head of the finalize kernel, level by level.
 // ------------------------------------------------------------------------------------------------
-__device__ inline void pyramid_upper(const Geo& g, float* part, float* nsum, int chunk, int f, int lane) {
+__device__ inline void pyramid_upper_node(const Geo& g, float* part, float* nsum, int chunk, int f, int lane, int lvl,
+                                          int nd) {
   const int NB = g.NN - g.lvl_base[3];
   float* pd = part + (size_t)(f * g.nC + chunk) * 2 * g.NN + g.NN;
   float* rows = nsum + (size_t)f * NB * g.D;
-  for (int lvl = 4; lvl <= g.L; ++lvl) {
-    const int G = g.P >> lvl;
-    for (int nd = 0; nd < G * G; ++nd) {
-      const int by = nd / G, bx = nd - by * G;
-      if (!node_exists(g, lvl, by, bx)) continue;  // wave-uniform
-      float tot[4] = {0.f, 0.f, 0.f, 0.f};
-      for (int c = lane * 4; c < g.cch; c += 256) {
-        const int ch = chunk * g.cch + c;
-        if (ch >= g.D) continue;
-        float4 a[4];
-        float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int G = g.P >> lvl;
+  const int by = nd / G, bx = nd - by * G;
+  if (!node_exists(g, lvl, by, bx)) return;  // wave-uniform
+  float tot[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int c = lane * 4; c < g.cch; c += 256) {
+    const int ch = chunk * g.cch + c;
+    if (ch >= g.D) continue;
+    float4 a[4];
+    float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
-          a[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (node_exists(g, lvl - 1, cy, cx))
-            a[k] = *reinterpret_cast<const float4*>(rows + (size_t)(node_index(g, lvl - 1, cy, cx) - g.lvl_base[3]) * g.D + ch);
-        }
-        S.x = (a[0].x + a[1].x) + (a[2].x + a[3].x);
-        S.y = (a[0].y + a[1].y) + (a[2].y + a[3].y);
-        S.z = (a[0].z + a[1].z) + (a[2].z + a[3].z);
-        S.w = (a[0].w + a[1].w) + (a[2].w + a[3].w);
-        *reinterpret_cast<float4*>(rows + (size_t)(node_index(g, lvl, by, bx) - g.lvl_base[3]) * g.D + ch) = S;
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-          tot[k] = fmaf(a[k].x, S.x, fmaf(a[k].y, S.y, fmaf(a[k].z, S.z, fmaf(a[k].w, S.w, tot[k]))));
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) tot[j] = wave_sum(tot[j]);
-      if (lane == 0) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
-          if (node_exists(g, lvl - 1, cy, cx)) pd[node_index(g, lvl - 1, cy, cx)] = tot[k];
-        }
-      }
+    for (int k = 0; k < 4; ++k) {
+      const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
+      a[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (node_exists(g, lvl - 1, cy, cx))
+        a[k] = *reinterpret_cast<const float4*>(rows + (size_t)(node_index(g, lvl - 1, cy, cx) - g.lvl_base[3]) * g.D + ch);
     }
-    // the next level reads back, lane by lane, exactly the channels this lane has just stored
+    S.x = (a[0].x + a[1].x) + (a[2].x + a[3].x);
+    S.y = (a[0].y + a[1].y) + (a[2].y + a[3].y);
+    S.z = (a[0].z + a[1].z) + (a[2].z + a[3].z);
+    S.w = (a[0].w + a[1].w) + (a[2].w + a[3].w);
+    *reinterpret_cast<float4*>(rows + (size_t)(node_index(g, lvl, by, bx) - g.lvl_base[3]) * g.D + ch) = S;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      tot[k] = fmaf(a[k].x, S.x, fmaf(a[k].y, S.y, fmaf(a[k].z, S.z, fmaf(a[k].w, S.w, tot[k]))));
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) tot[j] = wave_sum(tot[j]);
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
+      if (node_exists(g, lvl - 1, cy, cx)) pd[node_index(g, lvl - 1, cy, cx)] = tot[k];
+    }
   }
 }
 
@@ -282,12 +278,12 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* n
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_spatial_finalize: one workgroup per frame. First the levels above the 8x8 units (one wavefront per chunk,
-// see pyramid_upper), then it sums the per-chunk partials in chunk order, turns
+// k_spatial_finalize: one workgroup per frame. First the levels above the 8x8 units (see pyramid_upper_node),
+// then it sums the per-chunk partials in chunk order, turns
 // them into sigma(parent, child) (Sec. 3.2: cosine between a level's nodes and their children),
 // m_n = min over existing children, and the split score s_n = max of m along the path from the root.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_spatial_finalize(Geo g, float* part, float* __restrict__ nsum,
+__global__ __launch_bounds__(512) void k_spatial_finalize(Geo g, float* part, float* __restrict__ nsum,
                                                           float* __restrict__ nrm2, float* __restrict__ sim,
                                                           float* __restrict__ m, uint32_t* __restrict__ sel_key,
                                                           uint8_t* __restrict__ sel_w,
@@ -300,10 +296,11 @@ __global__ __launch_bounds__(1024) void k_spatial_finalize(Geo g, float* part, f
   float* s_m = sm + 2 * g.NN;
   const int f = blockIdx.x;
   const size_t fo = (size_t)f * g.NN;
-  if (g.L > 3) {
-    const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    for (int chunk = wave; chunk < g.nC; chunk += nwaves) pyramid_upper(g, part, nsum, chunk, f, threadIdx.x & 63);
-    __syncthreads();  // the dot products written above are read below by other threads of this workgroup
+  for (int lvl = 4; lvl <= g.L; ++lvl) {  // the levels above the 8x8 units: one wavefront per (node, chunk)
+    const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6, side = g.P >> lvl;
+    for (int w = wave; w < side * side * g.nC; w += nwaves)
+      pyramid_upper_node(g, part, nsum, w % g.nC, f, threadIdx.x & 63, lvl, w / g.nC);
+    __syncthreads();  // sums and dot products written above are read by other wavefronts of this workgroup
   }
   for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
     int lvl, by, bx;
@@ -413,7 +410,7 @@ __global__ __launch_bounds__(1024) void k_spatial_finalize(Geo g, float* part, f
 
 void launch_spatial_finalize(const Geo& g, float* part, float* nsum, float* nrm2, float* sim, float* m,
                              uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s) {
-  const int threads = g.NN <= 256 ? 256 : (g.NN <= 512 ? 512 : 1024);  // one node per thread where it fits
+  const int threads = g.NN <= 256 ? 256 : 512;  // one node per thread where it fits; more workgroups per CU beyond
   hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(threads), 3 * g.NN * sizeof(float), s, g, part, nsum, nrm2,
                      sim,
                      m, sel_key, sel_w, sel);
