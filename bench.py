@@ -191,19 +191,24 @@ def main() -> int:
             limiter = threadpool_limits(limits=1)
         except Exception:  # pragma: no cover
             limiter = None
-        nf = min(T, args.cpu_frames, max(2, int(3.2e8 // (H * W * D))))   # bounds the oracle's work to tens of seconds
+        nf = min(T, args.cpu_frames, max(2, int(3.2e8 // (H * W * D))))   # bounds one pass of the oracle
         sample = feats[:1, :nf]
+        reps = 0
         t0 = time.perf_counter()
-        if budget_mode:
-            O.sttm(sample, keep=keep, root_grid=R, mode=args.match, order=args.order)
-        else:
-            O.sttm(sample, tau_s=cfg.tau_s, tau_t=cfg.tau_t, root_grid=R, mode=args.match, order=args.order)
-        cpu_s = time.perf_counter() - t0
+        while True:   # whole passes over the sample until about ten seconds of CPU work have been timed
+            if budget_mode:
+                O.sttm(sample, keep=keep, root_grid=R, mode=args.match, order=args.order)
+            else:
+                O.sttm(sample, tau_s=cfg.tau_s, tau_t=cfg.tau_t, root_grid=R, mode=args.match, order=args.order)
+            reps += 1
+            cpu_s = time.perf_counter() - t0
+            if cpu_s >= 10.0 or reps >= 8:
+                break
         if limiter is not None:
             limiter.restore_original_limits()
-        out["cpu_baseline"] = {"value": nf * H * W / cpu_s / 1e6, "unit": "Mtok/s", "cores": 1, "kind": "oracle",
+        out["cpu_baseline"] = {"value": reps * nf * H * W / cpu_s / 1e6, "unit": "Mtok/s", "cores": 1, "kind": "oracle",
                                "sample": f"video 0, first {nf} of {T} frames of the same workload "
-                                         f"({nf * H * W} tokens, {cpu_s:.1f} s, fp64 numpy, 1 thread)"}
+                                         f"({nf * H * W} tokens), {reps} passes in {cpu_s:.1f} s, fp64 numpy, 1 thread"}
     print(json.dumps(out))
     return 0
 
