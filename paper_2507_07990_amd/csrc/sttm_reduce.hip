@@ -678,52 +678,74 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
   }
 }
 
-// A fixed number of workgroups walks the list of big clusters; each cluster's partial sums are added up in
-// item order (the starting item's own, then the left-hand shares of the items after it), eight in flight.
+// A fixed number of workgroups per chunk walks the list of big clusters. A cluster's partial sums are added up
+// in item order (the starting item's own, then the left-hand shares of the items after it): the run of items is
+// cut into kBigSeg contiguous segments, one wavefront each, eight loads in flight, and the segment sums are
+// added in segment order through LDS -- an order that depends on the list alone.
 constexpr int kBigGrid = 256;
 constexpr int kBigBatch = 8;
+constexpr int kBigSeg = 8;
 
 template <int DT, int ODT>
-__global__ __launch_bounds__(1024) void k_reduce_big_combine(Geo g, GatherArgs a) {
+__global__ __launch_bounds__(64 * kBigSeg) void k_reduce_big_combine(Geo g, GatherArgs a) {
   constexpr int VEC = Row<DT>::VEC;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  __shared__ float segsum[kBigSeg - 1][64][VEC];
+  __shared__ int segmem[kBigSeg];
+  const int seg = threadIdx.x >> 6, lane = threadIdx.x & 63, chunk = blockIdx.y;
+  const int ch0 = chunk * g.cch + lane * VEC;
+  const bool act = ch0 < g.D;
   const int nbig = *a.bigcount;
-  for (int e = blockIdx.x; e < nbig; e += gridDim.x) {
+  for (int e = blockIdx.x; e < nbig; e += gridDim.x) {  // uniform over the workgroup
     const int4 en = a.biglist[e];
     const int k = en.x, it0 = en.y / kItem, it1 = (en.z - 1) / kItem;
-    if (k >= a.capacity) continue;
+    // the partial sums of the cluster: number 0 is the starting item's (slot 1), number j > 0 item it0 + j's (slot 0)
+    const int np = it1 - it0 + 1, per = (np + kBigSeg - 1) / kBigSeg;
+    const int j0 = min(np, seg * per), j1 = min(np, j0 + per);
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
     int members = 0;
-    for (int it = it0 + lane; it <= it1; it += 64) members += a.bigw[it * 2 + (it == it0 ? 1 : 0)];
+    for (int j = j0; j < j1; j += kBigBatch) {
+      float4 r[kBigBatch][VEC / 4];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) members += __shfl_xor(members, o, 64);
-    if (wave == 0 && lane == 0 && a.counts) a.counts[k] = members;
-    for (int chunk = wave; chunk < g.nC; chunk += nw) {
-      const int ch0 = chunk * g.cch + lane * VEC;
-      if (ch0 >= g.D) continue;
-      float acc[VEC];
-      const float* pp = a.bigpart + ((size_t)it0 * 2 + 1) * g.D + ch0;
+      for (int u = 0; u < kBigBatch; ++u) {
+        const int jj = min(j + u, j1 - 1);
+        const float4* q =
+            reinterpret_cast<const float4*>(a.bigpart + ((size_t)(it0 + jj) * 2 + (jj == 0 ? 1 : 0)) * g.D + (act ? ch0 : 0));
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[v] = pp[v];
-      for (int it = it0 + 1; it <= it1; it += kBigBatch) {
-        float4 r[kBigBatch][VEC / 4];
+        for (int v = 0; v < VEC / 4; ++v) r[u][v] = q[v];
+      }
 #pragma unroll
-        for (int u = 0; u < kBigBatch; ++u) {
-          const float4* q = reinterpret_cast<const float4*>(a.bigpart + ((size_t)min(it + u, it1) * 2) * g.D + ch0);
+      for (int u = 0; u < kBigBatch; ++u) {
+        if (j + u >= j1) continue;
 #pragma unroll
-          for (int v = 0; v < VEC / 4; ++v) r[u][v] = q[v];
-        }
-#pragma unroll
-        for (int u = 0; u < kBigBatch; ++u) {
-          if (it + u > it1) continue;
-#pragma unroll
-          for (int v = 0; v < VEC / 4; ++v) {
-            acc[4 * v] += r[u][v].x; acc[4 * v + 1] += r[u][v].y;
-            acc[4 * v + 2] += r[u][v].z; acc[4 * v + 3] += r[u][v].w;
-          }
+        for (int v = 0; v < VEC / 4; ++v) {
+          acc[4 * v] += r[u][v].x; acc[4 * v + 1] += r[u][v].y;
+          acc[4 * v + 2] += r[u][v].z; acc[4 * v + 3] += r[u][v].w;
         }
       }
-      store_mean<DT, ODT>(a.merged, (size_t)k * g.D + ch0, acc, 1.f / (float)members);
     }
+    for (int j = j0 + lane; j < j1; j += 64) members += a.bigw[(it0 + j) * 2 + (j == 0 ? 1 : 0)];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) members += __shfl_xor(members, o, 64);
+    if (seg > 0) {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) segsum[seg - 1][lane][v] = acc[v];
+    }
+    if (lane == 0) segmem[seg] = members;
+    __syncthreads();
+    if (seg == 0 && k < a.capacity) {
+      int total = 0;
+#pragma unroll
+      for (int u = 0; u < kBigSeg; ++u) total += segmem[u];
+#pragma unroll
+      for (int u = 1; u < kBigSeg; ++u)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[v] += segsum[u - 1][lane][v];
+      if (chunk == 0 && lane == 0 && a.counts) a.counts[k] = total;
+      if (act) store_mean<DT, ODT>(a.merged, (size_t)k * g.D + ch0, acc, 1.f / (float)total);
+    }
+    __syncthreads();
   }
 }
 
@@ -959,8 +981,7 @@ void launch_reduce_big(const Geo& g, const void* feats, const float* nsum, const
                        const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
                        const ReduceBuffers& rb, bool zscan, hipStream_t s) {
   const int nmax = (int)reduce_biglist_entries(g);
-  const int nw = g.nC < 16 ? g.nC : 16;
-  dim3 grid(nmax < kBigGrid ? nmax : kBigGrid), block(64 * nw);
+  dim3 grid(nmax < kBigGrid ? nmax : kBigGrid, g.nC), block(64 * kBigSeg);
   const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb, zscan);
   STTM_DISPATCH_IO(k_reduce_big_combine, g.dtype, out_dtype, grid, block, s, g, a);
 }

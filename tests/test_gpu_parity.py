@@ -55,6 +55,8 @@ def test_config0_tiny_fixed_thresholds(lib):
     (21, 2, 3, 14, 14, 1032, "f16", 0.8, 0.85, 4),    # half precision, three chunks, 4x4 roots
     (22, 1, 3, 18, 24, 8192, "bf16", 0.9, 0.8, 1),    # 16 chunks (the widest row one workgroup covers), non-square
     (23, 1, 2, 7, 30, 8200, "f32", 0.8, 0.8, 1),      # fp32, 33 chunks: more chunks than wavefronts per workgroup
+    (27, 1, 300, 3, 3, 72, "bf16", 1.0, -2.0, 1),     # nine chains of 300 cells: clusters summed item by item
+    (28, 2, 40, 8, 8, 264, "f32", 0.95, 0.2, 1),      # long chains of mixed nodes
 ])
 def test_small_shapes_fixed_thresholds(lib, seed, B, T, H, W, D, dtype, tau_s, tau_t, R):
     cfg = _variant(seed, B, T, H, W, D, dtype)
