@@ -48,6 +48,10 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="index into the workload table (default: long video)")
     ap.add_argument("--keep", type=float, default=None, help="token budget (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--event-period", type=int, default=4,
+                    help="bracket the feature kernels of every n-th timed step with HIP events (default 4)")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket the feature kernels with HIP events (the roofline block is then empty)")
     ap.add_argument("--cpu-frames", type=int, default=512, help="frames of the workload the oracle is timed on")
     ap.add_argument("--match", choices=["first_passing", "topleft_only", "most_similar"], default="first_passing",
                     help="destination rule of the temporal stage (default: the paper's top-left-most passing one)")
@@ -123,7 +127,8 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    s.sttm_profile_enable(True)
+    # every 4th step's feature kernels are bracketed by events (a pair costs about 3 us of stream time)
+    s.sttm_profile_enable(0 if args.no_kernel_events else args.event_period)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()

@@ -205,10 +205,12 @@ typedef enum {
   STTM_KERNEL_COUNT = 3
 } sttm_kernel;
 
-/* Benchmark aid: when on, every launch of the three feature kernels is bracketed by HIP events on the context's
- * stream (turning it on or off resets the record). sttm_profile_read synchronises the stream and returns the summed
- * device time in milliseconds and the number of launches recorded for one kernel. */
-int sttm_profile_enable(sttm_ctx* ctx, int on);
+/* Benchmark aid: with every > 0, every `every`-th launch of each of the three feature kernels (the first one
+ * included) is bracketed by HIP events on the context's stream; 0 turns it off; either call resets the record.
+ * An event pair costs a few microseconds of stream time, hence the option to sample. sttm_profile_read
+ * synchronises the stream and returns the summed device time in milliseconds and the number of launches
+ * recorded for one kernel. */
+int sttm_profile_enable(sttm_ctx* ctx, int every);
 int sttm_profile_read(sttm_ctx* ctx, int kernel, double* total_ms, int64_t* launches);
 
 #ifdef __cplusplus

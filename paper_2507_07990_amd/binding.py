@@ -191,8 +191,9 @@ class Sttm:
     def sttm_export(self, table, dst):
         self._check(_lib.sttm_export(self._h, table, _ptr(dst), dst.numel() * dst.element_size()))
 
-    def sttm_profile_enable(self, on: bool):
-        self._check(_lib.sttm_profile_enable(self._h, 1 if on else 0))
+    def sttm_profile_enable(self, every):
+        """every: False / 0 = off, True / 1 = every launch, n = every n-th launch of each feature kernel."""
+        self._check(_lib.sttm_profile_enable(self._h, int(every)))
 
     def sttm_profile_read(self, kernel: int):
         ms, n = C.c_double(0.0), C.c_int64(0)

@@ -123,7 +123,8 @@ struct sttm_ctx {
   bool sel_s_dirty = false, sel_t_dirty = false;                // searched since the statistics pass
   std::string err;
   // optional per-kernel timing of the three feature passes (HIP events on the context's stream)
-  bool profiling = false;
+  int profiling = 0;  // 0 = off, n = every n-th launch of each feature kernel is bracketed by events
+  size_t prof_seen[STTM_KERNEL_COUNT] = {0, 0, 0};
   struct EvPair { hipEvent_t a, b; };
   std::vector<EvPair> ev[STTM_KERNEL_COUNT];
   size_t ev_used[STTM_KERNEL_COUNT] = {0, 0, 0};
@@ -192,7 +193,7 @@ struct Timed {
   int kid;
   sttm_ctx::EvPair* p = nullptr;
   Timed(sttm_ctx* c_, int kid_) : c(c_), kid(kid_) {
-    if (!c->profiling) return;
+    if (!c->profiling || (c->prof_seen[kid]++ % (size_t)c->profiling) != 0) return;
     if (c->ev_used[kid] == c->ev[kid].size()) {
       sttm_ctx::EvPair n;
       if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
@@ -594,8 +595,9 @@ int sttm_export(sttm_ctx* ctx, int table, void* dst_dev, size_t bytes) {
 
 int sttm_profile_enable(sttm_ctx* ctx, int on) {
   if (!ctx) return STTM_ERR_NULL;
-  ctx->profiling = on != 0;
+  ctx->profiling = on < 0 ? 0 : on;
   for (auto& u : ctx->ev_used) u = 0;
+  for (auto& u : ctx->prof_seen) u = 0;
   return STTM_OK;
 }
 

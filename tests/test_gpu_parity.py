@@ -282,6 +282,31 @@ def test_identity_at_every_size_class_of_the_list_sort(lib, B, T, H, W):
     assert torch.equal(merged, x)
 
 
+def test_longest_video_the_library_accepts_collapses_to_one_token_when_static(lib):
+    """65535 frames (the most a context takes) of one constant token: every frame merges into its predecessor, so
+    one cluster remains whose root chain is as long as chains get (pointer jumping needs all its rounds)."""
+    import torch
+    B, T, H, W, D = 1, 65535, 1, 1, 8
+    x = torch.full((T, D), 0.75, device="cuda:0")
+    s = lib.Sttm(0)
+    s.ensure_workspace(B, T, H, W, D, lib.STTM_F32, 1)
+    nm = torch.empty(T, dtype=torch.int32, device="cuda:0")
+    nl = torch.empty(T, dtype=torch.uint8, device="cuda:0")
+    cl = torch.empty(T, dtype=torch.int32, device="cuda:0")
+    s.sttm_spatial_quadtree(x, lib.STTM_F32, B, T, H, W, D, 1, [0.5], nm, nl)
+    s.sttm_temporal_merge(x, nm, nl, [0.5], cl)
+    assert int(cl.max().item()) == 0
+    merged = torch.zeros(4, D, device="cuda:0")
+    counts = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    off = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    K = s.sttm_reduce(x, cl, nm, nl, lib.STTM_F32, 4, merged, counts, None, off)
+    assert K == 1 and int(counts[0].item()) == T
+    np.testing.assert_allclose(merged[0].cpu().numpy(), 0.75, rtol=0, atol=1e-4)
+    with pytest.raises(lib.SttmError) as e:                         # one frame more is refused
+        s.sttm_spatial_stats(x, lib.STTM_F32, 1, 65536, 1, 1, D, 1)
+    assert e.value.code == lib.STTM_ERR_SHAPE
+
+
 def test_positions_without_the_partition(lib):
     cfg = wl.Workload("alt", 95, 2, 5, 8, 8, 16, "f32", 2, 0.05, 0.9)
     feats = wl.generate_alternating(cfg, 0.7)
