@@ -65,7 +65,7 @@ def main() -> int:
                          "FETCH_SIZE / WRITE_SIZE by what they read for it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the path's sharding is described in DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU only (how the path would shard is described in the design notes); "
               "rerun with --gpus 1", file=sys.stderr)
         return 2
 

@@ -4,15 +4,6 @@
 
 namespace sttm {
 
-__device__ inline void morton_decode(int z, int& dy, int& dx) {
-  dx = 0; dy = 0;
-#pragma unroll
-  for (int b = 0; b < kMaxLevels; ++b) {
-    dx |= ((z >> (2 * b)) & 1) << b;
-    dy |= ((z >> (2 * b + 1)) & 1) << b;
-  }
-}
-
 // Sum of the valid cells of the block [y0, y0+s) x [x0, x0+s) of one frame, for this lane's channels.
 template <int DT>
 __device__ inline void block_sum(const typename Row<DT>::Elem* fb, int D, int H, int W, int y0, int x0, int s,
@@ -58,8 +49,8 @@ __device__ inline void block_sum(const typename Row<DT>::Elem* fb, int D, int H,
 //  * J <= 1 ("fast"): aligned 2x2 regions in which both frames' nodes are single cells or the 2x2 block.
 //    A wavefront loads the 4+4 cells of two regions at once (16 rows in flight) and emits up to four dot
 //    products per region.
-//  * J == 2 ("mid"): a wavefront sums the 4x4 block in the frame where it is one node, then walks the
-//    other frame's nodes inside it in Morton order, summing each and emitting the dot product.
+//  * J == 2 ("mid"): a wavefront sums the 4x4 block in the frame where it is one node, then dots every cell
+//    of the other frame's block with that sum; a finer node's dot product is the sum over its cells.
 //  * J >= 3 ("big"): the coarse sum is not recomputed: the spatial pass left the per-channel sums of all
 //    nodes at levels >= 3 in `nsum`; the workgroup stages the rows it needs in LDS. Pairs whose finer
 //    node is a single cell are handled 8 rows at a time, the others one by one (finer nodes at levels
@@ -300,33 +291,78 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
     if (lane == 0) out[q] = d;
   }
 
-  // ---- mid join blocks (4x4)
+  // ---- mid join blocks (4x4): the block's sum in the frame where it is one node, then every cell of the other
+  //      frame dotted with it; the dot product of a finer node is the sum over its cells (eight rows in flight)
   const int nm = min(nmid, 64);
   for (int ti = wave; ti < nm; ti += 4) {
     const int c = mid[ti];
     const int a = lvl_t[c], bb = lvl_p[c];
     const bool coarse_is_t = a >= bb;
     const int y0 = c / W, x0 = c - y0 * W;
-    float SA[VEC];
-    block_sum<DT>(coarse_is_t ? ft : fp, g.D, H, W, y0, x0, 4, act, SA);
+    const typename R::Elem* coarse = coarse_is_t ? ft : fp;
     const typename R::Elem* fine = coarse_is_t ? fp : ft;
     const uint8_t* fine_lvl = coarse_is_t ? lvl_p : lvl_t;
-    int z = 0;
-    while (z < 16) {
-      int dy, dx;
-      morton_decode(z, dy, dx);
-      const int y = y0 + dy, x = x0 + dx;
-      if (y >= H || x >= W) { ++z; continue; }
-      const int cb = y * W + x;
-      const int lf = min((int)fine_lvl[cb], 2);
-      float SB[VEC];
-      block_sum<DT>(fine, g.D, H, W, y, x, 1 << lf, act, SB);
-      float d = 0.f;
+    float SA[VEC];
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) d = fmaf(SA[v], SB[v], d);
-      d = wave_sum(d);
-      if (lane == 0) out[cb] = d;
-      z += 1 << (2 * lf);
+    for (int v = 0; v < VEC; ++v) SA[v] = 0.f;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      typename R::Raw r[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int y = y0 + half * 2 + (j >> 2), x = x0 + (j & 3);
+        r[j] = R::zero();
+        if (y < H && x < W && act) r[j] = *reinterpret_cast<const typename R::Raw*>(coarse + (size_t)(y * W + x) * g.D);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float t[VEC];
+        R::unpack(r[j], t);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) SA[v] += t[v];
+      }
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      typename R::Raw r[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int y = y0 + half * 2 + (j >> 2), x = x0 + (j & 3);
+        r[j] = R::zero();
+        if (y < H && x < W && act) r[j] = *reinterpret_cast<const typename R::Raw*>(fine + (size_t)(y * W + x) * g.D);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float t[VEC];
+        R::unpack(r[j], t);
+        float d = 0.f;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) d = fmaf(t[v], SA[v], d);
+        tb[(half * 8 + j) * 68 + lane] = d;
+      }
+    }
+    wave_lds_fence();
+    float cd = 0.f;  // lane i < 16: the dot product of cell (i / 4, i % 4) of the block with the coarse sum
+    if (lane < 16) {
+      const float4* row = reinterpret_cast<const float4*>(tb + lane * 68);
+#pragma unroll
+      for (int jj = 0; jj < 16; ++jj) {
+        const float4 q = row[jj];
+        cd += (q.x + q.y) + (q.z + q.w);
+      }
+    }
+    wave_lds_fence();
+    const float s4 = (cd + __shfl_down(cd, 1, 64)) + (__shfl_down(cd, 4, 64) + __shfl_down(cd, 5, 64));  // 2x2 at lane
+    float s16 = s4;  // lanes 0, 2, 8, 10 hold the four 2x2 sums
+    s16 = (s16 + __shfl_down(s16, 2, 64)) + (__shfl_down(s16, 8, 64) + __shfl_down(s16, 10, 64));
+    if (lane < 16) {
+      const int dy = lane >> 2, dx = lane & 3, y = y0 + dy, x = x0 + dx;
+      if (y < H && x < W) {
+        const int cb = y * W + x, lf = min((int)fine_lvl[cb], 2);
+        if (lf == 0) out[cb] = cd;
+        else if (lf == 1 && !(dy & 1) && !(dx & 1)) out[cb] = s4;
+        else if (lf == 2 && lane == 0) out[cb] = s16;
+      }
     }
   }
 }

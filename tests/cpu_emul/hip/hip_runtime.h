@@ -92,6 +92,10 @@ template <class T> inline T __shfl_up(T v, int delta, int = 64) {
   const int lane = hip_emul::t_threadIdx.x & 63;
   return __shfl(v, lane >= delta ? lane - delta : lane);
 }
+template <class T> inline T __shfl_down(T v, int delta, int = 64) {
+  const int lane = hip_emul::t_threadIdx.x & 63;
+  return __shfl(v, lane + delta < 64 ? lane + delta : lane);
+}
 inline unsigned long long __ballot(int pred) {
   const int lane = hip_emul::t_threadIdx.x & 63;
   hip_emul::t_wave->slot[lane] = pred ? 1 : 0;

@@ -43,6 +43,7 @@ def _variant(seed, B, T, H, W, D, dtype):
     (92, 1, 2, 9, 9, 16, "bf16", dict(tau_s=0.2, tau_t=0.2)),   # nodes that the reduce takes from stored sums
     (93, 1, 3, 8, 8, 24, "f16", dict(tau_s=0.7, tau_t=0.7)),    # half-precision input and output
     (94, 1, 2, 17, 18, 16, "f32", dict(tau_s=0.3, tau_t=0.3)),  # P = 32: two pyramid levels above the 8x8 units
+    (97, 2, 3, 14, 14, 24, "bf16", dict(tau_s=0.8, tau_t=0.7, root_grid=4)),  # 4x4 roots: 4x4 join blocks everywhere
     (96, 1, 150, 2, 2, 8, "f32", dict(tau_s=1.0, tau_t=-2.0)),  # four chains of 150 cells: clusters summed item by item
 ])
 def test_emulated_kernels_match_the_oracle(emul, seed, B, T, H, W, D, dtype, kw):
