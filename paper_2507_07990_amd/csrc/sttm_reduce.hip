@@ -582,19 +582,32 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  // Lane j < kItem describes list position p0 + j, the next kTail lanes the positions after the item (the start of
+  // a cluster that runs past it). The list entries are requested together with the list's length: entries at or
+  // beyond the end are stale and are not used.
+  const int p0 = blockIdx.x * kItem, pl = p0 + lane;
+  int cell_l = 0, rank_l = 0;
+  if (lane < kItem + kTail && pl < g.N) {
+    cell_l = a.order[pl];
+    rank_l = a.orow[pl];  // clusters are listed in ascending id; the output row may differ
+  }
   const int M = a.kdev[1];
-  const int p0 = blockIdx.x * kItem, p1 = min(p0 + kItem, M);
+  const int p1 = min(p0 + kItem, M);
   if (p0 >= M) return;
-  // lane j < kItem describes list position p0 + j
   Slot sv = {0, 0, 0};
   int row_v = -1, beg_v = 0, end_v = 0;
-  if (lane < kItem && p0 + lane < p1) {
-    sv = describe<DT>(g, a.node_map, a.lvl, a.order[p0 + lane]);
-    const int rank = a.orow[p0 + lane];  // clusters are listed in ascending id; the output row may differ
-    beg_v = a.seg[rank];
-    end_v = a.seg[rank + 1];
-    row_v = a.zpos ? a.zpos[rank] : rank;
+  if (lane < kItem + kTail && pl < M) {
+    sv = describe<DT>(g, a.node_map, a.lvl, cell_l);
+    if (lane < kItem) {
+      beg_v = a.seg[rank_l];
+      end_v = a.seg[rank_l + 1];
+      row_v = a.zpos ? a.zpos[rank_l] : rank_l;
+    }
   }
+  Slot tnext;  // lanes 0..kTail-1: the positions p0 + kItem ... described above
+  tnext.kind = __shfl(sv.kind, kItem + (lane & (kTail - 1)), 64);
+  tnext.idx = __shfl(sv.idx, kItem + (lane & (kTail - 1)), 64);
+  tnext.weight = __shfl(sv.weight, kItem + (lane & (kTail - 1)), 64);
   for (int chunk = wave; chunk < g.nC; chunk += nw) {
     const int ch0 = chunk * g.cch + lane * VEC;
     const bool act = ch0 < g.D;
@@ -653,7 +666,8 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
       // the last cluster runs past the item: finish it from the list, kTail loads in flight
       for (int q = p1; q < open_end; q += kTail) {
         Slot ts = {0, 0, 0};
-        if (lane < kTail && q + lane < open_end) ts = describe<DT>(g, a.node_map, a.lvl, a.order[q + lane]);
+        if (q == p1) ts = tnext;  // (an open cluster means the item is full: p1 == p0 + kItem)
+        else if (lane < kTail && q + lane < open_end) ts = describe<DT>(g, a.node_map, a.lvl, a.order[q + lane]);
         typename R::Raw tr[kTail];
 #pragma unroll
         for (int u = 0; u < kTail; ++u) {
