@@ -15,7 +15,7 @@ constexpr int kSortTile = kSortThreads * kSortPer;  // 2048 elements per workgro
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxDigitBits = 11;
 constexpr int kItem = 16;  // list positions per gather item
-constexpr int kBig = 64;   // clusters with more list slots than this are summed window by window
+constexpr int kBig = 64;   // clusters with more list slots than this are summed item by item, then combined
 constexpr int kTail = 8;
 constexpr int kMaxDigits = 1 << kMaxDigitBits;
 // How a scatter workgroup gets its start offsets from hist[tile][digit]: up to kDirectTiles tiles it adds up all

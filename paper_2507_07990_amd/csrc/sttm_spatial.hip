@@ -22,7 +22,7 @@ namespace sttm {
 // which the finalize kernel adds up.)
 // Output: part[f][chunk][0][cell node] = partial squared norm over this chunk's channels,
 //         part[f][chunk][1][node]      = partial dot product of the node's sum with its parent's sum
-//         (levels 0..2 here; level 3 and above by k_pyramid_upper when the pyramid is taller than a unit),
+//         (levels 0..2 here; level 3 and above by the finalize kernel when the pyramid is taller than a unit),
 //         nsum[f][node - first level-3 node][D] = the per-channel sums of the level-3 nodes (fp32), which
 //         the later stages read instead of re-adding up to 64 token rows.
 // ------------------------------------------------------------------------------------------------
