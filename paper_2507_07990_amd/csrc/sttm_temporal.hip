@@ -549,15 +549,19 @@ void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, co
 // Common root by pointer jumping (Sec. 3.3, "union-find in a vectorized form"): every edge points one
 // frame back, so a chain has at most T-1 edges; each launch multiplies the reach by kHops.
 // ------------------------------------------------------------------------------------------------
-// One launch follows kHops edges of the previous array, i.e. multiplies the reach by kHops.
-constexpr int kHops = 8;
+// One launch follows up to kHops edges of the previous array, i.e. multiplies the reach by kHops; a walk stops at a
+// root (an entry that points to itself), so short chains cost a load or two.
+constexpr int kHops = 23;
 __global__ __launch_bounds__(256) void k_root_jump(int n, const int32_t* __restrict__ src,
                                                    int32_t* __restrict__ dst) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   int p = i;
-#pragma unroll
-  for (int h = 0; h < kHops; ++h) p = src[p];
+  for (int h = 0; h < kHops; ++h) {
+    const int q = src[p];
+    if (q == p) break;
+    p = q;
+  }
   dst[i] = p;
 }
 
@@ -568,7 +572,11 @@ __global__ __launch_bounds__(256) void k_root_jump_cells(int n, int hops, const 
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   int p = node_map[i];
-  for (int h = 0; h < hops; ++h) p = src[p];
+  for (int h = 0; h < hops; ++h) {
+    const int q = src[p];
+    if (q == p) break;
+    p = q;
+  }
   cluster_ids[i] = p;
 }
 
