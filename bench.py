@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="index into the workload table (default: long video)")
     ap.add_argument("--keep", type=float, default=None, help="token budget (default: the config's first)")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="distinct device copies of the input the steps rotate over, so that no step finds its input "
+                         "in a cache because the step before read the same buffer (default: enough for 512 MB, 2..8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-period", type=int, default=4,
                     help="bracket the feature kernels of every n-th timed step with HIP events (default 4)")
@@ -91,6 +94,11 @@ def main() -> int:
     else:
         x = torch.from_numpy(feats).to(dev)
 
+    # consecutive steps work on different buffers holding the same video
+    copies = args.copies if args.copies > 0 else max(2, min(8, -(-(512 << 20) // (N * D * esz))))
+    xs = [x] + [x.clone() for _ in range(copies - 1)]
+    step_no = [0]
+
     s = lib.Sttm(0)
     s.sttm_set_match_mode({"first_passing": 0, "topleft_only": 1, "most_similar": 2}[args.match])
     s.sttm_set_output_order({"raster": 0, "zscan": 1}[args.order])
@@ -109,6 +117,8 @@ def main() -> int:
         pos_rt = torch.empty(N, 4, dtype=torch.int32, device=dev)
 
     def step():
+        x = xs[step_no[0] % copies]
+        step_no[0] += 1
         if budget_mode:
             s.sttm_spatial_stats(x, dt, B, T, H, W, D, R)
             s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, keep, want_tau=False)
@@ -178,7 +188,7 @@ def main() -> int:
                                + (f", match={args.match}" if args.match != "first_passing" else "")
                                + (f", order={args.order}" if args.order != "raster" else "")
                                + (", with position indices" if args.positions else ""),
-                   "tokens": N, "kept_tokens": K, "kept_fraction": rho, "generate_s": gen_s},
+                   "tokens": N, "kept_tokens": K, "kept_fraction": rho, "generate_s": gen_s, "input_copies": copies},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": traffic.get(dom),
                      "alg_bytes_per_launch": kernels[dom]["alg_bytes"], "kernels": kernels},

@@ -97,6 +97,32 @@ template <> struct Row<2> {
   }
 };
 
+// 16-byte accesses for data that is touched once (the gather's rows and its output): marked non-temporal so that
+// they do not displace what later kernels want to find in the caches.
+#ifndef STTM_HOST_EMULATION
+typedef unsigned int sttm_u32x4 __attribute__((ext_vector_type(4)));
+typedef float sttm_f32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 load_once(const uint4* p) {
+  const sttm_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const sttm_u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ inline float4 load_once(const float4* p) {
+  const sttm_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const sttm_f32x4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ inline void store_once(uint4* p, const uint4& v) {
+  sttm_u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<sttm_u32x4*>(p));
+}
+__device__ inline void store_once(float4* p, const float4& v) {
+  sttm_f32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<sttm_f32x4*>(p));
+}
+#else
+template <class T> inline T load_once(const T* p) { return *p; }
+template <class T> inline void store_once(T* p, const T& v) { *p = v; }
+#endif
+
 __device__ inline uint32_t f32_to_f16_rne(float f) { return (uint32_t)__half_as_ushort(__float2half_rn(f)); }
 
 __device__ inline uint32_t f32_to_bf16_rne(float f) {

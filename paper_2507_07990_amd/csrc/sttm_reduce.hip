@@ -501,9 +501,9 @@ template <int DT>
 __device__ inline typename Row<DT>::Raw load_slot(const void* feats, const float* nsum, int D, int ch0, int kind,
                                                   int idx) {
   typedef Row<DT> R;
-  if (kind == 0)
-    return *reinterpret_cast<const typename R::Raw*>(reinterpret_cast<const typename R::Elem*>(feats) +
-                                                     (size_t)idx * D + ch0);
+  if (kind == 0)  // a feature row: this is its last use
+    return load_once(reinterpret_cast<const typename R::Raw*>(reinterpret_cast<const typename R::Elem*>(feats) +
+                                                              (size_t)idx * D + ch0));
   return *reinterpret_cast<const typename R::Raw*>(nsum + (size_t)idx * D + ch0 + (kind - 1) * 4);
 }
 
@@ -536,8 +536,8 @@ __device__ inline void store_mean(void* merged_v, size_t elem_off, const float (
     float* o = reinterpret_cast<float*>(merged_v) + elem_off;
 #pragma unroll
     for (int v = 0; v < VEC; v += 4)
-      *reinterpret_cast<float4*>(o + v) =
-          make_float4(acc[v] * inv, acc[v + 1] * inv, acc[v + 2] * inv, acc[v + 3] * inv);
+      store_once(reinterpret_cast<float4*>(o + v),
+                 make_float4(acc[v] * inv, acc[v + 1] * inv, acc[v + 2] * inv, acc[v + 3] * inv));
   } else {
     uint16_t* o = reinterpret_cast<uint16_t*>(merged_v) + elem_off;
     uint32_t w[VEC / 2];
@@ -546,7 +546,7 @@ __device__ inline void store_mean(void* merged_v, size_t elem_off, const float (
       w[v / 2] = ODT == 1 ? (f32_to_bf16_rne(acc[v] * inv) | (f32_to_bf16_rne(acc[v + 1] * inv) << 16))
                           : (f32_to_f16_rne(acc[v] * inv) | (f32_to_f16_rne(acc[v + 1] * inv) << 16));
     if (VEC == 8)
-      *reinterpret_cast<uint4*>(o) = make_uint4(w[0], w[1], w[2 % (VEC / 2)], w[3 % (VEC / 2)]);
+      store_once(reinterpret_cast<uint4*>(o), make_uint4(w[0], w[1], w[2 % (VEC / 2)], w[3 % (VEC / 2)]));
     else
       *reinterpret_cast<uint2*>(o) = make_uint2(w[0], w[1]);
   }
