@@ -112,6 +112,7 @@ struct sttm_ctx {
   Geo g{};
   Layout lay{};
   bool have_spatial = false, have_tau_s = false, have_temporal = false, have_tau_t = false;
+  bool tau_s_pending = false, tau_t_pending = false;  // the budget search left its last digit to the consumer kernel
   int match_mode = STTM_MATCH_FIRST_PASSING, order = STTM_ORDER_RASTER;
   const int32_t* cluster_ids_reduced = nullptr;  // cluster ids of the last reduce call (NULL: none since the shape was bound)
   bool reduced_zscan = false;
@@ -170,6 +171,7 @@ int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int ro
   c->lay = l;
   c->bound = true;
   c->have_spatial = c->have_tau_s = c->have_temporal = c->have_tau_t = false;
+  c->tau_s_pending = c->tau_t_pending = false;
   c->cluster_ids_reduced = nullptr;
   if (!same) c->target_s_on_device = c->target_t_on_device = false;  // the layout moved: upload targets again
   return STTM_OK;
@@ -359,6 +361,7 @@ int sttm_spatial_quadtree(sttm_ctx* ctx, const void* feats_dev, int dtype, int B
     rc = upload_tau(ctx, tau_s_host, at<float>(ctx, ctx->lay.tau_s), &ctx->h_tau_s);
     if (rc) return rc;
     ctx->have_tau_s = true;
+    ctx->tau_s_pending = false;
     rc = run_spatial_stats(ctx, feats_dev);
     if (rc) return rc;
   } else {
@@ -369,8 +372,10 @@ int sttm_spatial_quadtree(sttm_ctx* ctx, const void* feats_dev, int dtype, int B
     if (!ctx->have_tau_s)
       return fail(ctx, STTM_ERR_STATE, "no spatial threshold chosen (call sttm_budget_threshold first)");
   }
-  launch_spatial_decide(ctx->g, at<float>(ctx, ctx->lay.m), at<float>(ctx, ctx->lay.tau_s), node_map_dev,
-                        node_level_dev, ctx->stream);
+  launch_spatial_decide(ctx->g, at<float>(ctx, ctx->lay.m), at<float>(ctx, ctx->lay.tau_s),
+                        ctx->tau_s_pending ? at<SelState>(ctx, ctx->lay.sel_s) : nullptr, node_map_dev, node_level_dev,
+                        ctx->stream);
+  ctx->tau_s_pending = false;  // the kernel has left the threshold in the workspace
   return after_launch(ctx);
 }
 
@@ -408,6 +413,7 @@ int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* nod
     rc = upload_tau(ctx, tau_t_host, at<float>(ctx, ctx->lay.tau_t), &ctx->h_tau_t);
     if (rc) return rc;
     ctx->have_tau_t = true;
+    ctx->tau_t_pending = false;
     rc = run_temporal_stats(ctx, feats_dev, node_map_dev, node_level_dev);
     if (rc) return rc;
   } else {
@@ -417,8 +423,10 @@ int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* nod
       return fail(ctx, STTM_ERR_STATE, "no temporal threshold chosen (call sttm_budget_threshold first)");
   }
   launch_temporal_parent(ctx->g, ctx->match_mode, node_map_dev, node_level_dev, at<float>(ctx, ctx->lay.sig),
-                         at<float>(ctx, ctx->lay.tau_t), at<int32_t>(ctx, ctx->lay.parent),
-                         at<int32_t>(ctx, ctx->lay.ptr_a), ctx->stream);
+                         at<float>(ctx, ctx->lay.tau_t),
+                         ctx->tau_t_pending ? at<SelState>(ctx, ctx->lay.sel_t) : nullptr,
+                         at<int32_t>(ctx, ctx->lay.parent), at<int32_t>(ctx, ctx->lay.ptr_a), ctx->stream);
+  ctx->tau_t_pending = false;
   launch_roots(ctx->g, at<int32_t>(ctx, ctx->lay.ptr_a), at<int32_t>(ctx, ctx->lay.ptr_b), node_map_dev,
                cluster_ids_dev, ctx->stream);
   return after_launch(ctx);
@@ -456,14 +464,19 @@ int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_ho
     on_device = true;
   }
   float* tau_dev = at<float>(ctx, spatial ? ctx->lay.tau_s : ctx->lay.tau_t);
+  // When the caller does not ask for the value, the last digit of the search is resolved by the kernel that uses the
+  // threshold (one launch less); otherwise by a launch of its own.
+  float* tau_now = tau_out_host ? tau_dev : nullptr;
   if (spatial) {
     launch_select_spatial(g, at<uint32_t>(ctx, ctx->lay.sel_key_s), at<uint8_t>(ctx, ctx->lay.sel_w_s),
-                          target_dev, at<SelState>(ctx, ctx->lay.sel_s), ctx->sel_s_dirty, tau_dev, ctx->stream);
+                          target_dev, at<SelState>(ctx, ctx->lay.sel_s), ctx->sel_s_dirty, tau_now, ctx->stream);
     ctx->sel_s_dirty = true;
+    ctx->tau_s_pending = tau_now == nullptr;
   } else {
     launch_select_temporal(g, ctx->node_map_temporal, at<uint32_t>(ctx, ctx->lay.sel_key_t), target_dev,
-                           at<SelState>(ctx, ctx->lay.sel_t), ctx->sel_t_dirty, tau_dev, ctx->stream);
+                           at<SelState>(ctx, ctx->lay.sel_t), ctx->sel_t_dirty, tau_now, ctx->stream);
     ctx->sel_t_dirty = true;
+    ctx->tau_t_pending = tau_now == nullptr;
   }
   rc = after_launch(ctx);
   if (rc) return rc;

@@ -216,6 +216,94 @@ __device__ inline void sel_flush_level0(SelState* st, const unsigned* lds_hist) 
     if (lds_hist[j]) atomicAdd(&dst[j], lds_hist[j]);
 }
 
+constexpr int kSelThreads = 256;
+
+// Workgroup-wide (kSelThreads threads): the first bin of `hist` at which acc + running weight exceeds `budget`.
+// Returns false when the whole histogram fits. All threads get the same answer.
+// *below = largest non-empty bin before the found one, or -1.
+// The histogram is the sum of COPIES arrays of kSelBins counters.
+template <int COPIES>
+__device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long long acc,
+                                unsigned long long budget, unsigned* digit, unsigned long long* acc_out,
+                                int* below) {
+  __shared__ unsigned long long wsum[kSelThreads / 64];
+  __shared__ unsigned s_digit;
+  __shared__ unsigned long long s_acc;
+  __shared__ int s_found, s_below;
+  constexpr int PER = kSelBins / kSelThreads;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned h[PER];
+  unsigned long long tot = 0;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) h[j] = 0;
+#pragma unroll
+  for (int c = 0; c < COPIES; ++c)  // all loads at once
+#pragma unroll
+    for (int j = 0; j < PER; ++j) h[j] += hist[c * kSelBins + tid * PER + j];
+#pragma unroll
+  for (int j = 0; j < PER; ++j) tot += h[j];
+  unsigned long long inc = tot;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  if (tid == 0) { s_found = 0; s_below = -1; }
+  if (lane == 63) wsum[wave] = inc;
+  __syncthreads();
+  unsigned long long ex = acc + inc - tot;
+  for (int w = 0; w < wave; ++w) ex += wsum[w];
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    if (ex <= budget && ex + h[j] > budget) {
+      s_found = 1;
+      s_digit = (unsigned)(tid * PER + j);
+      s_acc = ex;
+    }
+    ex += h[j];
+  }
+  __syncthreads();
+  const bool found = s_found != 0;
+  if (found && below) {
+    int mine = -1;  // largest non-empty bin below the found one: per thread, per wavefront, then one LDS atomic each
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+      if (h[j] && tid * PER + j < (int)s_digit) mine = tid * PER + j;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mine = max(mine, __shfl_xor(mine, o, 64));
+    if (lane == 0 && mine >= 0) atomicMax(&s_below, mine);
+    __syncthreads();
+    *below = s_below;
+  }
+  *digit = s_digit;
+  *acc_out = s_acc;
+  __syncthreads();
+  return found;
+}
+
+// Last digit of a budget search, by a workgroup of kSelThreads threads: tau = midpoint between the searched key
+// and the largest key below it. All threads get the value.
+__device__ inline float sel_last_digit(const SelState* __restrict__ st) {
+  const SelFound fd = st->found[1];
+  float t = 1.f;
+  if (fd.rc == 2) {
+    t = -2.f;
+  } else if (fd.rc == 0) {  // uniform over the workgroup
+    unsigned d2;
+    unsigned long long a2;
+    int below;
+    if (sel_pick<1>(st->hist[1], fd.acc, fd.budget, &d2, &a2, &below)) {
+      const unsigned over = (fd.prefix << 10) | d2;
+      const unsigned lo_key = below >= 0 ? ((fd.prefix << 10) | (unsigned)below) : st->lo_out;
+      const float hi = key_float(over);
+      const float lof = lo_key ? key_float(lo_key) : -2.f;
+      t = 0.5f * (lof + hi);
+      if (!(t < hi)) t = lof;
+    }
+  }
+  return t;
+}
+
 // ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
 
 // `sel`: the spatial search states [B]; cleared by the statistics pass, level 0 filled by the finalize kernel.
@@ -224,9 +312,12 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* n
 // Also works out the levels above an 8x8 unit from the stored unit sums (extends `part` and `nsum`).
 void launch_spatial_finalize(const Geo& g, float* part, float* nsum, float* nrm2, float* sim, float* m,
                              uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s);
-void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
+// `pending` (may be NULL): the search states of a budget search whose last digit has not been resolved yet; the
+// kernel then works the threshold out itself (and leaves it in `tau` for later readers) instead of reading `tau`.
+void launch_spatial_decide(const Geo& g, const float* m, float* tau, const SelState* pending, int32_t* node_map,
                            uint8_t* node_level, hipStream_t s);
 // `dirty`: the state has been searched since its statistics pass (levels 1-2 must be cleared first).
+// `tau` == NULL: the last digit is left to the kernel that uses the threshold (see `pending` above).
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,
                            SelState* state, bool dirty, float* tau, hipStream_t s);
 void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_t* keys, const int* target,
@@ -242,7 +333,8 @@ void launch_temporal_resolve(const Geo& g, int match, const int32_t* node_map, c
                              const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
                              SelState* sel, hipStream_t s);
 void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
-                            const float* sig, const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s);
+                            const float* sig, float* tau, const SelState* pending, int32_t* parent, int32_t* ptr,
+                            hipStream_t s);
 void launch_roots(const Geo& g, int32_t* ptr_a, int32_t* ptr_b, const int32_t* node_map, int32_t* cluster_ids,
                   hipStream_t s);
 void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_level, hipStream_t s);

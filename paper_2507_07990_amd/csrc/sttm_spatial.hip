@@ -417,18 +417,27 @@ void launch_spatial_finalize(const Geo& g, float* part, float* nsum, float* nrm2
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_spatial_decide: coarse-to-fine search (Sec. 3.2). One thread per cell walks down from its root:
-// the first node on the path whose smallest child similarity exceeds tau_S is kept.
+// k_spatial_decide: coarse-to-fine search (Sec. 3.2). Grid (cells of a video / 256, videos); one thread per cell
+// walks down from its root: the first node on the path whose smallest child similarity exceeds tau_S is kept.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_spatial_decide(Geo g, const float* __restrict__ m,
-                                                        const float* __restrict__ tau,
-                                                        int32_t* __restrict__ node_map,
-                                                        uint8_t* __restrict__ node_level) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= g.N) return;
+__global__ __launch_bounds__(kSelThreads) void k_spatial_decide(Geo g, const float* __restrict__ m,
+                                                                float* __restrict__ tau,
+                                                                const SelState* __restrict__ pending,
+                                                                int32_t* __restrict__ node_map,
+                                                                uint8_t* __restrict__ node_level) {
+  const int b = blockIdx.y, per_video = g.T * g.HW;
+  float t;
+  if (pending) {  // the budget search left its last digit to this kernel
+    t = sel_last_digit(pending + b);
+    if (blockIdx.x == 0 && threadIdx.x == 0) tau[b] = t;
+  } else {
+    t = tau[b];
+  }
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= per_video) return;
+  const int i = b * per_video + j;
   const int f = i / g.HW, c = i - f * g.HW;
   const int y = c / g.W, x = c - y * g.W;
-  const float t = tau[f / g.T];
   const float* mf = m + (size_t)f * g.NN;
   int lvl = g.L;
   for (; lvl >= 1; --lvl)
@@ -438,10 +447,11 @@ __global__ __launch_bounds__(256) void k_spatial_decide(Geo g, const float* __re
   if (node_level) node_level[i] = (uint8_t)lvl;
 }
 
-void launch_spatial_decide(const Geo& g, const float* m, const float* tau, int32_t* node_map,
+void launch_spatial_decide(const Geo& g, const float* m, float* tau, const SelState* pending, int32_t* node_map,
                            uint8_t* node_level, hipStream_t s) {
-  hipLaunchKernelGGL(k_spatial_decide, dim3((g.N + 255) / 256), dim3(256), 0, s, g, m, tau, node_map,
-                     node_level);
+  const int per_video = g.T * g.HW;
+  hipLaunchKernelGGL(k_spatial_decide, dim3((per_video + kSelThreads - 1) / kSelThreads, g.B), dim3(kSelThreads), 0, s,
+                     g, m, tau, pending, node_map, node_level);
 }
 
 // Recovers node levels from a node map (callers may pass node_level == NULL to the temporal stage).
@@ -485,73 +495,9 @@ void launch_node_levels(const Geo& g, const int32_t* node_map, uint8_t* node_lev
 // Input: keys[video][per_video] (0 = not an element), weights (NULL = 1 for every element).
 // ------------------------------------------------------------------------------------------------
 constexpr int kSelPer = 8;   // elements per thread and pass
-constexpr int kSelThreads = 256;
 
 __device__ inline int sel_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
 __device__ inline int sel_width(int pass) { return pass == 2 ? 10 : 11; }
-
-// Workgroup-wide (256 threads): the first bin of `hist` at which acc + running weight exceeds `budget`.
-// Returns false when the whole histogram fits. All threads get the same answer.
-// *below = largest non-empty bin before the found one, or -1.
-// The histogram is the sum of `copies` arrays of kSelBins counters.
-template <int COPIES>
-__device__ inline bool sel_pick(const unsigned* __restrict__ hist, unsigned long long acc,
-                                unsigned long long budget, unsigned* digit, unsigned long long* acc_out,
-                                int* below) {
-  __shared__ unsigned long long wsum[kSelThreads / 64];
-  __shared__ unsigned s_digit;
-  __shared__ unsigned long long s_acc;
-  __shared__ int s_found, s_below;
-  constexpr int PER = kSelBins / kSelThreads;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  unsigned h[PER];
-  unsigned long long tot = 0;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) h[j] = 0;
-#pragma unroll
-  for (int c = 0; c < COPIES; ++c)  // all loads at once
-#pragma unroll
-    for (int j = 0; j < PER; ++j) h[j] += hist[c * kSelBins + tid * PER + j];
-#pragma unroll
-  for (int j = 0; j < PER; ++j) tot += h[j];
-  unsigned long long inc = tot;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned long long t = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += t;
-  }
-  if (tid == 0) { s_found = 0; s_below = -1; }
-  if (lane == 63) wsum[wave] = inc;
-  __syncthreads();
-  unsigned long long ex = acc + inc - tot;
-  for (int w = 0; w < wave; ++w) ex += wsum[w];
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    if (ex <= budget && ex + h[j] > budget) {
-      s_found = 1;
-      s_digit = (unsigned)(tid * PER + j);
-      s_acc = ex;
-    }
-    ex += h[j];
-  }
-  __syncthreads();
-  const bool found = s_found != 0;
-  if (found && below) {
-    int mine = -1;  // largest non-empty bin below the found one: per thread, per wavefront, then one LDS atomic each
-#pragma unroll
-    for (int j = 0; j < PER; ++j)
-      if (h[j] && tid * PER + j < (int)s_digit) mine = tid * PER + j;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mine = max(mine, __shfl_xor(mine, o, 64));
-    if (lane == 0 && mine >= 0) atomicMax(&s_below, mine);
-    __syncthreads();
-    *below = s_below;
-  }
-  *digit = s_digit;
-  *acc_out = s_acc;
-  __syncthreads();
-  return found;
-}
 
 // base of the step function: spatial = constant (roots * T), temporal = kept nodes of the video's first frame
 __device__ inline int sel_base(const Geo& g, int b, int base_const, const int32_t* node_map) {
@@ -653,29 +599,11 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pass(Geo g, const uint32
   }
 }
 
-// Last digit, then tau = midpoint between the searched key and the largest key below it.
+// Last digit as a launch of its own (when the caller wants the threshold back).
 __global__ __launch_bounds__(kSelThreads) void k_select_tau(const SelState* __restrict__ states,
                                                             float* __restrict__ tau) {
-  const int b = blockIdx.x;
-  const SelState* st = states + b;
-  const SelFound fd = st->found[1];
-  float t = 1.f;
-  if (fd.rc == 2) {
-    t = -2.f;
-  } else if (fd.rc == 0) {
-    unsigned d2;
-    unsigned long long a2;
-    int below;
-    if (sel_pick<1>(st->hist[1], fd.acc, fd.budget, &d2, &a2, &below)) {
-      const unsigned over = (fd.prefix << 10) | d2;
-      const unsigned lo_key = below >= 0 ? ((fd.prefix << 10) | (unsigned)below) : st->lo_out;
-      const float hi = key_float(over);
-      const float lof = lo_key ? key_float(lo_key) : -2.f;
-      t = 0.5f * (lof + hi);
-      if (!(t < hi)) t = lof;
-    }
-  }
-  if (threadIdx.x == 0) tau[b] = t;
+  const float t = sel_last_digit(states + blockIdx.x);
+  if (threadIdx.x == 0) tau[blockIdx.x] = t;
 }
 
 static void launch_select(const Geo& g, const uint32_t* keys, const uint8_t* weights, int per_video,
@@ -688,7 +616,7 @@ static void launch_select(const Geo& g, const uint32_t* keys, const uint8_t* wei
                      node_map, st);
   hipLaunchKernelGGL(k_select_pass<2>, grid, block, 0, s, g, keys, weights, per_video, target, base_const,
                      node_map, st);
-  hipLaunchKernelGGL(k_select_tau, dim3(g.B), block, 0, s, st, tau);
+  if (tau) hipLaunchKernelGGL(k_select_tau, dim3(g.B), block, 0, s, st, tau);
 }
 
 void launch_select_spatial(const Geo& g, const uint32_t* keys, const uint8_t* weights, const int* target,

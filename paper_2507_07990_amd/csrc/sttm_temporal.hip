@@ -489,15 +489,23 @@ void launch_temporal_resolve(const Geo& g, int match, const int32_t* node_map, c
 // (similarity image, reversed raster index), so ties go towards the top-left). Also seeds the
 // pointer-jumping array.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_temporal_parent(Geo g, int match, const int32_t* __restrict__ node_map,
+__global__ __launch_bounds__(kSelThreads) void k_temporal_parent(Geo g, int match, const int32_t* __restrict__ node_map,
                                                          const uint8_t* __restrict__ node_level,
                                                          const float* __restrict__ sig,
-                                                         const float* __restrict__ tau,
+                                                         float* __restrict__ tau,
+                                                         const SelState* __restrict__ pending,
                                                          int32_t* __restrict__ parent, int32_t* __restrict__ ptr) {
   __shared__ PairFrame pf;
   __shared__ int par[1024];
   __shared__ unsigned long long best[1024];
   const int f = blockIdx.x, HW = g.HW;
+  float th;
+  if (pending) {  // the budget search left its last digit to this kernel
+    th = sel_last_digit(pending + f / g.T);
+    if (f % g.T == 0 && threadIdx.x == 0) tau[f / g.T] = th;
+  } else {
+    th = tau[f / g.T];
+  }
   if (f % g.T == 0) {
     for (int c = threadIdx.x; c < HW; c += blockDim.x) {
       parent[(size_t)f * HW + c] = -1;
@@ -511,7 +519,6 @@ __global__ __launch_bounds__(256) void k_temporal_parent(Geo g, int match, const
     best[c] = 0ull;
   }
   __syncthreads();
-  const float th = tau[f / g.T];
   for (int c = threadIdx.x; c < HW; c += blockDim.x) {
     const int a = pf.lvl_t[c], b = pf.lvl_p[c];
     const int n = pf.rep_t[c], d = pf.rep_p[c];
@@ -540,9 +547,10 @@ __global__ __launch_bounds__(256) void k_temporal_parent(Geo g, int match, const
 }
 
 void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
-                            const float* sig, const float* tau, int32_t* parent, int32_t* ptr, hipStream_t s) {
-  hipLaunchKernelGGL(k_temporal_parent, dim3(g.F), dim3(256), 0, s, g, match, node_map, node_level, sig, tau, parent,
-                     ptr);
+                            const float* sig, float* tau, const SelState* pending, int32_t* parent, int32_t* ptr,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(k_temporal_parent, dim3(g.F), dim3(kSelThreads), 0, s, g, match, node_map, node_level, sig, tau,
+                     pending, parent, ptr);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -38,7 +38,7 @@ def load():
 
 
 def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, lib=None, use_nodes=True,
-            match=0, order=0, positions=False):
+            match=0, order=0, positions=False, defer_tau=False):
     lib = lib or load()
     B, T, H, W, D = feats.shape
     dt = STTM_BF16 if feats.dtype == np.uint16 else (STTM_F16 if feats.dtype == np.float16 else STTM_F32)
@@ -67,7 +67,7 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     if tau_s is None:
         chk(lib.sttm_spatial_stats(h, _p(x), dt, B, T, H, W, D, root_grid))
         out = (C.c_float * B)()
-        chk(lib.sttm_budget_threshold(h, 0, karr(keep), out))
+        chk(lib.sttm_budget_threshold(h, 0, karr(keep), None if defer_tau else out))
         r.tau_s = np.array(list(out), np.float32)
         chk(lib.sttm_spatial_quadtree(h, _p(x), dt, B, T, H, W, D, root_grid, None, _p(node_map), _p(node_level)))
     else:
@@ -85,7 +85,7 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     if tau_t is None:
         chk(lib.sttm_temporal_stats(h, _p(x), _p(node_map), _p(node_level)))
         out = (C.c_float * B)()
-        chk(lib.sttm_budget_threshold(h, 1, karr(keep), out))
+        chk(lib.sttm_budget_threshold(h, 1, karr(keep), None if defer_tau else out))
         r.tau_t = np.array(list(out), np.float32)
         chk(lib.sttm_temporal_merge(h, _p(x), _p(node_map), _p(node_level), None, _p(cluster)))
     else:

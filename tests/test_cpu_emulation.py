@@ -64,3 +64,15 @@ def test_emulated_destination_rules_orders_and_positions(emul, mode, order):
     r = run_cpu.run_cpu(feats, match=P.MODES[mode], order=P.ORDERS[order], positions=True, **kw)
     info = P.check_parity(fake, feats, r, mode=mode, order=order, **kw)
     assert "merged_pos_err" in info
+
+
+def test_emulated_budget_threshold_left_to_the_consumer_kernels(emul):
+    """Without a host pointer for the threshold the last digit of the search is resolved by the kernels that use it:
+    same partition, same clusters, same rows."""
+    run_cpu, fake = emul
+    feats = wl.generate(_variant(91, 2, 3, 5, 6, 24, "bf16"))
+    a = run_cpu.run_cpu(feats, keep=0.5)
+    b = run_cpu.run_cpu(feats, keep=0.5, defer_tau=True)
+    assert (a.node_map == b.node_map).all() and (a.cluster_ids == b.cluster_ids).all()
+    assert (a.parent == b.parent).all() and a.K == b.K
+    np.testing.assert_array_equal(a.merged, b.merged)

@@ -175,6 +175,35 @@ def test_budget_call_can_be_repeated(lib):
     assert (r.tau_s == t50).all() and (r.tau_t == u50).all()
 
 
+def test_budget_threshold_left_to_the_consumer_kernels(lib):
+    """sttm_budget_threshold without a host pointer resolves the last digit of the search inside the decision and
+    edge kernels; the outputs must be those of the explicit path, bit for bit."""
+    import torch
+    cfg = wl.small_variant(wl.CONFIGS[1], T=12, B=2)
+    feats = wl.generate(cfg)
+    B, T, H, W, D = feats.shape
+    N = B * T * H * W
+    ref = P.run_gpu(lib, feats, keep=0.5)
+    s = lib.Sttm(0)
+    s.ensure_workspace(B, T, H, W, D, lib.STTM_BF16, 1)
+    x = ref.feats_dev
+    nm = torch.empty(N, dtype=torch.int32, device="cuda:0")
+    nl = torch.empty(N, dtype=torch.uint8, device="cuda:0")
+    cl = torch.empty(N, dtype=torch.int32, device="cuda:0")
+    s.sttm_spatial_stats(x, lib.STTM_BF16, B, T, H, W, D, 1)
+    s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, 0.5, want_tau=False)
+    s.sttm_spatial_quadtree(x, lib.STTM_BF16, B, T, H, W, D, 1, None, nm, nl)
+    s.sttm_temporal_stats(x, nm, nl)
+    s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.5, want_tau=False)
+    s.sttm_temporal_merge(x, nm, nl, None, cl)
+    assert (nm.cpu().numpy().reshape(ref.node_map.shape) == ref.node_map).all()
+    assert (cl.cpu().numpy().reshape(ref.cluster_ids.shape) == ref.cluster_ids).all()
+    # the thresholds the kernels worked out are in the workspace: asking for them now gives the explicit path's
+    np.testing.assert_array_equal(s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.5), ref.tau_t)
+    s.sttm_temporal_merge(x, nm, nl, None, cl)                   # and the stage can be repeated with them
+    assert (cl.cpu().numpy().reshape(ref.cluster_ids.shape) == ref.cluster_ids).all()
+
+
 def test_bitwise_reproducible(lib):
     cfg = _variant(50, 2, 8, 13, 13, 520, "bf16")
     feats = wl.generate(cfg)
