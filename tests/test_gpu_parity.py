@@ -396,6 +396,21 @@ def test_positions_and_settings_error_paths(lib):
     with pytest.raises(lib.SttmError) as e:
         s.sttm_positions(None, None, None, off, N, sv)
     assert e.value.code == lib.STTM_ERR_NULL
+    # the order may not change between the reduce call and its position indices
+    x = r.feats_dev
+    nm = torch.from_numpy(r.node_map.reshape(-1)).cuda()
+    nl = torch.from_numpy(r.node_level.reshape(-1)).cuda()
+    merged = torch.zeros(N, feats.shape[-1], device="cuda:0")
+    s.sttm_reduce(x, cl, None, None, lib.STTM_F32, N, merged, None, None, off)
+    s.sttm_positions(cl, nm, nl, off, N, sv)                     # fine: follows the reduce call on these ids
+    s.sttm_set_output_order(lib.STTM_ORDER_ZSCAN)
+    with pytest.raises(lib.SttmError) as e:
+        s.sttm_positions(cl, nm, nl, off, N, sv)
+    assert e.value.code == lib.STTM_ERR_STATE
+    s.sttm_set_match_mode(lib.STTM_MATCH_MOST_SIMILAR)             # another rule: the temporal statistics are stale
+    with pytest.raises(lib.SttmError) as e:
+        s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, [0.5])
+    assert e.value.code == lib.STTM_ERR_STATE
 
 
 def test_config3_long_video_most_similar_zscan_positions(lib):
