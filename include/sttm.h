@@ -151,7 +151,8 @@ int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* nod
  * chosen is the midpoint of the last interval between consecutive distinct v on which K <= target (1 if K never
  * exceeds it, -2 if even merging everything exceeds it). Requires the stage's statistics in the workspace; stores
  * the thresholds on the device for the following sttm_spatial_quadtree / sttm_temporal_merge call with NULL
- * thresholds. tau_out: host array [B] or NULL; when non-NULL the stream is synchronised and the values copied out. */
+ * thresholds. tau_out: host array [B] or NULL; when non-NULL the stream is synchronised and the values copied out
+ * (with NULL the last step of the search is left to that following call, which saves a kernel launch). */
 int sttm_budget_threshold(sttm_ctx* ctx, int stage, const double* target_keep_host, float* tau_out_host);
 
 /* ---- stage 3: gather / average (Sec. 3.1, 3.3, 3.4) ---------------------------------------------------- */
