@@ -29,7 +29,8 @@ def stored_traffic(config: int, keep):
     """HBM-side bytes per launch of the feature kernels, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     runs of this very script (summaries under profiles/; bench.py itself cannot run a profiler around itself).
     Returns {kernel: read + written bytes} or {} when no summary covers the workload."""
-    names = {(3, 0.5): "whole_path_long_video_keep50.txt", (3, 0.3): "whole_path_long_video_keep30.txt"}
+    names = {(3, 0.5): "whole_path_long_video_keep50.txt", (3, 0.3): "whole_path_long_video_keep30.txt",
+             (5, 0.5): "whole_path_paper_grid_keep50.txt", (4, None): "whole_path_batched_unpooled.txt"}
     path = os.path.join(ROOT, "profiles", names.get((config, keep), "-"))
     out = {}
     if os.path.exists(path):
