@@ -17,7 +17,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  size_t part, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_s, sel_t, lvl,
+  size_t part, partu, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_s, sel_t, lvl,
       pd_part, sig, e, parent, ptr_a, ptr_b;
   size_t rank, key_a, val_a, key_b, val_b, order, orow, hist, tot, gsum, tile_roots, tile_live, seg, kdev,
       bigpart, bigw, biglist, zpos, possum, poscnt;
@@ -56,7 +56,8 @@ Layout make_layout(const Geo& g) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   const size_t F = g.F, NN = g.NN, N = g.N;
-  l.part = take(F * g.nC * 2 * NN * sizeof(float));
+  l.part = take(F * g.nC * unit_cols(g) * unit_rows(g) * kUnitScalars * sizeof(float));
+  l.partu = take(F * g.nC * nsum_nodes(g) * sizeof(float));
   l.nsum = take(F * nsum_nodes(g) * g.D * sizeof(float));
   l.nrm2 = take(F * NN * sizeof(float));
   l.sim = take(F * NN * sizeof(float));
@@ -217,7 +218,8 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
     launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum),
                          at<SelState>(c, c->lay.sel_s), c->stream);
   }
-  launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum), at<float>(c, c->lay.nrm2),
+  launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.partu), at<float>(c, c->lay.nsum),
+                          at<float>(c, c->lay.nrm2),
                           at<float>(c, c->lay.sim),
                           at<float>(c, c->lay.m), at<uint32_t>(c, c->lay.sel_key_s), at<uint8_t>(c, c->lay.sel_w_s),
                           at<SelState>(c, c->lay.sel_s), c->stream);

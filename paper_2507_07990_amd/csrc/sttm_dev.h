@@ -69,6 +69,10 @@ template <> struct Row<0> {
   __device__ static inline void unpack(const Raw& r, float (&x)[4]) {
     x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
   }
+  // this lane's share of the dot product of two rows
+  __device__ static inline float dot(const Raw& a, const Raw& b) {
+    return fmaf(a.x, b.x, fmaf(a.y, b.y, fmaf(a.z, b.z, a.w * b.w)));
+  }
 };
 
 template <> struct Row<1> {
@@ -82,6 +86,23 @@ template <> struct Row<1> {
     x[4] = __uint_as_float(r.z << 16); x[5] = __uint_as_float(r.z & 0xffff0000u);
     x[6] = __uint_as_float(r.w << 16); x[7] = __uint_as_float(r.w & 0xffff0000u);
   }
+  // Straight from the packed pairs: one instruction multiplies two pairs and adds both products to the running
+  // fp32 sum (a product of two bf16 values is exact in fp32), so nothing has to be unpacked.
+  __device__ static inline float dot(const Raw& a, const Raw& b) {
+#ifndef STTM_HOST_EMULATION
+    typedef __bf16 pair __attribute__((ext_vector_type(2)));
+    float d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.x), __builtin_bit_cast(pair, b.x), 0.f, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.y), __builtin_bit_cast(pair, b.y), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.z), __builtin_bit_cast(pair, b.z), d, false);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.w), __builtin_bit_cast(pair, b.w), d, false);
+#else
+    float x[8], y[8], d = 0.f;
+    unpack(a, x);
+    unpack(b, y);
+    for (int v = 0; v < 8; ++v) d = fmaf(x[v], y[v], d);
+    return d;
+#endif
+  }
 };
 
 template <> struct Row<2> {
@@ -94,6 +115,21 @@ template <> struct Row<2> {
   __device__ static inline void unpack(const Raw& r, float (&x)[8]) {
     x[0] = lo(r.x); x[1] = hi(r.x); x[2] = lo(r.y); x[3] = hi(r.y);
     x[4] = lo(r.z); x[5] = hi(r.z); x[6] = lo(r.w); x[7] = hi(r.w);
+  }
+  __device__ static inline float dot(const Raw& a, const Raw& b) {
+#ifndef STTM_HOST_EMULATION
+    typedef _Float16 pair __attribute__((ext_vector_type(2)));
+    float d = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.x), __builtin_bit_cast(pair, b.x), 0.f, false);
+    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.y), __builtin_bit_cast(pair, b.y), d, false);
+    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.z), __builtin_bit_cast(pair, b.z), d, false);
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.w), __builtin_bit_cast(pair, b.w), d, false);
+#else
+    float x[8], y[8], d = 0.f;
+    unpack(a, x);
+    unpack(b, y);
+    for (int v = 0; v < 8; ++v) d = fmaf(x[v], y[v], d);
+    return d;
+#endif
   }
 };
 
@@ -310,7 +346,7 @@ __device__ inline float sel_last_digit(const SelState* __restrict__ st) {
 void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
                           hipStream_t s);
 // Also works out the levels above an 8x8 unit from the stored unit sums (extends `part` and `nsum`).
-void launch_spatial_finalize(const Geo& g, float* part, float* nsum, float* nrm2, float* sim, float* m,
+void launch_spatial_finalize(const Geo& g, const float* part, float* partu, float* nsum, float* nrm2, float* sim, float* m,
                              uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s);
 // `pending` (may be NULL): the search states of a budget search whose last digit has not been resolved yet; the
 // kernel then works the threshold out itself (and leaves it in `tau` for later readers) instead of reading `tau`.
@@ -326,6 +362,12 @@ inline size_t select_state_bytes(int B) { return (size_t)B * sizeof(SelState); }
 // `sel`: the temporal search states [B]; cleared here, level 0 filled by launch_temporal_resolve.
 void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
                           float* pd_part, SelState* sel, hipStream_t s);
+// The first pass works in 8x8-cell units (one wavefront per unit, chunk and frame) and leaves each unit's scalars
+// as one block of kUnitScalars floats: per 4x4 tile 16 squared norms, 16 cell and 4 level-1 dot products, then the
+// 4 level-2 dot products (padded to whole 128-byte lines): part[f][chunk][unit][kUnitScalars].
+constexpr int kUnitScalars = 160;
+inline __host__ __device__ int unit_cols(const Geo& g) { return (g.W + 7) >> 3; }
+inline __host__ __device__ int unit_rows(const Geo& g) { return (g.H + 7) >> 3; }
 // fp32 sums of the pyramid nodes at levels >= 3: [F][nsum_nodes][D]
 inline size_t nsum_nodes(const Geo& g) { return g.L >= 3 ? (size_t)(g.NN - g.lvl_base[3]) : 0; }
 // `match`: destination rule (0 = top-left-most passing, 1 = the one under the top-left cell only, 2 = most similar).

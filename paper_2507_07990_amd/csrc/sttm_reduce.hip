@@ -571,6 +571,9 @@ struct GatherArgs {
   const int32_t* zpos;  // output row of every cluster rank when the rows follow the Z-shaped scan, else NULL
 };
 
+// Wavefronts that share an item: one per chunk of the row, at most 16 (beyond that a wavefront takes several chunks).
+__host__ __device__ inline int gather_waves(const Geo& g) { return g.nC < 16 ? g.nC : 16; }
+
 template <int VEC>
 __device__ inline void store_partial(float* o, const float (&acc)[VEC]) {
 #pragma unroll
@@ -578,14 +581,15 @@ __device__ inline void store_partial(float* o, const float (&acc)[VEC]) {
 }
 
 template <int DT, int ODT>
-__global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
+__global__ __launch_bounds__(64) void k_reduce(Geo g, GatherArgs a) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  // one-wavefront workgroups; consecutive ones take the chunks of one item
+  const int nw = gather_waves(g), wave = blockIdx.x % nw, item = blockIdx.x / nw, lane = threadIdx.x;
   // Lane j < kItem describes list position p0 + j, the next kTail lanes the positions after the item (the start of
   // a cluster that runs past it). The list entries are requested together with the list's length: entries at or
   // beyond the end are stale and are not used.
-  const int p0 = blockIdx.x * kItem, pl = p0 + lane;
+  const int p0 = item * kItem, pl = p0 + lane;
   int cell_l = 0, rank_l = 0;
   if (lane < kItem + kTail && pl < g.N) {
     cell_l = a.order[pl];
@@ -639,9 +643,9 @@ __global__ __launch_bounds__(1024) void k_reduce(Geo g, GatherArgs a) {
         if (big) {
           if (closes || last) {  // this item's share of a big cluster
             const int slot = beg < p0 ? 0 : 1;
-            if (act) store_partial<VEC>(a.bigpart + ((size_t)blockIdx.x * 2 + slot) * g.D + ch0, acc);
+            if (act) store_partial<VEC>(a.bigpart + ((size_t)item * 2 + slot) * g.D + ch0, acc);
             if (chunk == 0 && lane == 0) {
-              a.bigw[blockIdx.x * 2 + slot] = members;
+              a.bigw[item * 2 + slot] = members;
               if (slot == 1) a.biglist[atomicAdd(a.bigcount, 1)] = make_int4(row, beg, end, 0);
             }
 #pragma unroll
@@ -984,8 +988,7 @@ void launch_reduce_gather(const Geo& g, const void* feats, const float* nsum, co
                           const uint8_t* node_level, int out_dtype, int64_t capacity, void* merged, int32_t* counts,
                           const ReduceBuffers& rb, bool zscan, hipStream_t s) {
   const int nitems = (g.N + kItem - 1) / kItem;
-  const int nw = g.nC < 16 ? g.nC : 16;
-  dim3 grid(nitems), block(64 * nw);
+  dim3 grid((unsigned)(nitems * gather_waves(g))), block(64);  // <= N + 15 workgroups
   const GatherArgs a = gather_args(feats, nsum, node_map, node_level, capacity, merged, counts, rb, zscan);
   STTM_DISPATCH_IO(k_reduce, g.dtype, out_dtype, grid, block, s, g, a);
 }

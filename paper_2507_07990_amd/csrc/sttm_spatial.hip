@@ -62,8 +62,7 @@ __device__ __forceinline__ void tile_mask(typename Row<DT>::Raw (&raw)[16], int 
 // cells and level-1 blocks to the per-chunk tables.
 template <int DT>
 __device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>::Raw (&raw)[16], float* tb,
-                                           int lane, int ty, int tx, int th, int tw, float* pn,
-                                           float* pd, float (&S2)[Row<DT>::VEC]) {
+                                           int lane, int th, int tw, float* st, float (&S2)[Row<DT>::VEC]) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
 #pragma unroll
@@ -121,16 +120,16 @@ __device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>:
       dy = (q1 >> 1) * 2;
       dx = (q1 & 1) * 2;
     }
+    float acc = 0.f;
     if (dy < th && dx < tw && !(is_dot && lvl >= g.L) && lvl <= g.L) {
       const float4* row = reinterpret_cast<const float4*>(tb + r * kRowStride);
-      float acc = 0.f;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         float4 q = row[j];
         acc += (q.x + q.y) + (q.z + q.w);
       }
-      (is_dot ? pd : pn)[node_index(g, lvl, (ty + dy) >> lvl, (tx + dx) >> lvl)] = acc;
     }
+    st[r] = acc;
   }
   wave_lds_fence();
 }
@@ -142,6 +141,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   __shared__ float tb[kTileRows * kRowStride];
+  __shared__ __attribute__((aligned(16))) float st[kUnitScalars];
   const int chunk = blockIdx.x, u = blockIdx.y, f = blockIdx.z, lane = threadIdx.x;
   const int ch0 = chunk * g.cch + lane * VEC;
   const bool act = ch0 < g.D;
@@ -156,14 +156,11 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
   tile_load<DT>(bufA, fbase, W, g.D, y3, x3, min(vh, 4), min(vw, 4));
   {
     if (chunk == 0 && u == 0 && f % g.T == 0) sel_clear(sel + f / g.T);  // this video's budget search starts afresh
-    float* pn = part + (size_t)(f * g.nC + chunk) * 2 * g.NN;
-    float* pd = pn + g.NN;
     float S3[VEC], S2[4][VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) S3[v] = 0.f;
 #pragma unroll
     for (int q2 = 0; q2 < 4; ++q2) {
-      const int ty = y3 + (q2 >> 1) * 4, tx = x3 + (q2 & 1) * 4;
       const int th = max(0, min(4, vh - (q2 >> 1) * 4)), tw = max(0, min(4, vw - (q2 & 1) * 4));
       if (q2 < 3) {
         // the next tile's rows fly while this one is worked on; a tile wholly beyond the edge reads the
@@ -176,15 +173,17 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
       }
       if (th > 0 && tw > 0) {
         tile_mask<DT>((q2 & 1) ? bufB : bufA, th, tw, act);
-        tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, ty, tx, th, tw, pn, pd, S2[q2]);
+        tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, th, tw, st + q2 * kTileRows, S2[q2]);
       } else {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) S2[q2][v] = 0.f;
+        if (lane < kTileRows) st[q2 * kTileRows + lane] = 0.f;
       }
 #pragma unroll
       for (int v = 0; v < VEC; ++v) S3[v] += S2[q2][v];
     }
     // level-2 dot products of the four tiles with the unit's sum
+    if (lane < kUnitScalars - 4 * kTileRows) st[4 * kTileRows + lane] = 0.f;
     if (L >= 3) {
 #pragma unroll
       for (int q2 = 0; q2 < 4; ++q2) {
@@ -204,7 +203,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
             float4 q = row[j];
             acc += (q.x + q.y) + (q.z + q.w);
           }
-          pd[node_index(g, 2, (y3 >> 2) + (q2 >> 1), (x3 >> 2) + (q2 & 1))] = acc;
+          st[4 * kTileRows + q2] = acc;
         }
       }
       wave_lds_fence();
@@ -215,6 +214,11 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
           *reinterpret_cast<float4*>(o + v) = make_float4(S3[v], S3[v + 1], S3[v + 2], S3[v + 3]);
       }
     }
+    // the workgroup's scalars leave in one piece: whole, aligned 128-byte lines that no other workgroup touches
+    wave_lds_fence();
+    if (lane < kUnitScalars / 4)
+      reinterpret_cast<float4*>(part + ((size_t)(f * g.nC + chunk) * gridDim.y + u) * kUnitScalars)[lane] =
+          reinterpret_cast<const float4*>(st)[lane];
   }
 }
 
@@ -224,10 +228,10 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
 // sum next to the level-3 sums and the partial dot product of every child with it in the same per-chunk
 // tables as above. Runs at the head of the finalize kernel, level by level.
 // ------------------------------------------------------------------------------------------------
-__device__ inline void pyramid_upper_node(const Geo& g, float* part, float* nsum, int chunk, int f, int lane, int lvl,
+__device__ inline void pyramid_upper_node(const Geo& g, float* partu, float* nsum, int chunk, int f, int lane, int lvl,
                                           int nd) {
   const int NB = g.NN - g.lvl_base[3];
-  float* pd = part + (size_t)(f * g.nC + chunk) * 2 * g.NN + g.NN;
+  float* pd = partu + (size_t)(f * g.nC + chunk) * NB;  // indexed by node - first level-3 node
   float* rows = nsum + (size_t)f * NB * g.D;
   const int G = g.P >> lvl;
   const int by = nd / G, bx = nd - by * G;
@@ -260,14 +264,14 @@ __device__ inline void pyramid_upper_node(const Geo& g, float* part, float* nsum
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int cy = 2 * by + (k >> 1), cx = 2 * bx + (k & 1);
-      if (node_exists(g, lvl - 1, cy, cx)) pd[node_index(g, lvl - 1, cy, cx)] = tot[k];
+      if (node_exists(g, lvl - 1, cy, cx)) pd[node_index(g, lvl - 1, cy, cx) - g.lvl_base[3]] = tot[k];
     }
   }
 }
 
 void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
                           hipStream_t s) {
-  const int UX = (g.W + 7) / 8, UY = (g.H + 7) / 8;
+  const int UX = unit_cols(g), UY = unit_rows(g);
   dim3 grid(g.nC, UX * UY, g.F), block(64);
   if (g.dtype == 1)
     hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, 0, s, g, feats, part, nsum, sel);
@@ -283,7 +287,8 @@ void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* n
 // them into sigma(parent, child) (Sec. 3.2: cosine between a level's nodes and their children),
 // m_n = min over existing children, and the split score s_n = max of m along the path from the root.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void k_spatial_finalize(Geo g, float* part, float* __restrict__ nsum,
+__global__ __launch_bounds__(512) void k_spatial_finalize(Geo g, const float* __restrict__ part, float* partu,
+                                                          float* __restrict__ nsum,
                                                           float* __restrict__ nrm2, float* __restrict__ sim,
                                                           float* __restrict__ m, uint32_t* __restrict__ sel_key,
                                                           uint8_t* __restrict__ sel_w,
@@ -299,7 +304,7 @@ __global__ __launch_bounds__(512) void k_spatial_finalize(Geo g, float* part, fl
   for (int lvl = 4; lvl <= g.L; ++lvl) {  // the levels above the 8x8 units: one wavefront per (node, chunk)
     const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6, side = g.P >> lvl;
     for (int w = wave; w < side * side * g.nC; w += nwaves)
-      pyramid_upper_node(g, part, nsum, w % g.nC, f, threadIdx.x & 63, lvl, w / g.nC);
+      pyramid_upper_node(g, partu, nsum, w % g.nC, f, threadIdx.x & 63, lvl, w / g.nC);
     __syncthreads();  // sums and dot products written above are read by other wavefronts of this workgroup
   }
   for (int idx = threadIdx.x; idx < g.NN; idx += blockDim.x) {
@@ -307,15 +312,32 @@ __global__ __launch_bounds__(512) void k_spatial_finalize(Geo g, float* part, fl
     node_decode(g, idx, lvl, by, bx);
     float n = 0.f, d = 0.f;
     if (node_exists(g, lvl, by, bx)) {
-      const float* p = part + (size_t)f * g.nC * 2 * g.NN + idx;
+      // where the first pass (levels 0..2) or the step above (levels >= 3) left this node's partials
+      const float* p;
+      size_t cstride;  // from one chunk's value to the next
+      int dn = 0;      // offset of the squared norm relative to the dot product (cells only)
+      if (lvl <= 2) {
+        const int y = by << lvl, x = bx << lvl;
+        const int NU = unit_cols(g) * unit_rows(g);
+        const int q2 = ((y >> 2) & 1) * 2 + ((x >> 2) & 1), q1 = ((y >> 1) & 1) * 2 + ((x >> 1) & 1);
+        const int slot = lvl == 2 ? 4 * kTileRows + q2
+                                  : q2 * kTileRows + (lvl == 1 ? 32 + q1 : 16 + q1 * 4 + (y & 1) * 2 + (x & 1));
+        p = part + ((size_t)f * g.nC * NU + (y >> 3) * unit_cols(g) + (x >> 3)) * kUnitScalars + slot;
+        cstride = (size_t)NU * kUnitScalars;
+        dn = -16;
+      } else {
+        const int NB = g.NN - g.lvl_base[3];
+        p = partu + (size_t)f * g.nC * NB + (idx - g.lvl_base[3]);
+        cstride = NB;
+      }
       const bool want_n = lvl == 0, want_d = lvl < g.L;
       for (int c0 = 0; c0 < g.nC; c0 += 8) {  // eight chunks' partials in flight, added in chunk order
         float pn[8], pd[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           const bool in = c0 + u < g.nC;
-          pn[u] = in && want_n ? p[(size_t)(c0 + u) * 2 * g.NN] : 0.f;
-          pd[u] = in && want_d ? p[(size_t)(c0 + u) * 2 * g.NN + g.NN] : 0.f;
+          pn[u] = in && want_n ? p[(size_t)(c0 + u) * cstride + dn] : 0.f;
+          pd[u] = in && want_d ? p[(size_t)(c0 + u) * cstride] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -408,10 +430,10 @@ __global__ __launch_bounds__(512) void k_spatial_finalize(Geo g, float* part, fl
   sel_flush_level0(sel + f / g.T, h0);
 }
 
-void launch_spatial_finalize(const Geo& g, float* part, float* nsum, float* nrm2, float* sim, float* m,
-                             uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s) {
+void launch_spatial_finalize(const Geo& g, const float* part, float* partu, float* nsum, float* nrm2, float* sim,
+                             float* m, uint32_t* sel_key, uint8_t* sel_w, SelState* sel, hipStream_t s) {
   const int threads = g.NN <= 256 ? 256 : 512;  // one node per thread where it fits; more workgroups per CU beyond
-  hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(threads), 3 * g.NN * sizeof(float), s, g, part, nsum, nrm2,
+  hipLaunchKernelGGL(k_spatial_finalize, dim3(g.F), dim3(threads), 3 * g.NN * sizeof(float), s, g, part, partu, nsum, nrm2,
                      sim,
                      m, sel_key, sel_w, sel);
 }

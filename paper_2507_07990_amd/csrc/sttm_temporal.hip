@@ -164,6 +164,11 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
         const int ri = base + half * 2 + rr;
         const int c0 = ri < nf ? fast[ri] : 0;
         const bool t_block = lvl_t[c0] == 1, p_block = lvl_p[c0] == 1;  // wave-uniform
+        if (!t_block && !p_block) {  // four cells against four cells: no sums needed
+#pragma unroll
+          for (int k = 0; k < 4; ++k) tb[((half * 2 + rr) * 4 + k) * 68 + lane] = R::dot(rt[rr][k], rp[rr][k]);
+          continue;
+        }
         float xt[4][VEC], xp[4][VEC];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
