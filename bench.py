@@ -61,6 +61,8 @@ def main() -> int:
                     help="destination rule of the temporal stage (default: the paper's top-left-most passing one)")
     ap.add_argument("--order", choices=["raster", "zscan"], default="raster", help="row order of the output")
     ap.add_argument("--positions", action="store_true", help="also emit the position indices of the rows each step")
+    ap.add_argument("--no-cell-dots", action="store_true",
+                    help="keep the spatial and temporal passes separate (sttm_set_cell_dots(0))")
     ap.add_argument("--no-node-sums", action="store_true",
                     help="reduce stage without the stage-1 partition: every cell is read again")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -103,6 +105,7 @@ def main() -> int:
     s = lib.Sttm(0)
     s.sttm_set_match_mode({"first_passing": 0, "topleft_only": 1, "most_similar": 2}[args.match])
     s.sttm_set_output_order({"raster": 0, "zscan": 1}[args.order])
+    s.sttm_set_cell_dots(0 if args.no_cell_dots else 1)
     s.ensure_workspace(B, T, H, W, D, dt, R)
     node_map = torch.empty(N, dtype=torch.int32, device=dev)
     node_level = torch.empty(N, dtype=torch.uint8, device=dev)
@@ -157,10 +160,28 @@ def main() -> int:
     rho = K / N
 
     # Algorithmic bytes per launch of each feature kernel: every input element it must see read once,
-    # every output element written once (design notes: data layout / kernels).
+    # every output element written once (design notes: data layout / kernels). The temporal pass must see the rows
+    # of the node pairs it computes: both nodes' cells when the coarser one is at most a 4x4 block, only the finer
+    # node's cells above that (the coarser node's sum is stored) -- and nothing for a pair of two single cells when
+    # the spatial pass left that dot product. A row needed by two frame pairs counts once.
+    lv = node_level.view(B, T, H * W)
+    if T > 1:
+        a, b = lv[:, 1:].int(), lv[:, :-1].int()
+        J = torch.maximum(a, b)
+        small = J <= 2
+        if not args.no_cell_dots:
+            small = small & (J > 0)
+        need_t = small | ((J >= 3) & (a < b))   # rows of the later frame of a pair
+        need_p = small | ((J >= 3) & (b < a))   # rows of the earlier frame
+        need = torch.zeros(B, T, H * W, dtype=torch.bool, device=dev)
+        need[:, 1:] |= need_t
+        need[:, :-1] |= need_p
+        rows_temporal = int(need.sum().item())
+    else:
+        rows_temporal = 0
     alg = {
         lib.STTM_KERNEL_PYRAMID_STATS: ("k_pyramid_stats", N * D * esz),
-        lib.STTM_KERNEL_TEMPORAL_DOTS: ("k_temporal_dots", N * D * esz),
+        lib.STTM_KERNEL_TEMPORAL_DOTS: ("k_temporal_dots", rows_temporal * D * esz),
         lib.STTM_KERNEL_REDUCE_GATHER: ("k_reduce", N * D * esz + K * D * esz),
     }
     kernels = {}
@@ -188,7 +209,8 @@ def main() -> int:
                                + (f", root_grid={R}" if R != 1 else "")
                                + (f", match={args.match}" if args.match != "first_passing" else "")
                                + (f", order={args.order}" if args.order != "raster" else "")
-                               + (", with position indices" if args.positions else ""),
+                               + (", with position indices" if args.positions else "")
+                               + (", separate spatial and temporal passes" if args.no_cell_dots else ""),
                    "tokens": N, "kept_tokens": K, "kept_fraction": rho, "generate_s": gen_s, "input_copies": copies},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": traffic.get(dom),

@@ -110,6 +110,14 @@ int sttm_set_workspace(sttm_ctx* ctx, void* workspace_dev, size_t bytes);
 int sttm_set_match_mode(sttm_ctx* ctx, int mode);
 /* Row order of sttm_reduce and sttm_positions (sttm_order); applies to the calls that follow. */
 int sttm_set_output_order(sttm_ctx* ctx, int order);
+/* on = 1 (the default): the spatial statistics pass also computes x_c(t) . x_c(t+1) for every cell c and frame t
+ * (Sec. 3.3 compares the features of overlapping nodes of consecutive frames; where both nodes are single cells
+ * that is this dot product), and the temporal pass leaves those pairs out instead of reading both rows again.
+ * The statistics pass gets slower, the temporal pass much faster wherever many tokens stay unmerged in space;
+ * on = 0 keeps the two passes separate (better when almost everything merges spatially). Results agree to
+ * rounding. Takes effect with the next statistics pass (sttm_spatial_stats / sttm_spatial_quadtree with
+ * thresholds). */
+int sttm_set_cell_dots(sttm_ctx* ctx, int on);
 
 /* ---- stage 1: spatial quadtree (Sec. 3.2) ------------------------------------------------------------- */
 

@@ -29,6 +29,7 @@ EXPORTS = [
     "sttm_workspace_bytes", "sttm_set_workspace", "sttm_spatial_stats", "sttm_spatial_quadtree",
     "sttm_temporal_stats", "sttm_temporal_merge", "sttm_budget_threshold", "sttm_reduce", "sttm_export",
     "sttm_profile_enable", "sttm_profile_read", "sttm_set_match_mode", "sttm_set_output_order", "sttm_positions",
+    "sttm_set_cell_dots",
 ]
 STTM_MATCH_FIRST_PASSING, STTM_MATCH_TOPLEFT_ONLY, STTM_MATCH_MOST_SIMILAR = 0, 1, 2
 STTM_ORDER_RASTER, STTM_ORDER_ZSCAN = 0, 1
@@ -62,6 +63,7 @@ def _load() -> C.CDLL:
     lib.sttm_profile_read.argtypes = [vp, i, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.sttm_set_match_mode.argtypes = [vp, i]
     lib.sttm_set_output_order.argtypes = [vp, i]
+    lib.sttm_set_cell_dots.argtypes = [vp, i]
     lib.sttm_positions.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     return lib
 
@@ -181,6 +183,9 @@ class Sttm:
 
     def sttm_set_output_order(self, order: int):
         self._check(_lib.sttm_set_output_order(self._h, order))
+
+    def sttm_set_cell_dots(self, on: int):
+        self._check(_lib.sttm_set_cell_dots(self._h, on))
 
     def sttm_positions(self, cluster_ids, node_map, node_level, offsets, capacity, survived=None, reassigned=None,
                        merged_pos=None, root_tyxl=None):

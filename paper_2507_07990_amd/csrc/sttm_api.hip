@@ -115,6 +115,8 @@ struct sttm_ctx {
   bool have_spatial = false, have_tau_s = false, have_temporal = false, have_tau_t = false;
   bool tau_s_pending = false, tau_t_pending = false;  // the budget search left its last digit to the consumer kernel
   int match_mode = STTM_MATCH_FIRST_PASSING, order = STTM_ORDER_RASTER;
+  bool cell_dots = true;        // setting: the spatial pass also emits the cell-to-cell dot products
+  bool have_cell_dots = false;  // the statistics in the workspace were computed with them
   const int32_t* cluster_ids_reduced = nullptr;  // cluster ids of the last reduce call (NULL: none since the shape was bound)
   bool reduced_zscan = false;
   const void* feats_spatial = nullptr;
@@ -215,8 +217,8 @@ int after_launch(sttm_ctx* c) { return hip_check(c, hipGetLastError(), "kernel l
 int run_spatial_stats(sttm_ctx* c, const void* feats) {
   {
     Timed t(c, STTM_KERNEL_PYRAMID_STATS);
-    launch_pyramid_stats(c->g, feats, at<float>(c, c->lay.part), at<float>(c, c->lay.nsum),
-                         at<SelState>(c, c->lay.sel_s), c->stream);
+    launch_pyramid_stats(c->g, feats, c->cell_dots && c->g.T > 1, at<float>(c, c->lay.part),
+                         at<float>(c, c->lay.nsum), at<SelState>(c, c->lay.sel_s), c->stream);
   }
   launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.partu), at<float>(c, c->lay.nsum),
                           at<float>(c, c->lay.nrm2),
@@ -229,6 +231,7 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
     c->have_spatial = true;
     c->have_temporal = false;
     c->feats_spatial = feats;
+    c->have_cell_dots = c->cell_dots && c->g.T > 1;
   }
   return rc;
 }
@@ -236,10 +239,11 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
 int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, const uint8_t* node_level) {
   {
     Timed t(c, STTM_KERNEL_TEMPORAL_DOTS);
-    launch_temporal_dots(c->g, feats, node_level, at<float>(c, c->lay.nsum), at<float>(c, c->lay.pd_part),
-                         at<SelState>(c, c->lay.sel_t), c->stream);
+    launch_temporal_dots(c->g, feats, node_level, at<float>(c, c->lay.nsum), c->have_cell_dots,
+                         at<float>(c, c->lay.pd_part), at<SelState>(c, c->lay.sel_t), c->stream);
   }
-  launch_temporal_resolve(c->g, c->match_mode, node_map, node_level, at<float>(c, c->lay.pd_part), at<float>(c, c->lay.nrm2),
+  launch_temporal_resolve(c->g, c->match_mode, node_map, node_level, at<float>(c, c->lay.pd_part),
+                          c->have_cell_dots ? at<float>(c, c->lay.part) : nullptr, at<float>(c, c->lay.nrm2),
                           at<float>(c, c->lay.sig), at<float>(c, c->lay.e), at<uint32_t>(c, c->lay.sel_key_t),
                           at<SelState>(c, c->lay.sel_t), c->stream);
   int rc = after_launch(c);
@@ -330,6 +334,13 @@ int sttm_set_match_mode(sttm_ctx* ctx, int mode) {
   return STTM_OK;
 }
 
+int sttm_set_cell_dots(sttm_ctx* ctx, int on) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (on != 0 && on != 1) return fail(ctx, STTM_ERR_ARG, "cell dots: 0 or 1");
+  ctx->cell_dots = on != 0;  // takes effect with the next spatial statistics pass
+  return STTM_OK;
+}
+
 int sttm_set_output_order(sttm_ctx* ctx, int order) {
   if (!ctx) return STTM_ERR_NULL;
   if (order != STTM_ORDER_RASTER && order != STTM_ORDER_ZSCAN) return fail(ctx, STTM_ERR_ARG, "unknown output order");
@@ -388,6 +399,8 @@ static int temporal_prepare(sttm_ctx* ctx, const void* feats_dev, const int32_t*
     return fail(ctx, STTM_ERR_STATE, "temporal stage needs the spatial statistics of the same features");
   int rc = check_feats(ctx, feats_dev);
   if (rc) return rc;
+  if (feats_dev != ctx->feats_spatial)  // norms, node sums and cell-to-cell dot products come from that pass
+    return fail(ctx, STTM_ERR_STATE, "the spatial statistics in the workspace were computed from other features");
   if (!*node_level_dev) {
     launch_node_levels(ctx->g, node_map_dev, at<uint8_t>(ctx, ctx->lay.lvl), ctx->stream);
     *node_level_dev = at<uint8_t>(ctx, ctx->lay.lvl);

@@ -343,7 +343,8 @@ __device__ inline float sel_last_digit(const SelState* __restrict__ st) {
 // ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
 
 // `sel`: the spatial search states [B]; cleared by the statistics pass, level 0 filled by the finalize kernel.
-void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
+// `cell_dots`: also leave x_c(t) . x_c(t+1) of every cell in `part` (the temporal stage then skips those pairs).
+void launch_pyramid_stats(const Geo& g, const void* feats, bool cell_dots, float* part, float* nsum, SelState* sel,
                           hipStream_t s);
 // Also works out the levels above an 8x8 unit from the stored unit sums (extends `part` and `nsum`).
 void launch_spatial_finalize(const Geo& g, const float* part, float* partu, float* nsum, float* nrm2, float* sim, float* m,
@@ -360,20 +361,29 @@ void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_
                             SelState* state, bool dirty, float* tau, hipStream_t s);
 inline size_t select_state_bytes(int B) { return (size_t)B * sizeof(SelState); }
 // `sel`: the temporal search states [B]; cleared here, level 0 filled by launch_temporal_resolve.
+// `skip_cells`: pairs of two single cells are left out (their dot products are in the spatial pass's `part`).
 void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
-                          float* pd_part, SelState* sel, hipStream_t s);
+                          bool skip_cells, float* pd_part, SelState* sel, hipStream_t s);
 // The first pass works in 8x8-cell units (one wavefront per unit, chunk and frame) and leaves each unit's scalars
 // as one block of kUnitScalars floats: per 4x4 tile 16 squared norms, 16 cell and 4 level-1 dot products, then the
-// 4 level-2 dot products (padded to whole 128-byte lines): part[f][chunk][unit][kUnitScalars].
-constexpr int kUnitScalars = 160;
+// 4 level-2 dot products (padded to whole 128-byte lines), then per tile the 16 dot products of its cells with the
+// same cells of the next frame (zeros unless asked for): part[f][chunk][unit][kUnitScalars].
+constexpr int kUnitScalars = 224;
+constexpr int kUnitCellDots = 160;
+// Offset of cell (y, x)'s cell-to-cell dot product inside its unit's block.
+inline __host__ __device__ int unit_cell_dot_slot(int y, int x) {
+  return kUnitCellDots + (((y >> 2) & 1) * 2 + ((x >> 2) & 1)) * 16 + (((y >> 1) & 1) * 2 + ((x >> 1) & 1)) * 4 +
+         (y & 1) * 2 + (x & 1);
+}
 inline __host__ __device__ int unit_cols(const Geo& g) { return (g.W + 7) >> 3; }
 inline __host__ __device__ int unit_rows(const Geo& g) { return (g.H + 7) >> 3; }
 // fp32 sums of the pyramid nodes at levels >= 3: [F][nsum_nodes][D]
 inline size_t nsum_nodes(const Geo& g) { return g.L >= 3 ? (size_t)(g.NN - g.lvl_base[3]) : 0; }
 // `match`: destination rule (0 = top-left-most passing, 1 = the one under the top-left cell only, 2 = most similar).
+// `cell_part`: the spatial pass's `part` when it holds the cell-to-cell dot products (else NULL).
 void launch_temporal_resolve(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
-                             const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
-                             SelState* sel, hipStream_t s);
+                             const float* pd_part, const float* cell_part, const float* nrm2, float* sig, float* e,
+                             uint32_t* sel_key, SelState* sel, hipStream_t s);
 void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
                             const float* sig, float* tau, const SelState* pending, int32_t* parent, int32_t* ptr,
                             hipStream_t s);

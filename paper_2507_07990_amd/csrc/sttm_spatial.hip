@@ -134,7 +134,7 @@ __device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>:
   wave_lds_fence();
 }
 
-template <int DT>
+template <int DT, bool CC>
 __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
                                                       float* __restrict__ part, float* __restrict__ nsum,
                                                       SelState* __restrict__ sel) {
@@ -142,7 +142,26 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
   constexpr int VEC = R::VEC;
   __shared__ float tb[kTileRows * kRowStride];
   __shared__ __attribute__((aligned(16))) float st[kUnitScalars];
-  const int chunk = blockIdx.x, u = blockIdx.y, f = blockIdx.z, lane = threadIdx.x;
+  const int NU = unit_cols(g) * unit_rows(g), lane = threadIdx.x;
+  int chunk, u, f;
+  if (CC) {
+    // With the cell-to-cell dot products a tile is read by two workgroups: its own frame's and the one of the frame
+    // before. Workgroups go to the eight dies round-robin by their index; each die gets a contiguous range of
+    // frames and walks it in order, so the two readers run on the same die within microseconds of each other and
+    // part of the second reads comes from that die's L2.
+    const int per_die = (g.F + 7) / 8, die = blockIdx.x & 7;
+    int slot = blockIdx.x >> 3;
+    chunk = slot % g.nC;
+    slot /= g.nC;
+    u = slot % NU;
+    const int fl = slot / NU;
+    f = die * per_die + fl;
+    if (fl >= per_die || f >= g.F) return;
+  } else {
+    chunk = blockIdx.x;
+    u = blockIdx.y;
+    f = blockIdx.z;
+  }
   const int ch0 = chunk * g.cch + lane * VEC;
   const bool act = ch0 < g.D;
   const int H = g.H, W = g.W, L = g.L;
@@ -152,6 +171,8 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
   const int y3 = (u / UX) * 8, x3 = (u % UX) * 8;
   const int vh = min(8, H - y3), vw = min(8, W - x3);  // valid rows / columns of the unit
 
+  const bool has_next = CC && f % g.T != g.T - 1;
+  const typename R::Elem* nbase = has_next ? fbase + (size_t)g.HW * g.D : fbase;
   typename R::Raw bufA[16], bufB[16];
   tile_load<DT>(bufA, fbase, W, g.D, y3, x3, min(vh, 4), min(vw, 4));
   {
@@ -171,9 +192,40 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
         tile_load<DT>((q2 & 1) ? bufA : bufB, fbase, W, g.D, none ? y3 : y3 + (n >> 1) * 4,
                       none ? x3 : x3 + (n & 1) * 4, none ? 1 : nh, none ? 1 : nw);
       }
+      if (lane < 16) st[kUnitCellDots + q2 * 16 + lane] = 0.f;
       if (th > 0 && tw > 0) {
         tile_mask<DT>((q2 & 1) ? bufB : bufA, th, tw, act);
         tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, th, tw, st + q2 * kTileRows, S2[q2]);
+        if (CC) {
+          // x_c(t) . x_c(t+1) for the tile's cells: where both frames keep single cells the temporal stage needs
+          // nothing else (Sec. 3.3 compares node features; a cell's feature is its own row). The next frame's rows
+          // are asked for only now: held across the statistics above they would not fit the register file. The
+          // last frame of a video reads its own rows again and stores zeros.
+          typename R::Raw bufN[16];
+          tile_load<DT>(bufN, nbase, W, g.D, y3 + (q2 >> 1) * 4, x3 + (q2 & 1) * 4, th, tw);
+          if (has_next) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const float d = R::dot(((q2 & 1) ? bufB : bufA)[i], bufN[i]);
+              tb[i * kRowStride + lane] = act ? d : 0.f;  // (a lane beyond the last channel read channel 0's data)
+            }
+            wave_lds_fence();
+            if (lane < 16) {
+              const int q1 = lane >> 2, k = lane & 3;
+              if ((q1 >> 1) * 2 + (k >> 1) < th && (q1 & 1) * 2 + (k & 1) < tw) {
+                const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
+                float acc = 0.f;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                  float4 q = row[j];
+                  acc += (q.x + q.y) + (q.z + q.w);
+                }
+                st[kUnitCellDots + q2 * 16 + lane] = acc;
+              }
+            }
+            wave_lds_fence();
+          }
+        }
       } else {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) S2[q2][v] = 0.f;
@@ -183,7 +235,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
       for (int v = 0; v < VEC; ++v) S3[v] += S2[q2][v];
     }
     // level-2 dot products of the four tiles with the unit's sum
-    if (lane < kUnitScalars - 4 * kTileRows) st[4 * kTileRows + lane] = 0.f;
+    if (lane < kUnitCellDots - 4 * kTileRows) st[4 * kTileRows + lane] = 0.f;
     if (L >= 3) {
 #pragma unroll
       for (int q2 = 0; q2 < 4; ++q2) {
@@ -217,7 +269,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
     // the workgroup's scalars leave in one piece: whole, aligned 128-byte lines that no other workgroup touches
     wave_lds_fence();
     if (lane < kUnitScalars / 4)
-      reinterpret_cast<float4*>(part + ((size_t)(f * g.nC + chunk) * gridDim.y + u) * kUnitScalars)[lane] =
+      reinterpret_cast<float4*>(part + ((size_t)(f * g.nC + chunk) * NU + u) * kUnitScalars)[lane] =
           reinterpret_cast<const float4*>(st)[lane];
   }
 }
@@ -269,16 +321,27 @@ __device__ inline void pyramid_upper_node(const Geo& g, float* partu, float* nsu
   }
 }
 
-void launch_pyramid_stats(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel,
+void launch_pyramid_stats(const Geo& g, const void* feats, bool cell_dots, float* part, float* nsum, SelState* sel,
                           hipStream_t s) {
-  const int UX = unit_cols(g), UY = unit_rows(g);
-  dim3 grid(g.nC, UX * UY, g.F), block(64);
-  if (g.dtype == 1)
-    hipLaunchKernelGGL(k_pyramid_stats<1>, grid, block, 0, s, g, feats, part, nsum, sel);
-  else if (g.dtype == 2)
-    hipLaunchKernelGGL(k_pyramid_stats<2>, grid, block, 0, s, g, feats, part, nsum, sel);
-  else
-    hipLaunchKernelGGL(k_pyramid_stats<0>, grid, block, 0, s, g, feats, part, nsum, sel);
+  const int NU = unit_cols(g) * unit_rows(g);
+  const dim3 block(64);
+  if (cell_dots) {
+    const dim3 grid((unsigned)(8 * ((g.F + 7) / 8) * NU * g.nC));
+    if (g.dtype == 1)
+      hipLaunchKernelGGL((k_pyramid_stats<1, true>), grid, block, 0, s, g, feats, part, nsum, sel);
+    else if (g.dtype == 2)
+      hipLaunchKernelGGL((k_pyramid_stats<2, true>), grid, block, 0, s, g, feats, part, nsum, sel);
+    else
+      hipLaunchKernelGGL((k_pyramid_stats<0, true>), grid, block, 0, s, g, feats, part, nsum, sel);
+  } else {
+    const dim3 grid(g.nC, NU, g.F);
+    if (g.dtype == 1)
+      hipLaunchKernelGGL((k_pyramid_stats<1, false>), grid, block, 0, s, g, feats, part, nsum, sel);
+    else if (g.dtype == 2)
+      hipLaunchKernelGGL((k_pyramid_stats<2, false>), grid, block, 0, s, g, feats, part, nsum, sel);
+    else
+      hipLaunchKernelGGL((k_pyramid_stats<0, false>), grid, block, 0, s, g, feats, part, nsum, sel);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -66,7 +66,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __restrict__ feats_v,
                                                        const uint8_t* __restrict__ node_level,
                                                        const float* __restrict__ nsum,
-                                                       float* __restrict__ pd_part,
+                                                       int skip_cells, float* __restrict__ pd_part,
                                                        SelState* __restrict__ sel) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
@@ -102,7 +102,8 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
     const int y = c / W, x = c - y * W;
     const bool join_head = !(y & ((1 << J) - 1)) && !(x & ((1 << J) - 1));
     if (J <= 1) {
-      if (!(y & 1) && !(x & 1)) fast[atomicAdd(&nfast, 1)] = (int16_t)c;
+      // (a region of single cells in both frames has nothing to do when the spatial pass left those dot products)
+      if (!(y & 1) && !(x & 1) && (J == 1 || !skip_cells)) fast[atomicAdd(&nfast, 1)] = (int16_t)c;
     } else if (J == 2) {
       if (join_head) mid[atomicAdd(&nmid, 1)] = (int16_t)c;
     } else {
@@ -375,7 +376,7 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
 __global__ __launch_bounds__(256) void k_select_clear_all(SelState* st) { sel_clear(st + blockIdx.x); }
 
 void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
-                          float* pd_part, SelState* sel, hipStream_t s) {
+                          bool skip_cells, float* pd_part, SelState* sel, hipStream_t s) {
   if (g.T < 2) {  // no frame pairs: only the search states have to be reset
     hipLaunchKernelGGL(k_select_clear_all, dim3(g.B), dim3(256), 0, s, sel);
     return;
@@ -385,11 +386,14 @@ void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_l
   const int U = g.P >= 8 ? g.P >> 3 : 1;
   const size_t lds = g.L >= 3 ? (size_t)U * U * g.cch * sizeof(float) : 0;
   if (g.dtype == 1)
-    hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
+    hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, lds, s, g, feats, node_level, nsum, (int)skip_cells, pd_part,
+                       sel);
   else if (g.dtype == 2)
-    hipLaunchKernelGGL(k_temporal_dots<2>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
+    hipLaunchKernelGGL(k_temporal_dots<2>, grid, block, lds, s, g, feats, node_level, nsum, (int)skip_cells, pd_part,
+                       sel);
   else
-    hipLaunchKernelGGL(k_temporal_dots<0>, grid, block, lds, s, g, feats, node_level, nsum, pd_part, sel);
+    hipLaunchKernelGGL(k_temporal_dots<0>, grid, block, lds, s, g, feats, node_level, nsum, (int)skip_cells, pd_part,
+                       sel);
 }
 
 __device__ inline int node_idx_of(const Geo& g, int lvl, int y0, int x0) {
@@ -425,6 +429,7 @@ __device__ inline void load_pair_frame(const Geo& g, int f, const int32_t* node_
 __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, int match, const int32_t* __restrict__ node_map,
                                                           const uint8_t* __restrict__ node_level,
                                                           const float* __restrict__ pd_part,
+                                                          const float* __restrict__ cell_part,
                                                           const float* __restrict__ nrm2,
                                                           float* __restrict__ sig, float* __restrict__ e,
                                                           uint32_t* __restrict__ sel_key,
@@ -450,10 +455,18 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, int match, cons
     const float nd = nrm2[(size_t)(f - 1) * g.NN + node_idx_of(g, b, d / W, d % W)];
     float dot = 0.f;
     const float* pp = pd_part + (size_t)f * g.nC * HW + c;
+    size_t cstride = HW;  // from one chunk's partial to the next
+    if (cell_part && a == 0 && b == 0) {
+      // two single cells: the spatial pass of frame t-1 left the dot product with the same cell of frame t
+      const int y = c / W, x = c - y * W, NU = unit_cols(g) * unit_rows(g);
+      cstride = (size_t)NU * kUnitScalars;
+      pp = cell_part + ((size_t)(f - 1) * g.nC * NU + (y >> 3) * unit_cols(g) + (x >> 3)) * kUnitScalars +
+           unit_cell_dot_slot(y, x);
+    }
     for (int k0 = 0; k0 < g.nC; k0 += 8) {
       float pv[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) pv[u] = k0 + u < g.nC ? pp[(size_t)(k0 + u) * HW] : 0.f;
+      for (int u = 0; u < 8; ++u) pv[u] = k0 + u < g.nC ? pp[(size_t)(k0 + u) * cstride] : 0.f;
 #pragma unroll
       for (int u = 0; u < 8; ++u) dot += pv[u];
     }
@@ -481,10 +494,10 @@ __global__ __launch_bounds__(256) void k_temporal_resolve(Geo g, int match, cons
 }
 
 void launch_temporal_resolve(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
-                             const float* pd_part, const float* nrm2, float* sig, float* e, uint32_t* sel_key,
-                             SelState* sel, hipStream_t s) {
-  hipLaunchKernelGGL(k_temporal_resolve, dim3(g.F), dim3(256), 0, s, g, match, node_map, node_level, pd_part, nrm2, sig,
-                     e, sel_key, sel);
+                             const float* pd_part, const float* cell_part, const float* nrm2, float* sig, float* e,
+                             uint32_t* sel_key, SelState* sel, hipStream_t s) {
+  hipLaunchKernelGGL(k_temporal_resolve, dim3(g.F), dim3(256), 0, s, g, match, node_map, node_level, pd_part, cell_part,
+                     nrm2, sig, e, sel_key, sel);
 }
 
 // ------------------------------------------------------------------------------------------------

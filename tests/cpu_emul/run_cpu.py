@@ -38,7 +38,7 @@ def load():
 
 
 def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, lib=None, use_nodes=True,
-            match=0, order=0, positions=False, defer_tau=False):
+            match=0, order=0, positions=False, defer_tau=False, cell_dots=1):
     lib = lib or load()
     B, T, H, W, D = feats.shape
     dt = STTM_BF16 if feats.dtype == np.uint16 else (STTM_F16 if feats.dtype == np.float16 else STTM_F32)
@@ -52,6 +52,7 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
 
     chk(lib.sttm_set_match_mode(h, match))
     chk(lib.sttm_set_output_order(h, order))
+    chk(lib.sttm_set_cell_dots(h, cell_dots))
     need = lib.sttm_workspace_bytes(B, T, H, W, D, dt, root_grid)
     ws = _aligned(need, garbage=True)
     chk(lib.sttm_set_workspace(h, _p(ws), C.c_size_t(need)))

@@ -56,7 +56,7 @@ ORDERS = {"raster": 0, "zscan": 1}
 def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_grid: int = 1,
             out_dtype: Optional[int] = None, node_map_override=None, ctx=None, feats_dev=None,
             use_nodes: bool = True, mode: str = "first_passing", order: str = "raster",
-            positions: bool = False) -> GpuResult:
+            positions: bool = False, cell_dots: int = 1) -> GpuResult:
     """Whole path through the C ABI. Fixed thresholds, or `keep` (budget mode)."""
     import torch
     B, T, H, W, D = feats.shape
@@ -67,6 +67,7 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     s = ctx or lib.Sttm(0)
     s.sttm_set_match_mode(MODES[mode])
     s.sttm_set_output_order(ORDERS[order])
+    s.sttm_set_cell_dots(cell_dots)
     s.ensure_workspace(B, T, H, W, D, dt, root_grid)
     N = B * T * H * W
     NN = lib.sttm_nodes_per_frame(H, W, root_grid)

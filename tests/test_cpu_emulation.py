@@ -76,3 +76,16 @@ def test_emulated_budget_threshold_left_to_the_consumer_kernels(emul):
     assert (a.node_map == b.node_map).all() and (a.cluster_ids == b.cluster_ids).all()
     assert (a.parent == b.parent).all() and a.K == b.K
     np.testing.assert_array_equal(a.merged, b.merged)
+
+
+@pytest.mark.parametrize("kw", [dict(keep=0.5), dict(tau_s=0.95, tau_t=0.6)])
+def test_emulated_temporal_pass_without_the_cell_dot_products(emul, kw):
+    """With the option off the temporal pass computes every pair itself: same partition and clusters as with the
+    cell-to-cell dot products of the spatial pass, and parity with the oracle either way."""
+    run_cpu, fake = emul
+    feats = wl.generate(_variant(98, 2, 4, 9, 7, 24, "bf16"))
+    a = run_cpu.run_cpu(feats, **kw)
+    b = run_cpu.run_cpu(feats, cell_dots=0, **kw)
+    assert (a.node_map == b.node_map).all() and (a.cluster_ids == b.cluster_ids).all() and a.K == b.K
+    P.check_parity(fake, feats, a, **kw)
+    P.check_parity(fake, feats, b, **kw)

@@ -413,6 +413,43 @@ def test_positions_and_settings_error_paths(lib):
     assert e.value.code == lib.STTM_ERR_STATE
 
 
+@pytest.mark.parametrize("seed,B,T,H,W,D,dtype,kw", [
+    (70, 2, 6, 13, 13, 136, "bf16", dict(keep=0.5)),
+    (71, 1, 5, 16, 16, 64, "f32", dict(tau_s=0.95, tau_t=0.6)),
+    (72, 1, 4, 14, 14, 520, "f16", dict(tau_s=0.7, tau_t=0.7, root_grid=4)),
+])
+def test_temporal_pass_without_the_cell_dot_products(lib, seed, B, T, H, W, D, dtype, kw):
+    """sttm_set_cell_dots(0): the temporal pass computes the cell-to-cell pairs itself. Parity with the oracle, and
+    the same partition and clusters as with the option on."""
+    feats = wl.generate(_variant(seed, B, T, H, W, D, dtype))
+    print(f"case seed={seed} shape={feats.shape} dtype={feats.dtype} {kw}", flush=True)
+    s = lib.Sttm(0)
+    off = P.run_gpu(lib, feats, ctx=s, cell_dots=0, **kw)
+    P.check_parity(lib, feats, off, **kw)
+    on = P.run_gpu(lib, feats, ctx=s, cell_dots=1, **kw)     # same context: the setting applies to the next pass
+    assert (on.node_map == off.node_map).all() and (on.cluster_ids == off.cluster_ids).all() and on.K == off.K
+    P.check_parity(lib, feats, on, **kw)
+
+
+def test_cell_dot_setting_and_feature_pointer_error_paths(lib):
+    import torch
+    s = lib.Sttm(0)
+    with pytest.raises(lib.SttmError) as e:
+        s.sttm_set_cell_dots(2)
+    assert e.value.code == lib.STTM_ERR_ARG
+    cfg = wl.CONFIGS[0]
+    feats = wl.generate(cfg)
+    r = P.run_gpu(lib, feats, tau_s=cfg.tau_s, tau_t=cfg.tau_t, ctx=s)
+    nm = torch.from_numpy(r.node_map.reshape(-1)).cuda()
+    cl = torch.zeros(cfg.n_tokens, dtype=torch.int32, device="cuda:0")
+    other = r.feats_dev.clone()                                   # same values, another buffer
+    with pytest.raises(lib.SttmError) as e:                        # the statistics belong to r.feats_dev
+        s.sttm_temporal_merge(other, nm, None, [cfg.tau_t], cl)
+    assert e.value.code == lib.STTM_ERR_STATE
+    s.sttm_temporal_merge(r.feats_dev, nm, None, [cfg.tau_t], cl)
+    assert (cl.cpu().numpy() == r.cluster_ids.reshape(-1)).all()
+
+
 def test_config3_long_video_most_similar_zscan_positions(lib):
     """The bench workload once more under the alternative rule and scan, with position indices."""
     cfg = wl.CONFIGS[3]
