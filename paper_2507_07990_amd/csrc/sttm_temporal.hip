@@ -71,6 +71,7 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
   STTM_DYNAMIC_LDS(float, bigS);  // [big join blocks][cch]
+  __shared__ int8_t slot_of[24];  // node at a level >= 3 (counted from the first level-3 node) -> its row of bigS
   __shared__ uint8_t lvl_t[1024], lvl_p[1024];
   __shared__ int16_t fast[256], mid[64], bighead[16], pairs0[1024], pairsX[512];
   __shared__ int nfast, nmid, nbig, n0, nX;
@@ -109,7 +110,8 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
     } else {
       if (join_head) bighead[atomicAdd(&nbig, 1)] = (int16_t)c;
       if (!(y & ((1 << lf) - 1)) && !(x & ((1 << lf) - 1))) {  // top-left cell of the finer node
-        if (lf == 0) pairs0[atomicAdd(&n0, 1)] = (int16_t)c;
+        // packed: x (5 bits), y (5), join level (3), whether the cell is frame t's (1)
+        if (lf == 0) pairs0[atomicAdd(&n0, 1)] = (int16_t)(x | (y << 5) | (J << 10) | ((a < bb ? 1 : 0) << 13));
         else pairsX[atomicAdd(&nX, 1)] = (int16_t)c;
       }
     }
@@ -130,7 +132,9 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
     const int a = lvl_t[c], bb = lvl_p[c];
     const int J = max(a, bb), y = c / W, x = c - y * W;
     const int fc = a >= bb ? f : f - 1;  // frame in which the join block is one node
-    const float* row = nsum + ((size_t)fc * NB + node_index(g, J, y >> J, x >> J) - g.lvl_base[3]) * g.D;
+    const int nid = node_index(g, J, y >> J, x >> J) - g.lvl_base[3];
+    const float* row = nsum + ((size_t)fc * NB + nid) * g.D;
+    if (threadIdx.x == 0) slot_of[nid] = (int8_t)s;  // where the pairs under this block find its sum
     for (int cc = threadIdx.x; cc < g.cch; cc += blockDim.x) {
       const int ch = chunk * g.cch + cc;
       bigS[s * g.cch + cc] = ch < g.D ? row[ch] : 0.f;
@@ -230,9 +234,9 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
         const int pi = base + half * 8 + jj;
         r[jj] = R::zero();
         if (pi < np0 && act) {
-          const int q = pairs0[pi];
-          const typename R::Elem* fine = lvl_t[q] < lvl_p[q] ? ft : fp;
-          r[jj] = *reinterpret_cast<const typename R::Raw*>(fine + (size_t)q * g.D);
+          const int e = pairs0[pi];
+          const typename R::Elem* fine = (e >> 13) ? ft : fp;
+          r[jj] = *reinterpret_cast<const typename R::Raw*>(fine + (size_t)(((e >> 5) & 31) * W + (e & 31)) * g.D);
         }
       }
 #pragma unroll
@@ -240,15 +244,12 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
         const int pi = base + half * 8 + jj;
         float d = 0.f;
         if (pi < np0) {
-          const int q = pairs0[pi];
-          const int J = max(lvl_t[q], lvl_p[q]);
-          const int y = q / W, x = q - y * W;
-          const int cM = ((y >> J) << J) * W + ((x >> J) << J);
-          int slot = 0;
-          for (int s = 0; s < nb; ++s) slot = bighead[s] == cM ? s : slot;
+          const int e = pairs0[pi];
+          const int J = (e >> 10) & 7;
+          const int nid = node_index(g, J, ((e >> 5) & 31) >> J, (e & 31) >> J) - g.lvl_base[3];
           float xv[VEC];
           R::unpack(r[jj], xv);
-          const float* sm = bigS + slot * g.cch + lane * VEC;
+          const float* sm = bigS + slot_of[nid] * g.cch + lane * VEC;
 #pragma unroll
           for (int v = 0; v < VEC; ++v) d = fmaf(xv[v], sm[v], d);
         }
@@ -264,7 +265,10 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
         const float4 q = row[jj];
         acc += (q.x + q.y) + (q.z + q.w);
       }
-      if (base + lane < np0) out[pairs0[base + lane]] = acc;
+      if (base + lane < np0) {
+        const int e = pairs0[base + lane];
+        out[((e >> 5) & 31) * W + (e & 31)] = acc;
+      }
     }
     wave_lds_fence();
   }
@@ -276,9 +280,7 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
     const int a = lvl_t[q], bb = lvl_p[q];
     const int J = max(a, bb), lf = min(a, bb);
     const int y = q / W, x = q - y * W;
-    const int cM = ((y >> J) << J) * W + ((x >> J) << J);
-    int slot = 0;
-    for (int s = 0; s < nb; ++s) slot = bighead[s] == cM ? s : slot;
+    const int nid = node_index(g, J, y >> J, x >> J) - g.lvl_base[3];
     float SB[VEC];
     if (lf >= 3) {
       // when the levels are equal the join block is frame t's node (staged), the finer one is frame t-1's
@@ -289,7 +291,7 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
     } else {
       block_sum<DT>(a < bb ? ft : fp, g.D, H, W, y, x, 1 << lf, act, SB);
     }
-    const float* sm = bigS + slot * g.cch + lane * VEC;
+    const float* sm = bigS + slot_of[nid] * g.cch + lane * VEC;
     float d = 0.f;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) d = fmaf(SB[v], sm[v], d);
@@ -383,7 +385,7 @@ void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_l
   }
   const int per_die = (g.B * (g.T - 1) + 7) / 8;
   dim3 grid(8 * per_die * g.nC), block(256);
-  const int U = g.P >= 8 ? g.P >> 3 : 1;
+  const int U = g.P >= 8 ? g.P >> 3 : 1;  // at most U x U disjoint join blocks at levels >= 3
   const size_t lds = g.L >= 3 ? (size_t)U * U * g.cch * sizeof(float) : 0;
   if (g.dtype == 1)
     hipLaunchKernelGGL(k_temporal_dots<1>, grid, block, lds, s, g, feats, node_level, nsum, (int)skip_cells, pd_part,
