@@ -223,40 +223,38 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
     wave_lds_fence();
   }
 
-  // ---- big pairs whose finer node is one cell: sixteen per batch and wavefront. The list entries are read first, then
-  //      all sixteen rows are requested, then the dot products are formed in registers and written to the reduction
-  //      buffer together (no LDS store between the look-ups, so the compiler is free to overlap them).
+  // ---- big pairs whose finer node is one cell: sixteen per batch and wavefront, in stages without branches: the list
+  //      entries (a position beyond the list's end repeats the batch's first entry and is dropped at the end), the
+  //      sixteen row loads, the places of the coarse sums, then the dot products -- so that the look-ups of different
+  //      pairs overlap instead of forming one chain per pair.
   const int np0 = min(n0, 1024);
   for (int base = wave * 16; base < np0; base += 64) {
     int ent[16];
 #pragma unroll
-    for (int jj = 0; jj < 16; ++jj) ent[jj] = base + jj < np0 ? (int)pairs0[base + jj] : -1;
+    for (int jj = 0; jj < 16; ++jj) ent[jj] = pairs0[min(base + jj, np0 - 1)];
     typename R::Raw r[16];
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) {
       const int e = ent[jj];
-      r[jj] = R::zero();
-      if (e >= 0 && act) {
-        const typename R::Elem* fine = (e >> 13) ? ft : fp;
-        r[jj] = *reinterpret_cast<const typename R::Raw*>(fine + (size_t)(((e >> 5) & 31) * W + (e & 31)) * g.D);
-      }
+      const typename R::Elem* fine = (e >> 13) ? ft : fp;
+      r[jj] = *reinterpret_cast<const typename R::Raw*>(fine + (size_t)(((e >> 5) & 31) * W + (e & 31)) * g.D);
+    }
+    int srow[16];
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) {
+      const int e = ent[jj], J = (e >> 10) & 7;
+      srow[jj] = slot_of[node_index(g, J, ((e >> 5) & 31) >> J, (e & 31) >> J) - g.lvl_base[3]];
     }
     float dv[16];
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) {
-      const int e = ent[jj];
-      dv[jj] = 0.f;
-      if (e >= 0) {
-        const int J = (e >> 10) & 7;
-        const int nid = node_index(g, J, ((e >> 5) & 31) >> J, (e & 31) >> J) - g.lvl_base[3];
-        float xv[VEC];
-        R::unpack(r[jj], xv);
-        const float* sm = bigS + slot_of[nid] * g.cch + lane * VEC;
-        float d = 0.f;
+      float xv[VEC];
+      R::unpack(r[jj], xv);
+      const float* sm = bigS + srow[jj] * g.cch + lane * VEC;
+      float d = 0.f;
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) d = fmaf(xv[v], sm[v], d);
-        dv[jj] = d;
-      }
+      for (int v = 0; v < VEC; ++v) d = fmaf(xv[v], sm[v], d);
+      dv[jj] = (act && base + jj < np0) ? d : 0.f;
     }
 #pragma unroll
     for (int jj = 0; jj < 16; ++jj) tb[jj * 68 + lane] = dv[jj];
