@@ -101,6 +101,10 @@ __device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>:
     for (int v = 0; v < VEC; ++v) d1 = fmaf(S1[q1][v], S2[v], d1);
     tb[(32 + q1) * kRowStride + lane] = d1;
   }
+}
+
+// Second half of a tile's statistics: adds the per-lane scalars up across the wavefront and leaves them in `st`.
+__device__ __forceinline__ void tile_stats_reduce(const Geo& g, float* tb, int lane, int th, int tw, float* st) {
   wave_lds_fence();
   if (lane < kTileRows) {
     // which node / table does row `lane` belong to
@@ -196,6 +200,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
       if (th > 0 && tw > 0) {
         tile_mask<DT>((q2 & 1) ? bufB : bufA, th, tw, act);
         tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, th, tw, st + q2 * kTileRows, S2[q2]);
+        if (!CC) tile_stats_reduce(g, tb, lane, th, tw, st + q2 * kTileRows);
         if (CC) {
           // x_c(t) . x_c(t+1) for the tile's cells: where both frames keep single cells the temporal stage needs
           // nothing else (Sec. 3.3 compares node features; a cell's feature is its own row). The next frame's rows
@@ -203,6 +208,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
           // last frame of a video reads its own rows again and stores zeros.
           typename R::Raw bufN[16];
           tile_load<DT>(bufN, nbase, W, g.D, y3 + (q2 >> 1) * 4, x3 + (q2 & 1) * 4, th, tw);
+          tile_stats_reduce(g, tb, lane, th, tw, st + q2 * kTileRows);  // (the rows above travel meanwhile)
           if (has_next) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
