@@ -138,7 +138,9 @@ int sttm_spatial_quadtree(sttm_ctx* ctx, const void* feats_dev, int dtype, int B
 
 /* Similarities between every kept node of frame t >= 1 and each overlapping kept node of frame t-1, and the best
  * one per node (tables PAIR_SIM, BEST_SIM). node_map / node_level as produced by stage 1 (any valid quadtree
- * partition per frame is accepted). Needs the stage-1 statistics of the same feats in the workspace. Asynchronous. */
+ * partition per frame is accepted). Needs the stage-1 statistics of the same feats in the workspace: feats_dev must
+ * be the buffer the last statistics pass read (STTM_ERR_STATE otherwise; the norms, the sums of large nodes and the
+ * cell-to-cell dot products come from that pass). Asynchronous. */
 int sttm_temporal_stats(sttm_ctx* ctx, const void* feats_dev, const int32_t* node_map_dev,
                         const uint8_t* node_level_dev);
 
