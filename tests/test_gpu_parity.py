@@ -19,11 +19,12 @@ def _variant(seed, B, T, H, W, D, dtype, **kw):
     return wl.Workload("v", seed, B, T, H, W, D, dtype, depth, base.pop("sigma"), base.pop("persist"), **base)
 
 
-def _run_and_check(lib, cfg, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None):
+def _run_and_check(lib, cfg, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, cell_dots=1):
     feats = wl.generate(cfg)
     print(f"case {cfg.name} seed={cfg.seed} shape={feats.shape} dtype={feats.dtype} tau=({tau_s},{tau_t}) "
-          f"keep={keep} R={root_grid}", flush=True)
-    r = P.run_gpu(lib, feats, tau_s=tau_s, tau_t=tau_t, keep=keep, root_grid=root_grid, out_dtype=out_dtype)
+          f"keep={keep} R={root_grid} cell_dots={cell_dots}", flush=True)
+    r = P.run_gpu(lib, feats, tau_s=tau_s, tau_t=tau_t, keep=keep, root_grid=root_grid, out_dtype=out_dtype,
+                  cell_dots=cell_dots)
     out_bf16 = (out_dtype == lib.STTM_BF16) if out_dtype is not None else None
     info = P.check_parity(lib, feats, r, tau_s=tau_s, tau_t=tau_t, keep=keep, root_grid=root_grid,
                           out_is_bf16=out_bf16, out_is_f16=out_dtype == lib.STTM_F16)
@@ -472,10 +473,11 @@ def test_config2_encoder_width_budget(lib):
     _run_and_check(lib, cfg, keep=cfg.budgets[0])
 
 
-@pytest.mark.parametrize("keep", [0.5, 0.3])
-def test_config3_long_video_budget(lib, keep):
+@pytest.mark.parametrize("keep,cell_dots", [(0.5, 1), (0.3, 1), (0.5, 0)])
+def test_config3_long_video_budget(lib, keep, cell_dots):
+    """The bench workload at both budgets; once more with the spatial and temporal passes kept separate."""
     cfg = wl.CONFIGS[3]
-    _run_and_check(lib, cfg, keep=keep)
+    _run_and_check(lib, cfg, keep=keep, cell_dots=cell_dots)
 
 
 @pytest.mark.parametrize("index,keep,frames", [(5, 0.3, 180), (6, 0.5, 40)])
