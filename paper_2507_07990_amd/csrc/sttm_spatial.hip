@@ -7,8 +7,9 @@ namespace sttm {
 // ------------------------------------------------------------------------------------------------
 // k_pyramid_stats: the one pass over the features of the spatial stage.
 //
-// Grid (chunk, unit, frame); a workgroup is ONE wavefront that owns a "unit" = an 8x8 cell block (level 3)
-// of one frame for one chunk of the token rows. Units at the ragged edge of the grid are smaller, but every
+// One workgroup per (chunk, unit, frame) -- a 3-D grid, or a 1-D grid decoded die by die when the cell-to-cell dot
+// products are wanted (template parameter CC, see below); a workgroup is ONE wavefront that owns a "unit" = an 8x8
+// cell block (level 3) of one frame for one chunk of the token rows. Units at the ragged edge of the grid are smaller, but every
 // workgroup is a single wavefront, so the hardware dispatcher evens the load out. A lane owns VEC
 // consecutive channels, so all pyramid sums are private to the lane and only scalars are reduced across
 // lanes: the wavefront stages its per-lane partial scalars in LDS as [scalar][lane] and then lets lane r
@@ -20,9 +21,12 @@ namespace sttm {
 // Scalars: the squared norm of every cell, and for every node below the root the dot product of its sum
 // with its parent's sum. (The squared norm of a parent is the sum of its children's dot products with it,
 // which the finalize kernel adds up.)
-// Output: part[f][chunk][0][cell node] = partial squared norm over this chunk's channels,
-//         part[f][chunk][1][node]      = partial dot product of the node's sum with its parent's sum
-//         (levels 0..2 here; level 3 and above by the finalize kernel when the pyramid is taller than a unit),
+// With CC the wavefront also reads each tile of the next frame and forms x_c(t) . x_c(t+1) for the tile's cells (the
+// dot products the temporal stage needs where both frames keep single cells).
+// Output: part[f][chunk][unit][kUnitScalars] = the workgroup's scalars, partial over this chunk's channels, written
+//         as one block: per tile 16 squared norms, 16 cell and 4 level-1 dot products (child sum . parent sum), then
+//         the 4 level-2 dot products, then per tile the 16 cell-to-cell dot products (zeros without CC); the levels
+//         from 3 up are the finalize kernel's when the pyramid is taller than a unit;
 //         nsum[f][node - first level-3 node][D] = the per-channel sums of the level-3 nodes (fp32), which
 //         the later stages read instead of re-adding up to 64 token rows.
 // ------------------------------------------------------------------------------------------------
@@ -58,8 +62,8 @@ __device__ __forceinline__ void tile_mask(typename Row<DT>::Raw (&raw)[16], int 
   }
 }
 
-// Sums and scalars of one tile; returns the tile's per-channel sum in S2. Writes the scalars of the tile's
-// cells and level-1 blocks to the per-chunk tables.
+// Sums and per-lane scalars of one tile; returns the tile's per-channel sum in S2 and leaves the lanes' partial
+// scalars of the tile's cells and level-1 blocks in the reduction buffer (tile_stats_reduce adds them up).
 template <int DT>
 __device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>::Raw (&raw)[16], float* tb,
                                            int lane, int th, int tw, float* st, float (&S2)[Row<DT>::VEC]) {

@@ -48,13 +48,14 @@ __device__ inline void block_sum(const typename Row<DT>::Elem* fb, int D, int H,
 // listed per workgroup by join level J:
 //  * J <= 1 ("fast"): aligned 2x2 regions in which both frames' nodes are single cells or the 2x2 block.
 //    A wavefront loads the 4+4 cells of two regions at once (16 rows in flight) and emits up to four dot
-//    products per region.
+//    products per region. With `skip_cells` the regions of single cells in both frames are left out: the spatial
+//    pass has already formed those dot products (k_temporal_resolve reads them from its table).
 //  * J == 2 ("mid"): a wavefront sums the 4x4 block in the frame where it is one node, then dots every cell
 //    of the other frame's block with that sum; a finer node's dot product is the sum over its cells.
 //  * J >= 3 ("big"): the coarse sum is not recomputed: the spatial pass left the per-channel sums of all
 //    nodes at levels >= 3 in `nsum`; the workgroup stages the rows it needs in LDS. Pairs whose finer
-//    node is a single cell are handled 8 rows at a time, the others one by one (finer nodes at levels
-//    >= 3 also come from `nsum`).
+//    node is a single cell are handled sixteen at a time (their list entries carry the cell, the join level and
+//    the frame the cell belongs to), the others one by one (finer nodes at levels >= 3 also come from `nsum`).
 // Per-lane partial dot products are reduced across the wavefront through LDS ([scalar][lane] rows).
 // Frame pairs are visited last-to-first: the spatial pass before it reads frames first-to-last, so the
 // tail of the video may still sit in the memory-side cache.
