@@ -105,6 +105,13 @@ size_t sttm_workspace_bytes(int B, int T, int H, int W, int D, int dtype, int ro
  * sttm_set_workspace / sttm_destroy. Tables of earlier stages live there between calls. */
 int sttm_set_workspace(sttm_ctx* ctx, void* workspace_dev, size_t bytes);
 
+/* The library recognises "the same features / node map as before" by the device pointer alone: it cannot see a
+ * buffer being rewritten in place. A caller that overwrites feats, node_map or cluster_ids in place between two
+ * calls of one pass over a video calls sttm_invalidate() first: every table a later stage would reuse (statistics,
+ * thresholds, node sums, the reduce call's lists) is then treated as absent, and the stages that need them return
+ * STTM_ERR_STATE until they are computed again. Host-side only; the workspace itself is left alone. */
+int sttm_invalidate(sttm_ctx* ctx);
+
 /* Destination rule of the temporal stage (sttm_match); applies to the temporal calls that follow. With
  * STTM_MATCH_TOPLEFT_ONLY the table BEST_SIM and the temporal budget use the similarity to that one destination. */
 int sttm_set_match_mode(sttm_ctx* ctx, int mode);
@@ -146,7 +153,9 @@ int sttm_temporal_stats(sttm_ctx* ctx, const void* feats_dev, const int32_t* nod
 
 /* Directed edges (similarity > tau_T, top-left-most passing destination), then the common root of every chain.
  * tau_t: host array of B thresholds, or NULL = those chosen by sttm_budget_threshold(STTM_STAGE_TEMPORAL).
- * With tau_t != NULL the temporal statistics are (re)computed first; with NULL they must be in the workspace.
+ * With tau_t != NULL the temporal statistics are (re)computed first; with NULL they must be in the workspace and
+ * node_map_dev must be the node map they were computed for (STTM_ERR_STATE otherwise). A new statistics pass
+ * (sttm_temporal_stats) discards the threshold of an earlier budget search.
  * Output (device): cluster_ids int32 [B,T,H,W] = flat index of the top-left cell of the root node of the cell's
  * cluster (= the smallest flat index in the cluster). Asynchronous. */
 int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* node_map_dev,

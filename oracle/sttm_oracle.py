@@ -110,12 +110,17 @@ class Grid:
 
 
 def cosine(a: np.ndarray, b: np.ndarray) -> float:
-    """cos(a, b) clamped to <= 1; 0 when either vector has zero norm."""
-    na = math.sqrt(float(np.dot(a, a)))
-    nb = math.sqrt(float(np.dot(b, b)))
-    if na == 0.0 or nb == 0.0:
-        return 0.0
-    return min(1.0, float(np.dot(a, b)) / (na * nb))
+    """cos(a, b) clamped to <= 1; 0 when either vector has zero norm; NaN when an input holds a NaN or an infinity
+    (such a similarity never exceeds a threshold)."""
+    with np.errstate(invalid="ignore", over="ignore"):
+        na = math.sqrt(float(np.dot(a, a)))
+        nb = math.sqrt(float(np.dot(b, b)))
+        if na == 0.0 or nb == 0.0:
+            return 0.0
+        c = float(np.dot(a, b)) / (na * nb)
+    if c != c:
+        return math.nan
+    return min(1.0, c)
 
 
 # ----------------------------------------------------------------------------
@@ -173,7 +178,7 @@ def child_similarities(mean, cnt, grid: Grid, counter: Optional[List[int]] = Non
                     vals.append(s[by, bx, k])
                     if counter is not None:
                         counter[0] += 1
-                mm[by, bx] = min(vals)
+                mm[by, bx] = math.nan if any(v != v for v in vals) else min(vals)   # an undefined similarity splits
         sims.append(s)
         m.append(mm)
     return sims, m
@@ -242,7 +247,8 @@ def split_scores(m, grid: Grid):
     def visit(lvl, by, bx, above):
         if lvl == 0 or not grid.exists(lvl, by, bx):
             return
-        s = max(above, float(m[lvl][by, bx]))
+        mv = float(m[lvl][by, bx])
+        s = max(above, -2.0 if mv != mv else mv)          # an undefined m splits at every threshold
         kids = sum(grid.exists(lvl - 1, 2 * by + dy, 2 * bx + dx) for dy in (0, 1) for dx in (0, 1))
         out.append((s, kids))
         for dy in (0, 1):
@@ -416,8 +422,10 @@ def best_similarity(cands, node_map: np.ndarray, mode: str = "first_passing"):
         if mode == "topleft_only":
             d0 = int(flat[n - HW])            # the kept node of frame t-1 covering n's top-left cell
             e[n] = dict(lst)[d0]
+            if e[n] != e[n]:
+                e[n] = -2.0
         else:
-            e[n] = max(s for _, s in lst)
+            e[n] = max([s for _, s in lst if s == s], default=-2.0)   # undefined similarities never link
     return e
 
 

@@ -29,7 +29,7 @@ EXPORTS = [
     "sttm_workspace_bytes", "sttm_set_workspace", "sttm_spatial_stats", "sttm_spatial_quadtree",
     "sttm_temporal_stats", "sttm_temporal_merge", "sttm_budget_threshold", "sttm_reduce", "sttm_export",
     "sttm_profile_enable", "sttm_profile_read", "sttm_set_match_mode", "sttm_set_output_order", "sttm_positions",
-    "sttm_set_cell_dots",
+    "sttm_set_cell_dots", "sttm_invalidate",
 ]
 STTM_MATCH_FIRST_PASSING, STTM_MATCH_TOPLEFT_ONLY, STTM_MATCH_MOST_SIMILAR = 0, 1, 2
 STTM_ORDER_RASTER, STTM_ORDER_ZSCAN = 0, 1
@@ -64,6 +64,7 @@ def _load() -> C.CDLL:
     lib.sttm_set_match_mode.argtypes = [vp, i]
     lib.sttm_set_output_order.argtypes = [vp, i]
     lib.sttm_set_cell_dots.argtypes = [vp, i]
+    lib.sttm_invalidate.argtypes = [vp]
     lib.sttm_positions.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     return lib
 
@@ -183,6 +184,9 @@ class Sttm:
 
     def sttm_set_output_order(self, order: int):
         self._check(_lib.sttm_set_output_order(self._h, order))
+
+    def sttm_invalidate(self):
+        self._check(_lib.sttm_invalidate(self._h))
 
     def sttm_set_cell_dots(self, on: int):
         self._check(_lib.sttm_set_cell_dots(self._h, on))

@@ -247,6 +247,9 @@ int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, 
                           at<float>(c, c->lay.sig), at<float>(c, c->lay.e), at<uint32_t>(c, c->lay.sel_key_t),
                           at<SelState>(c, c->lay.sel_t), c->stream);
   int rc = after_launch(c);
+  // the search state of the temporal budget starts afresh with these statistics: a threshold chosen from the
+  // statistics before them (or a last digit still pending) no longer applies
+  c->have_tau_t = c->tau_t_pending = false;
   if (rc == STTM_OK) {
     c->sel_t_dirty = false;
     c->have_temporal = true;
@@ -321,6 +324,17 @@ int sttm_set_workspace(sttm_ctx* ctx, void* workspace_dev, size_t bytes) {
   ctx->ws_bytes = bytes;
   ctx->bound = false;
   ctx->have_spatial = ctx->have_tau_s = ctx->have_temporal = ctx->have_tau_t = false;
+  ctx->cluster_ids_reduced = nullptr;
+  return STTM_OK;
+}
+
+int sttm_invalidate(sttm_ctx* ctx) {
+  if (!ctx) return STTM_ERR_NULL;
+  ctx->have_spatial = ctx->have_tau_s = ctx->have_temporal = ctx->have_tau_t = false;
+  ctx->tau_s_pending = ctx->tau_t_pending = false;
+  ctx->have_cell_dots = false;
+  ctx->feats_spatial = nullptr;
+  ctx->node_map_temporal = nullptr;
   ctx->cluster_ids_reduced = nullptr;
   return STTM_OK;
 }
@@ -427,15 +441,16 @@ int sttm_temporal_merge(sttm_ctx* ctx, const void* feats_dev, const int32_t* nod
   if (tau_t_host) {
     rc = upload_tau(ctx, tau_t_host, at<float>(ctx, ctx->lay.tau_t), &ctx->h_tau_t);
     if (rc) return rc;
-    ctx->have_tau_t = true;
-    ctx->tau_t_pending = false;
     rc = run_temporal_stats(ctx, feats_dev, node_map_dev, node_level_dev);
     if (rc) return rc;
+    ctx->have_tau_t = true;
   } else {
     if (!ctx->have_temporal)
       return fail(ctx, STTM_ERR_STATE, "no temporal statistics in the workspace (call sttm_temporal_stats first)");
     if (!ctx->have_tau_t)
       return fail(ctx, STTM_ERR_STATE, "no temporal threshold chosen (call sttm_budget_threshold first)");
+    if (node_map_dev != ctx->node_map_temporal)
+      return fail(ctx, STTM_ERR_STATE, "the temporal statistics in the workspace were computed for another node map");
   }
   launch_temporal_parent(ctx->g, ctx->match_mode, node_map_dev, node_level_dev, at<float>(ctx, ctx->lay.sig),
                          at<float>(ctx, ctx->lay.tau_t),

@@ -577,7 +577,7 @@ void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, co
 }
 
 // ------------------------------------------------------------------------------------------------
-// Common root by pointer jumping (Sec. 3.3, "union-find in a vectorized form"): every edge points one
+// Common root of every chain by pointer jumping (root finding of Sec. 3.3): every edge points one
 // frame back, so a chain has at most T-1 edges; each launch multiplies the reach by kHops.
 // ------------------------------------------------------------------------------------------------
 // One launch follows up to kHops edges of the previous array, i.e. multiplies the reach by kHops; a walk stops at a

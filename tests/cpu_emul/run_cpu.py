@@ -38,7 +38,7 @@ def load():
 
 
 def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=None, lib=None, use_nodes=True,
-            match=0, order=0, positions=False, defer_tau=False, cell_dots=1):
+            match=0, order=0, positions=False, defer_tau=False, cell_dots=1, node_map_override=None):
     lib = lib or load()
     B, T, H, W, D = feats.shape
     dt = STTM_BF16 if feats.dtype == np.uint16 else (STTM_F16 if feats.dtype == np.float16 else STTM_F32)
@@ -83,6 +83,9 @@ def run_cpu(feats, *, tau_s=None, tau_t=None, keep=None, root_grid=1, out_dtype=
     r.min_sim = tbl.reshape(B * T, NN).copy()
     r.node_map = node_map.reshape(B, T, H, W).copy()
     r.node_level = node_level.reshape(B, T, H, W).copy()
+    if node_map_override is not None:   # any valid quadtree partition per frame may be handed to the temporal stage
+        node_map[:] = node_map_override[0].reshape(-1)
+        node_level[:] = node_map_override[1].reshape(-1)
     if tau_t is None:
         chk(lib.sttm_temporal_stats(h, _p(x), _p(node_map), _p(node_level)))
         out = (C.c_float * B)()

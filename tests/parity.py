@@ -29,15 +29,6 @@ class GpuResult:
     pass
 
 
-def _trace(msg):
-    """STTM_TRACE=1: synchronise and name every stage as it completes, so a hang or fault names its stage."""
-    import os
-    if os.environ.get("STTM_TRACE"):
-        import torch
-        torch.cuda.synchronize()
-        print(f"    [trace] {msg} done", flush=True)
-
-
 def _to_dev(feats: np.ndarray):
     import torch
     if feats.dtype == np.uint16:
@@ -53,11 +44,41 @@ MODES = {"first_passing": 0, "topleft_only": 1, "most_similar": 2}
 ORDERS = {"raster": 0, "zscan": 1}
 
 
+CANARY_BYTES = 4096
+CANARY_FILL = 0xA5
+
+
+class Guarded:
+    """Caller buffers with a band of CANARY_BYTES known bytes on either side: a kernel that stores outside a buffer
+    it was handed changes a band, and check() says which one. The second band starts at the buffer's last byte."""
+
+    def __init__(self, dev="cuda:0"):
+        self.dev = dev
+        self.items = []
+
+    def alloc(self, name, n_elems, dtype, zero=False):
+        import torch
+        nbytes = int(n_elems) * torch.empty(0, dtype=dtype).element_size()
+        raw = torch.full((2 * CANARY_BYTES + nbytes,), CANARY_FILL, dtype=torch.uint8, device=self.dev)
+        view = raw[CANARY_BYTES:CANARY_BYTES + nbytes].view(dtype)
+        if zero:
+            view.zero_()
+        self.items.append((name, raw, nbytes))
+        return view
+
+    def check(self, after: str):
+        for name, raw, nbytes in self.items:
+            lo = bool((raw[:CANARY_BYTES] == CANARY_FILL).all().item())
+            hi = bool((raw[CANARY_BYTES + nbytes:] == CANARY_FILL).all().item())
+            assert lo and hi, f"bytes {'before' if not lo else 'after'} buffer '{name}' were overwritten by {after}"
+
+
 def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_grid: int = 1,
             out_dtype: Optional[int] = None, node_map_override=None, ctx=None, feats_dev=None,
             use_nodes: bool = True, mode: str = "first_passing", order: str = "raster",
             positions: bool = False, cell_dots: int = 1) -> GpuResult:
-    """Whole path through the C ABI. Fixed thresholds, or `keep` (budget mode)."""
+    """Whole path through the C ABI. Fixed thresholds, or `keep` (budget mode). Every buffer the library writes
+    for the caller sits between canary bands, which are checked after every call."""
     import torch
     B, T, H, W, D = feats.shape
     dt = lib_dtype(lib, feats)
@@ -73,20 +94,19 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
     NN = lib.sttm_nodes_per_frame(H, W, root_grid)
     dev = "cuda:0"
     r = GpuResult()
-    node_map = torch.empty(N, dtype=torch.int32, device=dev)
-    node_level = torch.empty(N, dtype=torch.uint8, device=dev)
-    cluster = torch.empty(N, dtype=torch.int32, device=dev)
+    gd = Guarded(dev)
+    node_map = gd.alloc("node_map", N, torch.int32)
+    node_level = gd.alloc("node_level", N, torch.uint8)
+    cluster = gd.alloc("cluster_ids", N, torch.int32)
     r.tau_s = r.tau_t = None
     if tau_s is None:
         s.sttm_spatial_stats(x, dt, B, T, H, W, D, root_grid)
-        _trace("spatial statistics")
         r.tau_s = s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, keep)
-        _trace("spatial budget")
         s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, root_grid, None, node_map, node_level)
     else:
         s.sttm_spatial_quadtree(x, dt, B, T, H, W, D, root_grid, tau_s, node_map, node_level)
-    _trace("spatial stage")
-    tbl = torch.empty(B * T * NN, dtype=torch.float32, device=dev)
+    gd.check("the spatial stage")
+    tbl = gd.alloc("export table", B * T * NN, torch.float32)
     s.sttm_export(lib.STTM_TBL_CHILD_SIM, tbl)
     r.child_sim = tbl.cpu().numpy().reshape(B * T, NN)
     s.sttm_export(lib.STTM_TBL_MIN_SIM, tbl)
@@ -98,42 +118,40 @@ def run_gpu(lib, feats: np.ndarray, *, tau_s=None, tau_t=None, keep=None, root_g
         node_level.copy_(torch.from_numpy(node_map_override[1].reshape(-1)).cuda())
     if tau_t is None:
         s.sttm_temporal_stats(x, node_map, node_level)
-        _trace("temporal statistics")
         r.tau_t = s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, keep)
-        _trace("temporal budget")
         s.sttm_temporal_merge(x, node_map, node_level, None, cluster)
     else:
         s.sttm_temporal_merge(x, node_map, node_level, tau_t, cluster)
-    _trace("temporal stage")
-    t32 = torch.empty(N, dtype=torch.float32, device=dev)
+    gd.check("the temporal stage")
+    t32 = gd.alloc("export table (cells)", N, torch.float32)
     s.sttm_export(lib.STTM_TBL_PAIR_SIM, t32)
     r.pair_sim = t32.cpu().numpy()
     s.sttm_export(lib.STTM_TBL_BEST_SIM, t32)
     r.best_sim = t32.cpu().numpy()
-    ti = torch.empty(N, dtype=torch.int32, device=dev)
+    ti = gd.alloc("export table (parent)", N, torch.int32)
     s.sttm_export(lib.STTM_TBL_PARENT, ti)
     r.parent = ti.cpu().numpy().reshape(B, T, H, W)
     r.cluster_ids = cluster.cpu().numpy().reshape(B, T, H, W)
     odt = {lib.STTM_BF16: torch.bfloat16, lib.STTM_F16: torch.float16}.get(out_dtype, torch.float32)
-    merged = torch.zeros(N, D, dtype=odt, device=dev)
-    counts = torch.zeros(N, dtype=torch.int32, device=dev)
-    out_ids = torch.zeros(N, dtype=torch.int32, device=dev)
-    offsets = torch.zeros(B + 1, dtype=torch.int64, device=dev)
+    merged = gd.alloc("merged", N * D, odt, zero=True).view(N, D)
+    counts = gd.alloc("counts", N, torch.int32, zero=True)
+    out_ids = gd.alloc("out_ids", N, torch.int32, zero=True)
+    offsets = gd.alloc("offsets", B + 1, torch.int64, zero=True)
     K = s.sttm_reduce(x, cluster, node_map if use_nodes else None, node_level if use_nodes else None, out_dtype, N,
                       merged, counts, out_ids, offsets)
-    _trace("reduce stage")
+    gd.check("the reduce stage")
     r.K = K
     r.merged = merged[:K].float().cpu().numpy()
     r.counts = counts[:K].cpu().numpy()
     r.out_ids = out_ids[:K].cpu().numpy()
     r.offsets = offsets.cpu().numpy()
     if positions:
-        sv = torch.zeros(N, dtype=torch.int32, device=dev)
-        ra = torch.zeros(N, dtype=torch.int32, device=dev)
-        mp = torch.zeros(N, dtype=torch.float32, device=dev)
-        rt = torch.zeros(N, 4, dtype=torch.int32, device=dev)
+        sv = gd.alloc("survived", N, torch.int32, zero=True)
+        ra = gd.alloc("reassigned", N, torch.int32, zero=True)
+        mp = gd.alloc("merged_pos", N, torch.float32, zero=True)
+        rt = gd.alloc("root_tyxl", 4 * N, torch.int32, zero=True).view(N, 4)
         s.sttm_positions(cluster, node_map if use_nodes else None, node_level, offsets, N, sv, ra, mp, rt)
-        _trace("positions")
+        gd.check("the position indices")
         r.survived, r.reassigned = sv[:K].cpu().numpy(), ra[:K].cpu().numpy()
         r.merged_pos, r.root_tyxl = mp[:K].cpu().numpy(), rt[:K].cpu().numpy()
     r.ctx = s
@@ -159,10 +177,16 @@ def check_spatial(lib, feats, r: GpuResult, tau_s, root_grid=1, stats=None):
                         cy, cx = 2 * by + (k >> 1), 2 * bx + (k & 1)
                         if cnt[lvl - 1][cy, cx] == 0:
                             continue
-                        got = r.child_sim[f, lib.sttm_node_index(H, W, root_grid, lvl - 1, cy, cx)]
-                        worst = max(worst, abs(float(got) - sims[lvl][by, bx, k]))
-                    gm = r.min_sim[f, lib.sttm_node_index(H, W, root_grid, lvl, by, bx)]
-                    worst = max(worst, abs(float(gm) - m[lvl][by, bx]))
+                        got = float(r.child_sim[f, lib.sttm_node_index(H, W, root_grid, lvl - 1, cy, cx)])
+                        want = float(sims[lvl][by, bx, k])
+                        assert (got != got) == (want != want), "undefined similarity on one side only"
+                        if want == want:
+                            worst = max(worst, abs(got - want))
+                    gm = float(r.min_sim[f, lib.sttm_node_index(H, W, root_grid, lvl, by, bx)])
+                    wm = float(m[lvl][by, bx])
+                    assert (gm != gm) == (wm != wm), "undefined minimum similarity on one side only"
+                    if wm == wm:
+                        worst = max(worst, abs(gm - wm))
     assert worst <= SIM_TOL, f"spatial similarity error {worst}"
 
     def decide(b, t, lvl, by, bx, val):
@@ -188,7 +212,10 @@ def check_temporal(lib, feats, r: GpuResult, sp, tau_t, cands=None, mode: str = 
         for d, sig in lst:
             # slot = top-left cell of the finer node, in frame f's table
             q = n if lvl_flat[n] <= lvl_flat[d] else d + HW
-            worst = max(worst, abs(float(r.pair_sim[q]) - sig))
+            got = float(r.pair_sim[q])
+            assert (got != got) == (sig != sig), "undefined pair similarity on one side only"
+            if sig == sig:
+                worst = max(worst, abs(got - sig))
     best = O.best_similarity(cands, sp.node_map, mode)
     for n in cands:
         worst = max(worst, abs(float(r.best_sim[n]) - best[n]))

@@ -89,3 +89,33 @@ def test_emulated_temporal_pass_without_the_cell_dot_products(emul, kw):
     assert (a.node_map == b.node_map).all() and (a.cluster_ids == b.cluster_ids).all() and a.K == b.K
     P.check_parity(fake, feats, a, **kw)
     P.check_parity(fake, feats, b, **kw)
+
+
+def _uniform_partition(T, H, W, levels):
+    """Node map and levels of a video whose frame t consists of the aligned blocks of level levels[t] only."""
+    nm = np.empty((1, T, H, W), np.int32)
+    nl = np.empty((1, T, H, W), np.uint8)
+    yy, xx = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    for t, lv in enumerate(levels):
+        nm[0, t] = t * H * W + ((yy >> lv) << lv) * W + ((xx >> lv) << lv)
+        nl[0, t] = lv
+    return nm, nl
+
+
+def test_emulated_temporal_work_lists_at_their_largest(emul):
+    """The temporal pass lists its work per frame pair by join level and walks every list with a fixed stride and
+    a trip count known on entry. On a full 32 x 32 grid, frames of uniform level meet so that every list is as long
+    as it can get: 256 regions of 2 x 2 (levels 0|1), 64 blocks of 4 x 4 (1|2 and 2|0), 16 staged sums with 256
+    nodes of 2 x 2 under them (3|1), and 1024 single cells under one whole-frame node (5|0) or under sixteen
+    8 x 8 nodes (0|3). Every pair similarity, edge, cluster and merged row is compared with the oracle."""
+    run_cpu, fake = emul
+    levels = [5, 0, 3, 1, 2, 0, 1]
+    T, H, W, D = len(levels), 32, 32, 8
+    feats = wl.generate(wl.Workload("v", 99, 1, T, H, W, D, "f32", 5, 0.3, 0.8))
+    nm, nl = _uniform_partition(T, H, W, levels)
+    from oracle import sttm_oracle as O
+    sp = O.SpatialResult()
+    sp.node_map, sp.node_level = nm, nl
+    r = run_cpu.run_cpu(feats, tau_s=0.5, tau_t=0.3, node_map_override=(nm, nl))
+    tm, _ = P.check_temporal(fake, feats, r, sp, 0.3)
+    P.check_reduce(feats, r, tm, False)

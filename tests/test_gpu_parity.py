@@ -480,43 +480,160 @@ def test_config3_long_video_budget(lib, keep, cell_dots):
     _run_and_check(lib, cfg, keep=keep, cell_dots=cell_dots)
 
 
-@pytest.mark.parametrize("index,keep,frames", [(5, 0.3, 180), (6, 0.5, 40)])
-def test_paper_shapes_budget(lib, index, keep, frames):
-    """The paper's own grid (14 x 14, 4 x 4 roots, 180 frames) and a wide non-square one (its first 40 frames:
-    the oracle needs a minute for all 180), in budget mode."""
-    cfg = wl.small_variant(wl.CONFIGS[index], T=frames)
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("index,keep", [(5, 0.3), (6, 0.5)])
+def test_paper_shapes_budget(lib, index, keep):
+    """The paper's own grid (14 x 14, 4 x 4 roots, 180 frames) and a wide non-square one (18 x 24 at D = 8192), every
+    frame of both compared with the oracle, in budget mode."""
+    cfg = wl.CONFIGS[index]
     _run_and_check(lib, cfg, keep=keep, root_grid=cfg.root_grid)
 
 
-def test_config4_batched_fixed_thresholds_sampled_videos(lib):
-    """All 32 videos run on the GPU; the oracle checks four of them one by one (videos are independent,
-    so a video's slice of every output equals the single-video result shifted by its token offset)."""
+@pytest.fixture(scope="module")
+def batched(lib):
+    """Config 4 run once on the GPU (all 32 videos in one batch); the tests below compare it video by video."""
     cfg = wl.CONFIGS[4]
     feats = wl.generate(cfg)
-    B, T, H, W, D = feats.shape
     print(f"case {cfg.name} shape={feats.shape}", flush=True)
     r = P.run_gpu(lib, feats, tau_s=cfg.tau_s, tau_t=cfg.tau_t)
     assert int(r.counts.sum()) == cfg.n_tokens and r.offsets[-1] == r.K
+    return cfg, feats, r
+
+
+@pytest.mark.parametrize("b", range(32))
+def test_config4_batched_fixed_thresholds_every_video(lib, batched, b):
+    """Videos are independent, so a video's slice of every output equals the single-video result shifted by its
+    token offset: the oracle runs on each of the 32 videos and is compared element by element."""
+    cfg, feats, r = batched
+    B, T, H, W, D = feats.shape
     per = T * H * W
-    for b in (0, 11, 22, 31):
-        sub = P.GpuResult()
-        lo, hi = int(r.offsets[b]), int(r.offsets[b + 1])
-        NN = r.child_sim.shape[1]
-        sub.child_sim = r.child_sim[b * T:(b + 1) * T]
-        sub.min_sim = r.min_sim[b * T:(b + 1) * T]
-        sub.node_map = r.node_map[b:b + 1] - b * per
-        sub.node_level = r.node_level[b:b + 1]
-        sub.pair_sim = r.pair_sim[b * per:(b + 1) * per]
-        sub.best_sim = r.best_sim[b * per:(b + 1) * per]
-        par = r.parent[b:b + 1].copy()
-        par[par >= 0] -= b * per
-        sub.parent = par
-        sub.cluster_ids = r.cluster_ids[b:b + 1] - b * per
-        sub.K = hi - lo
-        sub.merged = r.merged[lo:hi]
-        sub.counts = r.counts[lo:hi]
-        sub.out_ids = r.out_ids[lo:hi] - b * per
-        sub.offsets = np.array([0, hi - lo])
-        info = P.check_parity(lib, feats[b:b + 1], sub, tau_s=cfg.tau_s, tau_t=cfg.tau_t)
-        print(f"   video {b}:", {k: (float(v) if isinstance(v, (float, np.floating)) else v)
-                                 for k, v in info.items()}, flush=True)
+    sub = P.GpuResult()
+    lo, hi = int(r.offsets[b]), int(r.offsets[b + 1])
+    sub.child_sim = r.child_sim[b * T:(b + 1) * T]
+    sub.min_sim = r.min_sim[b * T:(b + 1) * T]
+    sub.node_map = r.node_map[b:b + 1] - b * per
+    sub.node_level = r.node_level[b:b + 1]
+    sub.pair_sim = r.pair_sim[b * per:(b + 1) * per]
+    sub.best_sim = r.best_sim[b * per:(b + 1) * per]
+    par = r.parent[b:b + 1].copy()
+    par[par >= 0] -= b * per
+    sub.parent = par
+    sub.cluster_ids = r.cluster_ids[b:b + 1] - b * per
+    sub.K = hi - lo
+    sub.merged = r.merged[lo:hi]
+    sub.counts = r.counts[lo:hi]
+    sub.out_ids = r.out_ids[lo:hi] - b * per
+    sub.offsets = np.array([0, hi - lo])
+    info = P.check_parity(lib, feats[b:b + 1], sub, tau_s=cfg.tau_s, tau_t=cfg.tau_t)
+    print(f"   video {b}:", {k: (float(v) if isinstance(v, (float, np.floating)) else v)
+                             for k, v in info.items()}, flush=True)
+
+
+# ---- state handling, streams, contexts, non-finite inputs -------------------------------------------------------
+def test_infinite_and_nan_features_against_the_oracle(lib):
+    """An infinity or a NaN makes the similarities it enters undefined; they never pass a threshold, on either side."""
+    feats = wl.generate(_variant(41, 1, 4, 13, 13, 72, "f32"))
+    feats[0, 1, 5, 6, 3] = np.inf
+    feats[0, 2, 12, 12, 70] = -np.inf
+    feats[0, 3, 0, 0, 0] = np.nan
+    for kw in (dict(tau_s=0.7, tau_t=0.6), dict(tau_s=-2.0, tau_t=-2.0)):
+        r = P.run_gpu(lib, feats, **kw)
+        sp = O.spatial_quadtree(feats, kw["tau_s"])
+        assert (sp.node_map == r.node_map).all() and (sp.node_level == r.node_level).all()
+        assert r.node_level[0, 1, 5, 6] == 0 and r.node_level[0, 2, 12, 12] == 0 and r.node_level[0, 3, 0, 0] == 0
+        sp2, _ = P.check_spatial(lib, feats, r, kw["tau_s"])
+        tm, _ = P.check_temporal(lib, feats, r, sp2, kw["tau_t"])
+        assert r.parent[0, 1, 5, 6] == -1 and r.parent[0, 2, 5, 6] == -1      # no edge into or out of the broken token
+        assert (r.counts.sum() == feats[..., 0].size) and r.K == len(np.unique(tm.cluster_ids))
+
+
+def test_new_temporal_statistics_discard_the_pending_threshold(lib):
+    """temporal_stats, budget (threshold left to the consumer), temporal_stats again, merge without thresholds:
+    the second statistics pass starts the search afresh, so the merge must refuse instead of resolving a
+    threshold from an empty search state."""
+    import torch
+    cfg = _variant(81, 2, 5, 13, 13, 72, "bf16")
+    feats = wl.generate(cfg)
+    B, T, H, W, D = feats.shape
+    N = B * T * H * W
+    x = P._to_dev(feats)
+    s = lib.Sttm(0)
+    s.ensure_workspace(B, T, H, W, D, lib.STTM_BF16, 1)
+    nm = torch.empty(N, dtype=torch.int32, device="cuda:0")
+    nl = torch.empty(N, dtype=torch.uint8, device="cuda:0")
+    cl = torch.empty(N, dtype=torch.int32, device="cuda:0")
+    s.sttm_spatial_quadtree(x, lib.STTM_BF16, B, T, H, W, D, 1, [0.9, 0.9], nm, nl)
+    s.sttm_temporal_stats(x, nm, nl)
+    s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.5, want_tau=False)
+    s.sttm_temporal_stats(x, nm, nl)
+    with pytest.raises(lib.SttmError) as e:
+        s.sttm_temporal_merge(x, nm, nl, None, cl)
+    assert e.value.code == lib.STTM_ERR_STATE
+    tau = s.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.5)
+    nm2 = nm.clone()
+    with pytest.raises(lib.SttmError) as e:                      # not the node map the statistics were computed for
+        s.sttm_temporal_merge(x, nm2, nl, None, cl)
+    assert e.value.code == lib.STTM_ERR_STATE
+    s.sttm_temporal_merge(x, nm, nl, None, cl)
+    ref = P.run_gpu(lib, feats, tau_s=[0.9, 0.9], tau_t=list(tau))
+    assert (cl.cpu().numpy().reshape(ref.cluster_ids.shape) == ref.cluster_ids).all()
+    # after sttm_invalidate nothing cached is trusted any more
+    s.sttm_invalidate()
+    for call in (lambda: s.sttm_temporal_merge(x, nm, nl, [0.5, 0.5], cl),
+                 lambda: s.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, 0.5),
+                 lambda: s.sttm_spatial_quadtree(x, lib.STTM_BF16, B, T, H, W, D, 1, None, nm, nl)):
+        with pytest.raises(lib.SttmError) as e:
+            call()
+        assert e.value.code == lib.STTM_ERR_STATE
+    s.sttm_spatial_quadtree(x, lib.STTM_BF16, B, T, H, W, D, 1, [0.9, 0.9], nm, nl)   # and recomputing works
+    s.sttm_temporal_merge(x, nm, nl, list(tau), cl)
+    assert (cl.cpu().numpy().reshape(ref.cluster_ids.shape) == ref.cluster_ids).all()
+
+
+def test_non_default_stream_and_two_contexts_on_one_device(lib):
+    """Two contexts with workspaces of their own, one on a stream that is not the default one, interleaved call by
+    call on two different videos: each gives what it gives alone."""
+    import torch
+    fa = wl.generate(_variant(82, 1, 6, 13, 13, 520, "bf16"))
+    fb = wl.generate(_variant(83, 2, 4, 16, 16, 136, "f32"))
+    ra = P.run_gpu(lib, fa, keep=0.5)
+    rb = P.run_gpu(lib, fb, tau_s=0.8, tau_t=0.7)
+    side = torch.cuda.Stream(device=0)
+    sa = lib.Sttm(0, stream_ptr=side.cuda_stream)
+    sb = lib.Sttm(0)
+    xa, xb = P._to_dev(fa), P._to_dev(fb)
+    torch.cuda.synchronize()
+    out = {}
+    for name, s, x, f in (("a", sa, xa, fa), ("b", sb, xb, fb)):
+        B, T, H, W, D = f.shape
+        N = B * T * H * W
+        dt = P.lib_dtype(lib, f)
+        s.ensure_workspace(B, T, H, W, D, dt, 1)
+        out[name] = dict(nm=torch.empty(N, dtype=torch.int32, device="cuda:0"),
+                         nl=torch.empty(N, dtype=torch.uint8, device="cuda:0"),
+                         cl=torch.empty(N, dtype=torch.int32, device="cuda:0"),
+                         mg=torch.zeros(N, D, dtype=x.dtype, device="cuda:0"),
+                         ct=torch.zeros(N, dtype=torch.int32, device="cuda:0"),
+                         oi=torch.zeros(N, dtype=torch.int32, device="cuda:0"),
+                         of=torch.zeros(B + 1, dtype=torch.int64, device="cuda:0"), shape=(B, T, H, W, D), dt=dt, N=N)
+    torch.cuda.synchronize()
+    a, b = out["a"], out["b"]
+    Ba, Ta, Ha, Wa, Da = a["shape"]
+    Bb, Tb, Hb, Wb, Db = b["shape"]
+    sa.sttm_spatial_stats(xa, a["dt"], Ba, Ta, Ha, Wa, Da, 1)
+    sb.sttm_spatial_quadtree(xb, b["dt"], Bb, Tb, Hb, Wb, Db, 1, [0.8] * Bb, b["nm"], b["nl"])
+    sa.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, 0.5, want_tau=False)
+    sb.sttm_temporal_merge(xb, b["nm"], b["nl"], [0.7] * Bb, b["cl"])
+    sa.sttm_spatial_quadtree(xa, a["dt"], Ba, Ta, Ha, Wa, Da, 1, None, a["nm"], a["nl"])
+    sa.sttm_temporal_stats(xa, a["nm"], a["nl"])
+    Kb = sb.sttm_reduce(xb, b["cl"], b["nm"], b["nl"], b["dt"], b["N"], b["mg"], b["ct"], b["oi"], b["of"])
+    sa.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, 0.5, want_tau=False)
+    sa.sttm_temporal_merge(xa, a["nm"], a["nl"], None, a["cl"])
+    Ka = sa.sttm_reduce(xa, a["cl"], a["nm"], a["nl"], a["dt"], a["N"], a["mg"], a["ct"], a["oi"], a["of"])
+    side.synchronize()
+    torch.cuda.synchronize()
+    for r, o, K in ((ra, a, Ka), (rb, b, Kb)):
+        assert K == r.K
+        assert (o["cl"].cpu().numpy().reshape(r.cluster_ids.shape) == r.cluster_ids).all()
+        assert (o["ct"][:K].cpu().numpy() == r.counts).all() and (o["oi"][:K].cpu().numpy() == r.out_ids).all()
+        np.testing.assert_array_equal(o["mg"][:K].float().cpu().numpy(), r.merged)

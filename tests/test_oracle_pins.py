@@ -664,3 +664,29 @@ def test_destination_choice_against_restated_rules_and_relations(mode):
             assert par[n] == bpar[n]
     # the number of clusters equals nodes minus edges under every rule
     assert len(np.unique(tm.cluster_ids)) == len(np.unique(sp.node_map)) - len(merged)
+
+
+def test_undefined_similarities_never_pass_a_threshold():
+    """A NaN or an infinity in the input makes every similarity it enters undefined (NaN); the reading taken is
+    that such a similarity never exceeds a threshold: the node splits at every tau_S, no edge is drawn at any
+    tau_T, and the budget rule counts it as the lowest value. Worked by hand on a 4 x 4 frame."""
+    assert math.isnan(O.cosine(np.array([1.0, np.nan]), np.array([1.0, 2.0])))
+    assert math.isnan(O.cosine(np.array([np.inf, 0.0]), np.array([1.0, 1.0])))
+    assert math.isnan(O.cosine(np.array([1.0, 1.0]), np.array([-np.inf, 3.0])))
+    assert O.cosine(np.array([0.0, 0.0]), np.array([np.nan, 1.0])) == 0.0      # the zero-norm rule comes first
+    frame = np.ones((1, 2, 4, 4, 3), dtype=np.float32)
+    frame[0, 1, 3, 3, 1] = np.inf
+    sp = O.spatial_quadtree(frame, -2.0)
+    assert (sp.node_level[0, 0] == 2).all()                                    # the clean frame: one root
+    lv = sp.node_level[0, 1]
+    assert (lv[:2, :] == 1).all() and (lv[2:, :2] == 1).all() and (lv[2:, 2:] == 0).all()
+    grid = O.Grid(4, 4)
+    scores = O.split_scores(sp.m[1], grid)
+    # the root and the quadrant holding the infinity always split (-2); the three clean quadrants score their own m = 1
+    assert sorted(s for s, _ in scores) == [-2.0, -2.0, 1.0, 1.0, 1.0]
+    tm = O.temporal_merge(frame, sp.node_map, sp.node_level, -2.0)
+    par = tm.parent[0, 1]
+    assert par[3, 3] == -1 and par[0, 0] == 0 and par[2, 2] == 0 and par[2, 0] == 0     # only the broken cell stays
+    assert tm.e[16 + 15] == -2.0 and tm.e[16 + 0] == 1.0
+    rd = O.reduce_clusters(frame, tm.cluster_ids)
+    assert list(rd.counts) == [31, 1]
