@@ -194,6 +194,24 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
                 void* merged_dev, int32_t* counts_dev, int32_t* out_ids_dev, int64_t* offsets_dev,
                 int64_t* n_out_host);
 
+/* For callers that cannot allocate (code under HIP graph capture, serving loops and harnesses in which device
+ * allocation is forbidden): sttm_reduce without a workspace and without the stage-1 partition. Same result as
+ * sttm_reduce(ctx, feats, cluster_ids, NULL, NULL, ...) bit for bit (same kernels); the shape is passed here because
+ * no stage-1 call need have bound one. Its tables (ranks, sort buffers, member lists, partial sums of large clusters)
+ * live in a fixed array of sttm_reduce_noalloc_max_bytes() = 32 MiB inside the library's device image, held by every
+ * GPU the library runs on until the process ends; the call allocates nothing, on the device or through a library
+ * that would, never synchronises and copies nothing to the host, so K is read from offsets[B] (rows beyond
+ * capacity are not written). A shape whose tables need more (sttm_reduce_noalloc_bytes(), about 44 bytes per token
+ * plus D/2 bytes per token plus 2 MiB) is refused with STTM_ERR_WORKSPACE. All calls on one GPU share the one
+ * array: two calls that overlap in time on the same GPU (different streams or contexts) race; calls on one stream
+ * do not. The context's workspace, bound shape and cached tables are left untouched; sttm_positions does not
+ * follow this call. Row order as set by sttm_set_output_order. */
+int sttm_reduce_noalloc(sttm_ctx* ctx, const void* feats_dev, int dtype, int B, int T, int H, int W, int D,
+                        const int32_t* cluster_ids_dev, int out_dtype, int64_t capacity, void* merged_dev,
+                        int32_t* counts_dev, int32_t* out_ids_dev, int64_t* offsets_dev);
+size_t sttm_reduce_noalloc_max_bytes(void);
+size_t sttm_reduce_noalloc_bytes(int B, int T, int H, int W, int D, int dtype);
+
 /* ---- position indices of the output rows (Sec. 3.4) ---------------------------------------------------------- */
 
 /* For the rows the preceding sttm_reduce call on the same cluster_ids produced (same order), all device, each may

@@ -29,7 +29,8 @@ EXPORTS = [
     "sttm_workspace_bytes", "sttm_set_workspace", "sttm_spatial_stats", "sttm_spatial_quadtree",
     "sttm_temporal_stats", "sttm_temporal_merge", "sttm_budget_threshold", "sttm_reduce", "sttm_export",
     "sttm_profile_enable", "sttm_profile_read", "sttm_set_match_mode", "sttm_set_output_order", "sttm_positions",
-    "sttm_set_cell_dots", "sttm_invalidate",
+    "sttm_set_cell_dots", "sttm_invalidate", "sttm_reduce_noalloc", "sttm_reduce_noalloc_max_bytes",
+    "sttm_reduce_noalloc_bytes",
 ]
 STTM_MATCH_FIRST_PASSING, STTM_MATCH_TOPLEFT_ONLY, STTM_MATCH_MOST_SIMILAR = 0, 1, 2
 STTM_ORDER_RASTER, STTM_ORDER_ZSCAN = 0, 1
@@ -65,6 +66,11 @@ def _load() -> C.CDLL:
     lib.sttm_set_output_order.argtypes = [vp, i]
     lib.sttm_set_cell_dots.argtypes = [vp, i]
     lib.sttm_invalidate.argtypes = [vp]
+    lib.sttm_reduce_noalloc.argtypes = [vp, vp, i, i, i, i, i, i, vp, i, i64, vp, vp, vp, vp]
+    lib.sttm_reduce_noalloc_max_bytes.argtypes = []
+    lib.sttm_reduce_noalloc_max_bytes.restype = sz
+    lib.sttm_reduce_noalloc_bytes.argtypes = [i, i, i, i, i, i]
+    lib.sttm_reduce_noalloc_bytes.restype = sz
     lib.sttm_positions.argtypes = [vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     return lib
 
@@ -88,6 +94,14 @@ def sttm_node_index(H: int, W: int, root_grid: int, level: int, by: int, bx: int
 
 def sttm_workspace_bytes(B, T, H, W, D, dtype, root_grid=1) -> int:
     return int(_lib.sttm_workspace_bytes(B, T, H, W, D, dtype, root_grid))
+
+
+def sttm_reduce_noalloc_max_bytes() -> int:
+    return int(_lib.sttm_reduce_noalloc_max_bytes())
+
+
+def sttm_reduce_noalloc_bytes(B, T, H, W, D, dtype) -> int:
+    return int(_lib.sttm_reduce_noalloc_bytes(B, T, H, W, D, dtype))
 
 
 def _ptr(t) -> Optional[int]:
@@ -184,6 +198,11 @@ class Sttm:
 
     def sttm_set_output_order(self, order: int):
         self._check(_lib.sttm_set_output_order(self._h, order))
+
+    def sttm_reduce_noalloc(self, feats, dtype, B, T, H, W, D, cluster_ids, out_dtype, capacity, merged, counts,
+                            out_ids, offsets):
+        self._check(_lib.sttm_reduce_noalloc(self._h, _ptr(feats), dtype, B, T, H, W, D, _ptr(cluster_ids), out_dtype,
+                                             capacity, _ptr(merged), _ptr(counts), _ptr(out_ids), _ptr(offsets)))
 
     def sttm_invalidate(self):
         self._check(_lib.sttm_invalidate(self._h))

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -51,6 +52,33 @@ bool make_geo(int B, int T, int H, int W, int D, int dtype, int root_grid, Geo* 
   return true;
 }
 
+// The tables of the reduce stage (ranks, sort buffers, member lists, partial sums of large clusters), laid out
+// from byte `off` on; returns the first byte after them.
+size_t layout_reduce(const Geo& g, size_t off, Layout* lp) {
+  Layout& l = *lp;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  const size_t N = g.N;
+  l.rank = take(N * sizeof(int32_t));
+  l.key_a = take(N * sizeof(int32_t));
+  l.val_a = take(N * sizeof(int32_t));
+  l.key_b = take(N * sizeof(int32_t));
+  l.val_b = take(N * sizeof(int32_t));
+  l.order = take(N * sizeof(int32_t));
+  l.orow = take(N * sizeof(int32_t));
+  l.hist = take(reduce_hist_entries(g.N) * sizeof(int32_t));
+  l.tot = take(2048 * sizeof(int32_t));
+  l.gsum = take(reduce_gsum_entries() * sizeof(int32_t));
+  l.tile_roots = take(reduce_tiles(g.N) * sizeof(int32_t));
+  l.tile_live = take(reduce_tiles(g.N) * sizeof(int32_t));
+  l.seg = take((N + 1) * sizeof(int32_t));
+  l.kdev = take(4 * sizeof(int32_t));
+  l.bigpart = take(reduce_bigpart_floats(g) * sizeof(float));
+  l.bigw = take(reduce_bigw_entries(g) * sizeof(int32_t));
+  l.biglist = take(reduce_biglist_entries(g) * 4 * sizeof(int32_t));
+  l.zpos = take(N * sizeof(int32_t));
+  return off;
+}
+
 Layout make_layout(const Geo& g) {
   Layout l;
   size_t off = 0;
@@ -78,24 +106,7 @@ Layout make_layout(const Geo& g) {
   l.parent = take(N * sizeof(int32_t));
   l.ptr_a = take(N * sizeof(int32_t));
   l.ptr_b = take(N * sizeof(int32_t));
-  l.rank = take(N * sizeof(int32_t));
-  l.key_a = take(N * sizeof(int32_t));
-  l.val_a = take(N * sizeof(int32_t));
-  l.key_b = take(N * sizeof(int32_t));
-  l.val_b = take(N * sizeof(int32_t));
-  l.order = take(N * sizeof(int32_t));
-  l.orow = take(N * sizeof(int32_t));
-  l.hist = take(reduce_hist_entries(g.N) * sizeof(int32_t));
-  l.tot = take(2048 * sizeof(int32_t));
-  l.gsum = take(reduce_gsum_entries() * sizeof(int32_t));
-  l.tile_roots = take(reduce_tiles(g.N) * sizeof(int32_t));
-  l.tile_live = take(reduce_tiles(g.N) * sizeof(int32_t));
-  l.seg = take((N + 1) * sizeof(int32_t));
-  l.kdev = take(4 * sizeof(int32_t));
-  l.bigpart = take(reduce_bigpart_floats(g) * sizeof(float));
-  l.bigw = take(reduce_bigw_entries(g) * sizeof(int32_t));
-  l.biglist = take(reduce_biglist_entries(g) * 4 * sizeof(int32_t));
-  l.zpos = take(N * sizeof(int32_t));
+  off = layout_reduce(g, off, &l);
   l.possum = take(N * sizeof(unsigned long long));
   l.poscnt = take(N * sizeof(unsigned));
   l.total = off;
@@ -104,8 +115,35 @@ Layout make_layout(const Geo& g) {
 
 }  // namespace
 
+// Scratch memory of sttm_reduce_noalloc: a fixed array in the library's device image, so that the call needs no
+// allocation and no caller-provided workspace. Every device the library is loaded on holds its own copy; the
+// array's name is only a handle on the host, its device address is looked up once per device (see sttm_create).
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on every device seen so far
+
+// Device address of the static scratch array on `device` (which must be the current device), or NULL on failure.
+void* static_scratch_on(int device, hipError_t* err) {
+  *err = hipSuccess;
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[device] = p;
+  }
+  return g_scratch_ptr[device];
+}
+}  // namespace
+
 struct sttm_ctx {
   int device = 0;
+  char* static_scratch = nullptr;  // this device's copy of the static scratch array
   hipStream_t stream = nullptr;
   char* ws = nullptr;
   size_t ws_bytes = 0;
@@ -135,6 +173,31 @@ struct sttm_ctx {
 };
 
 namespace {
+
+// The reduce stage's tables inside a buffer laid out by layout_reduce().
+ReduceBuffers reduce_buffers(char* base, const Layout& l) {
+  ReduceBuffers rb;
+  auto i32 = [&](size_t off) { return reinterpret_cast<int32_t*>(base + off); };
+  rb.rank = i32(l.rank);
+  rb.key_a = i32(l.key_a);
+  rb.val_a = i32(l.val_a);
+  rb.key_b = i32(l.key_b);
+  rb.val_b = i32(l.val_b);
+  rb.order = i32(l.order);
+  rb.orow = i32(l.orow);
+  rb.hist = i32(l.hist);
+  rb.tot = i32(l.tot);
+  rb.gsum = i32(l.gsum);
+  rb.tile_roots = i32(l.tile_roots);
+  rb.tile_live = i32(l.tile_live);
+  rb.seg = i32(l.seg);
+  rb.kdev = i32(l.kdev);
+  rb.bigpart = reinterpret_cast<float*>(base + l.bigpart);
+  rb.bigw = i32(l.bigw);
+  rb.biglist = i32(l.biglist);
+  rb.zpos = i32(l.zpos);
+  return rb;
+}
 
 int fail(sttm_ctx* c, int code, const std::string& msg) {
   if (c) c->err = msg;
@@ -277,6 +340,13 @@ int sttm_create(sttm_ctx** out, int device, void* hip_stream) {
   if (!c) return STTM_ERR_HIP;
   c->device = device;
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  c->err.reserve(256);  // so that short messages need no allocation later
+  hipError_t e = hipSetDevice(device);
+  if (e == hipSuccess) c->static_scratch = static_cast<char*>(static_scratch_on(device, &e));
+  if (e != hipSuccess || !c->static_scratch) {
+    delete c;
+    return STTM_ERR_HIP;
+  }
   *out = c;
   return STTM_OK;
 }
@@ -540,25 +610,7 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
                 "a partition was given but the workspace holds no stage-1 statistics of these features");
   if (reinterpret_cast<uintptr_t>(merged_dev) & 15) return fail(ctx, STTM_ERR_ARG, "merged must be 16-byte aligned");
   STTM_HIP(ctx, hipSetDevice(ctx->device));
-  ReduceBuffers rb;
-  rb.rank = at<int32_t>(ctx, ctx->lay.rank);
-  rb.key_a = at<int32_t>(ctx, ctx->lay.key_a);
-  rb.val_a = at<int32_t>(ctx, ctx->lay.val_a);
-  rb.key_b = at<int32_t>(ctx, ctx->lay.key_b);
-  rb.val_b = at<int32_t>(ctx, ctx->lay.val_b);
-  rb.order = at<int32_t>(ctx, ctx->lay.order);
-  rb.orow = at<int32_t>(ctx, ctx->lay.orow);
-  rb.hist = at<int32_t>(ctx, ctx->lay.hist);
-  rb.tot = at<int32_t>(ctx, ctx->lay.tot);
-  rb.gsum = at<int32_t>(ctx, ctx->lay.gsum);
-  rb.tile_roots = at<int32_t>(ctx, ctx->lay.tile_roots);
-  rb.tile_live = at<int32_t>(ctx, ctx->lay.tile_live);
-  rb.seg = at<int32_t>(ctx, ctx->lay.seg);
-  rb.kdev = at<int32_t>(ctx, ctx->lay.kdev);
-  rb.bigpart = at<float>(ctx, ctx->lay.bigpart);
-  rb.bigw = at<int32_t>(ctx, ctx->lay.bigw);
-  rb.biglist = at<int32_t>(ctx, ctx->lay.biglist);
-  rb.zpos = at<int32_t>(ctx, ctx->lay.zpos);
+  const ReduceBuffers rb = reduce_buffers(ctx->ws, ctx->lay);
   const bool zscan = ctx->order == STTM_ORDER_ZSCAN;
   ctx->cluster_ids_reduced = nullptr;
   launch_reduce_prepare(ctx->g, cluster_ids_dev, node_map_dev, node_level_dev, capacity, out_ids_dev, offsets_dev,
@@ -586,6 +638,56 @@ int sttm_reduce(sttm_ctx* ctx, const void* feats_dev, const int32_t* cluster_ids
     }
   }
   return STTM_OK;
+}
+
+int sttm_reduce_noalloc(sttm_ctx* ctx, const void* feats_dev, int dtype, int B, int T, int H, int W, int D,
+                        const int32_t* cluster_ids_dev, int out_dtype, int64_t capacity, void* merged_dev,
+                        int32_t* counts_dev, int32_t* out_ids_dev, int64_t* offsets_dev) {
+  if (!ctx) return STTM_ERR_NULL;
+  if (!cluster_ids_dev || !merged_dev || !offsets_dev)
+    return fail(ctx, STTM_ERR_NULL, "cluster_ids, merged and offsets are required");
+  if (dtype != STTM_F32 && dtype != STTM_BF16 && dtype != STTM_F16) return fail(ctx, STTM_ERR_DTYPE, "bad dtype");
+  if (out_dtype != STTM_F32 && out_dtype != STTM_BF16 && out_dtype != STTM_F16)
+    return fail(ctx, STTM_ERR_DTYPE, "bad out_dtype");
+  if (!reduce_io_supported(dtype, out_dtype))
+    return fail(ctx, STTM_ERR_DTYPE, "a 16-bit input is written out in its own type or in fp32");
+  if (capacity < 0) return fail(ctx, STTM_ERR_ARG, "capacity < 0");
+  int rc = check_feats(ctx, feats_dev);
+  if (rc) return rc;
+  if (reinterpret_cast<uintptr_t>(merged_dev) & 15) return fail(ctx, STTM_ERR_ARG, "merged must be 16-byte aligned");
+  Geo g;
+  std::memset(&g, 0, sizeof g);
+  if (!make_geo(B, T, H, W, D, dtype, 1, &g))
+    return fail(ctx, STTM_ERR_SHAPE, "need B,T >= 1, B*T <= 65535, 1 <= H,W <= 32, D % 8 == 0, B*T*H*W < 2^31");
+  Layout l;
+  std::memset(&l, 0, sizeof l);
+  const size_t need = layout_reduce(g, 0, &l);
+  if (need > kStaticScratchBytes) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "shape needs %zu bytes of scratch, the static buffer holds %zu (use sttm_reduce)", need,
+             kStaticScratchBytes);
+    return fail(ctx, STTM_ERR_WORKSPACE, buf);
+  }
+  STTM_HIP(ctx, hipSetDevice(ctx->device));
+  const ReduceBuffers rb = reduce_buffers(ctx->static_scratch, l);
+  const bool zscan = ctx->order == STTM_ORDER_ZSCAN;
+  launch_reduce_prepare(g, cluster_ids_dev, nullptr, nullptr, capacity, out_ids_dev, offsets_dev, rb, zscan,
+                        ctx->stream);
+  launch_reduce_gather(g, feats_dev, nullptr, nullptr, nullptr, out_dtype, capacity, merged_dev, counts_dev, rb, zscan,
+                       ctx->stream);
+  launch_reduce_big(g, feats_dev, nullptr, nullptr, nullptr, out_dtype, capacity, merged_dev, counts_dev, rb, zscan,
+                    ctx->stream);
+  return after_launch(ctx);
+}
+
+size_t sttm_reduce_noalloc_max_bytes(void) { return kStaticScratchBytes; }
+
+size_t sttm_reduce_noalloc_bytes(int B, int T, int H, int W, int D, int dtype) {
+  Geo g;
+  if (!make_geo(B, T, H, W, D, dtype, 1, &g)) return 0;
+  Layout l;
+  std::memset(&l, 0, sizeof l);
+  return layout_reduce(g, 0, &l);
 }
 
 int sttm_positions(sttm_ctx* ctx, const int32_t* cluster_ids_dev, const int32_t* node_map_dev,
