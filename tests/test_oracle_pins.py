@@ -690,3 +690,19 @@ def test_undefined_similarities_never_pass_a_threshold():
     assert tm.e[16 + 15] == -2.0 and tm.e[16 + 0] == 1.0
     rd = O.reduce_clusters(frame, tm.cluster_ids)
     assert list(rd.counts) == [31, 1]
+
+
+@pytest.mark.parametrize("kw", [dict(keep=0.5), dict(tau_s=0.85, tau_t=0.7, mode="most_similar", order="zscan")])
+def test_frames_spread_over_processes_give_the_serial_result(kw):
+    """oracle/parallel.py only cuts the frame axis: thresholds, maps, edges and merged rows equal the serial run's."""
+    from oracle import parallel as OP
+    cfg = wl.Workload("v", 77, 2, 7, 13, 13, 24, "bf16", 4, 0.1, 0.7)
+    feats = wl.generate(cfg)
+    sp0, tm0, rd0, info0 = O.sttm(feats, **kw)
+    sp1, tm1, rd1, info1 = OP.sttm_parallel(feats, procs=3, **kw)
+    assert info0 == info1
+    assert (sp0.node_map == sp1.node_map).all() and (sp0.node_level == sp1.node_level).all()
+    assert (tm0.parent == tm1.parent).all() and (tm0.cluster_ids == tm1.cluster_ids).all()
+    assert tm0.cands == tm1.cands and tm0.comparisons == tm1.comparisons and sp0.comparisons == sp1.comparisons
+    assert (rd0.counts == rd1.counts).all() and (rd0.out_ids == rd1.out_ids).all()
+    np.testing.assert_array_equal(rd0.merged, rd1.merged)
