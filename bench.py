@@ -130,6 +130,8 @@ def main() -> int:
     ap.add_argument("--positions", action="store_true", help="also emit the position indices of the rows each step")
     ap.add_argument("--no-cell-dots", action="store_true",
                     help="keep the spatial and temporal passes separate (sttm_set_cell_dots(0))")
+    ap.add_argument("--node-dots", action="store_true",
+                    help="frame-to-frame dot products of the 2x2 and 4x4 blocks in the spatial pass too (sttm_set_cell_dots(2))")
     ap.add_argument("--no-node-sums", action="store_true",
                     help="reduce stage without the stage-1 partition: every cell is read again")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -182,7 +184,7 @@ def main() -> int:
     s = lib.Sttm(0)
     s.sttm_set_match_mode({"first_passing": 0, "topleft_only": 1, "most_similar": 2}[args.match])
     s.sttm_set_output_order({"raster": 0, "zscan": 1}[args.order])
-    s.sttm_set_cell_dots(0 if args.no_cell_dots else 1)
+    s.sttm_set_cell_dots(0 if args.no_cell_dots else (2 if args.node_dots else 1))
     s.ensure_workspace(B, T, H, W, D, dt, R)
     node_map = torch.empty(N, dtype=torch.int32, device=dev)
     node_level = torch.empty(N, dtype=torch.uint8, device=dev)
@@ -250,7 +252,9 @@ def main() -> int:
             a, b = lv[:, 1:].int(), lv[:, :-1].int()
             J = torch.maximum(a, b)
             small = J <= 2
-            if not args.no_cell_dots:
+            if args.node_dots:
+                small = small & (a != b)
+            elif not args.no_cell_dots:
                 small = small & (J > 0)
             need_t = small | ((J >= 3) & (a < b))   # rows of the later frame of a pair
             need_p = small | ((J >= 3) & (b < a))   # rows of the earlier frame
@@ -319,7 +323,8 @@ def main() -> int:
                                + (f", match={args.match}" if args.match != "first_passing" else "")
                                + (f", order={args.order}" if args.order != "raster" else "")
                                + (", with position indices" if args.positions else "")
-                               + (", separate spatial and temporal passes" if args.no_cell_dots else ""),
+                               + (", separate spatial and temporal passes" if args.no_cell_dots else "")
+                               + (", block dot products in the spatial pass" if args.node_dots else ""),
                    "tokens": N, "kept_tokens": head["kept_tokens"], "kept_fraction": head["kept_fraction"],
                    "generate_s": gen_s, "input_copies": copies},
         "roofline": head["roofline"],

@@ -117,14 +117,16 @@ int sttm_invalidate(sttm_ctx* ctx);
 int sttm_set_match_mode(sttm_ctx* ctx, int mode);
 /* Row order of sttm_reduce and sttm_positions (sttm_order); applies to the calls that follow. */
 int sttm_set_output_order(sttm_ctx* ctx, int order);
-/* on = 1 (the default): the spatial statistics pass also computes x_c(t) . x_c(t+1) for every cell c and frame t
+/* level = 1 (the default): the spatial statistics pass also computes x_c(t) . x_c(t+1) for every cell c and frame t
  * (Sec. 3.3 compares the features of overlapping nodes of consecutive frames; where both nodes are single cells
  * that is this dot product), and the temporal pass leaves those pairs out instead of reading both rows again.
- * The statistics pass gets slower, the temporal pass much faster wherever many tokens stay unmerged in space;
- * on = 0 keeps the two passes separate (better when almost everything merges spatially). Results agree to
- * rounding. Takes effect with the next statistics pass (sttm_spatial_stats / sttm_spatial_quadtree with
- * thresholds). */
-int sttm_set_cell_dots(sttm_ctx* ctx, int on);
+ * level = 2: the same also for every 2x2 and 4x4 block (S_n(t) . S_n(t+1), used where both frames keep the same
+ * node n at level 1 or 2). level = 0 keeps the two passes separate. Each level makes the statistics pass slower
+ * and the temporal pass faster: 1 pays wherever many tokens stay unmerged in space, 0 when almost everything
+ * merges spatially, 2 only at small budgets (the extra arithmetic costs the statistics pass more than the
+ * temporal pass gains at budgets of 30 % and above). Results agree to rounding. Takes effect with the next
+ * statistics pass (sttm_spatial_stats / sttm_spatial_quadtree with thresholds). */
+int sttm_set_cell_dots(sttm_ctx* ctx, int level);
 
 /* ---- stage 1: spatial quadtree (Sec. 3.2) ------------------------------------------------------------- */
 

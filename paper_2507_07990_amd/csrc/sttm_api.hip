@@ -19,7 +19,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   size_t part, partu, nsum, nrm2, sim, m, sel_key_s, sel_w_s, sel_key_t, tau_s, tau_t, target_s, target_t, sel_s, sel_t, lvl,
-      pd_part, sig, e, parent, ptr_a, ptr_b;
+      titems, tcount, pd_part, sig, e, parent, ptr_a, ptr_b;
   size_t rank, key_a, val_a, key_b, val_b, order, orow, hist, tot, gsum, tile_roots, tile_live, seg, kdev,
       bigpart, bigw, biglist, zpos, possum, poscnt;
   size_t total;
@@ -100,6 +100,8 @@ Layout make_layout(const Geo& g) {
   l.sel_s = take(select_state_bytes(g.B));
   l.sel_t = take(select_state_bytes(g.B));
   l.lvl = take(N);
+  l.titems = take(temporal_items_bytes(g));
+  l.tcount = take(temporal_count_bytes());
   l.pd_part = take(F * g.nC * g.HW * sizeof(float));
   l.sig = take(N * sizeof(float));
   l.e = take(N * sizeof(float));
@@ -153,8 +155,8 @@ struct sttm_ctx {
   bool have_spatial = false, have_tau_s = false, have_temporal = false, have_tau_t = false;
   bool tau_s_pending = false, tau_t_pending = false;  // the budget search left its last digit to the consumer kernel
   int match_mode = STTM_MATCH_FIRST_PASSING, order = STTM_ORDER_RASTER;
-  bool cell_dots = true;        // setting: the spatial pass also emits the cell-to-cell dot products
-  bool have_cell_dots = false;  // the statistics in the workspace were computed with them
+  int cell_dots = 1;       // setting: the spatial pass also emits frame-to-frame dot products (0 no, 1 cells, 2 + 2x2 / 4x4 blocks)
+  int have_cell_dots = 0;  // what the statistics in the workspace were computed with
   const int32_t* cluster_ids_reduced = nullptr;  // cluster ids of the last reduce call (NULL: none since the shape was bound)
   bool reduced_zscan = false;
   const void* feats_spatial = nullptr;
@@ -239,7 +241,11 @@ int bind_shape(sttm_ctx* c, int dtype, int B, int T, int H, int W, int D, int ro
   c->have_spatial = c->have_tau_s = c->have_temporal = c->have_tau_t = false;
   c->tau_s_pending = c->tau_t_pending = false;
   c->cluster_ids_reduced = nullptr;
-  if (!same) c->target_s_on_device = c->target_t_on_device = false;  // the layout moved: upload targets again
+  if (!same) {
+    c->target_s_on_device = c->target_t_on_device = false;  // the layout moved: upload targets again
+    // the work queue of the temporal pass starts empty (afterwards every pass leaves it empty behind itself)
+    STTM_HIP(c, hipMemsetAsync(at<int>(c, c->lay.tcount), 0, temporal_count_bytes(), c->stream));
+  }
   return STTM_OK;
 }
 
@@ -280,7 +286,7 @@ int after_launch(sttm_ctx* c) { return hip_check(c, hipGetLastError(), "kernel l
 int run_spatial_stats(sttm_ctx* c, const void* feats) {
   {
     Timed t(c, STTM_KERNEL_PYRAMID_STATS);
-    launch_pyramid_stats(c->g, feats, c->cell_dots && c->g.T > 1, at<float>(c, c->lay.part),
+    launch_pyramid_stats(c->g, feats, c->g.T > 1 ? c->cell_dots : 0, at<float>(c, c->lay.part),
                          at<float>(c, c->lay.nsum), at<SelState>(c, c->lay.sel_s), c->stream);
   }
   launch_spatial_finalize(c->g, at<float>(c, c->lay.part), at<float>(c, c->lay.partu), at<float>(c, c->lay.nsum),
@@ -294,7 +300,7 @@ int run_spatial_stats(sttm_ctx* c, const void* feats) {
     c->have_spatial = true;
     c->have_temporal = false;
     c->feats_spatial = feats;
-    c->have_cell_dots = c->cell_dots && c->g.T > 1;
+    c->have_cell_dots = c->g.T > 1 ? c->cell_dots : 0;
   }
   return rc;
 }
@@ -303,12 +309,14 @@ int run_temporal_stats(sttm_ctx* c, const void* feats, const int32_t* node_map, 
   {
     Timed t(c, STTM_KERNEL_TEMPORAL_DOTS);
     launch_temporal_dots(c->g, feats, node_level, at<float>(c, c->lay.nsum), c->have_cell_dots,
-                         at<float>(c, c->lay.pd_part), at<SelState>(c, c->lay.sel_t), c->stream);
+                         at<float>(c, c->lay.pd_part), at<SelState>(c, c->lay.sel_t), at<char>(c, c->lay.titems),
+                         at<int>(c, c->lay.tcount), c->stream);
   }
-  launch_temporal_resolve(c->g, c->match_mode, node_map, node_level, at<float>(c, c->lay.pd_part),
+  launch_temporal_resolve(c->g, c->match_mode, c->have_cell_dots == 2 ? 2 : 0, node_map, node_level,
+                          at<float>(c, c->lay.pd_part),
                           c->have_cell_dots ? at<float>(c, c->lay.part) : nullptr, at<float>(c, c->lay.nrm2),
                           at<float>(c, c->lay.sig), at<float>(c, c->lay.e), at<uint32_t>(c, c->lay.sel_key_t),
-                          at<SelState>(c, c->lay.sel_t), c->stream);
+                          at<SelState>(c, c->lay.sel_t), at<int>(c, c->lay.tcount), c->stream);
   int rc = after_launch(c);
   // the search state of the temporal budget starts afresh with these statistics: a threshold chosen from the
   // statistics before them (or a last digit still pending) no longer applies
@@ -402,7 +410,7 @@ int sttm_invalidate(sttm_ctx* ctx) {
   if (!ctx) return STTM_ERR_NULL;
   ctx->have_spatial = ctx->have_tau_s = ctx->have_temporal = ctx->have_tau_t = false;
   ctx->tau_s_pending = ctx->tau_t_pending = false;
-  ctx->have_cell_dots = false;
+  ctx->have_cell_dots = 0;
   ctx->feats_spatial = nullptr;
   ctx->node_map_temporal = nullptr;
   ctx->cluster_ids_reduced = nullptr;
@@ -420,8 +428,8 @@ int sttm_set_match_mode(sttm_ctx* ctx, int mode) {
 
 int sttm_set_cell_dots(sttm_ctx* ctx, int on) {
   if (!ctx) return STTM_ERR_NULL;
-  if (on != 0 && on != 1) return fail(ctx, STTM_ERR_ARG, "cell dots: 0 or 1");
-  ctx->cell_dots = on != 0;  // takes effect with the next spatial statistics pass
+  if (on < 0 || on > 2) return fail(ctx, STTM_ERR_ARG, "cell dots: 0, 1 or 2");
+  ctx->cell_dots = on;  // takes effect with the next spatial statistics pass
   return STTM_OK;
 }
 

@@ -11,6 +11,14 @@
 #define STTM_DYNAMIC_LDS(T, name) T* name = reinterpret_cast<T*>(hip_emul::g_dynamic_lds)
 #endif
 
+// Keeps the instruction scheduler from moving anything across this point (used where hoisting the next batch of
+// loads above the work on the current one would cost more registers than the overlap is worth).
+#ifndef STTM_HOST_EMULATION
+#define STTM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#else
+#define STTM_SCHED_FENCE() ((void)0)
+#endif
+
 namespace sttm {
 
 constexpr int kWave = 64;
@@ -343,8 +351,9 @@ __device__ inline float sel_last_digit(const SelState* __restrict__ st) {
 // ---- launchers (defined in the .hip files; all asynchronous on `s`) ------------------------------------
 
 // `sel`: the spatial search states [B]; cleared by the statistics pass, level 0 filled by the finalize kernel.
-// `cell_dots`: also leave x_c(t) . x_c(t+1) of every cell in `part` (the temporal stage then skips those pairs).
-void launch_pyramid_stats(const Geo& g, const void* feats, bool cell_dots, float* part, float* nsum, SelState* sel,
+// `cell_dots`: 1 = also leave x_c(t) . x_c(t+1) of every cell in `part` (the temporal stage then skips those pairs);
+// 2 = and S_n(t) . S_n(t+1) of every 2x2 and 4x4 block n.
+void launch_pyramid_stats(const Geo& g, const void* feats, int cell_dots, float* part, float* nsum, SelState* sel,
                           hipStream_t s);
 // Also works out the levels above an 8x8 unit from the stored unit sums (extends `part` and `nsum`).
 void launch_spatial_finalize(const Geo& g, const float* part, float* partu, float* nsum, float* nrm2, float* sim, float* m,
@@ -361,29 +370,42 @@ void launch_select_temporal(const Geo& g, const int32_t* node_map, const uint32_
                             SelState* state, bool dirty, float* tau, hipStream_t s);
 inline size_t select_state_bytes(int B) { return (size_t)B * sizeof(SelState); }
 // `sel`: the temporal search states [B]; cleared here, level 0 filled by launch_temporal_resolve.
-// `skip_cells`: pairs of two single cells are left out (their dot products are in the spatial pass's `part`).
+// `skip_same`: 0 = every pair is computed here; 1 = pairs of two single cells are left out, 2 = also pairs of the same
+// 2x2 or 4x4 block in both frames (their dot products are in the spatial pass's `part`).
+// `items` (temporal_items_bytes() of them) / `item_count`: the work queue of the pass; the count must be zero on
+// entry (launch_temporal_resolve leaves it so).
 void launch_temporal_dots(const Geo& g, const void* feats, const uint8_t* node_level, const float* nsum,
-                          bool skip_cells, float* pd_part, SelState* sel, hipStream_t s);
+                          int skip_same, float* pd_part, SelState* sel, void* items, int* item_count,
+                          hipStream_t s);
+size_t temporal_items_bytes(const Geo& g);
+size_t temporal_count_bytes();
 // The first pass works in 8x8-cell units (one wavefront per unit, chunk and frame) and leaves each unit's scalars
 // as one block of kUnitScalars floats: per 4x4 tile 16 squared norms, 16 cell and 4 level-1 dot products, then the
 // 4 level-2 dot products (padded to whole 128-byte lines), then per tile the 16 dot products of its cells with the
-// same cells of the next frame (zeros unless asked for): part[f][chunk][unit][kUnitScalars].
-constexpr int kUnitScalars = 224;
+// same cells of the next frame, then per tile the dot products of its four 2x2 blocks and of the tile itself with the
+// same blocks of the next frame (zeros unless asked for): part[f][chunk][unit][kUnitScalars].
+constexpr int kUnitScalars = 256;
 constexpr int kUnitCellDots = 160;
+constexpr int kUnitNodeDots = 224;
 // Offset of cell (y, x)'s cell-to-cell dot product inside its unit's block.
 inline __host__ __device__ int unit_cell_dot_slot(int y, int x) {
   return kUnitCellDots + (((y >> 2) & 1) * 2 + ((x >> 2) & 1)) * 16 + (((y >> 1) & 1) * 2 + ((x >> 1) & 1)) * 4 +
          (y & 1) * 2 + (x & 1);
+}
+// Offset of the frame-to-frame dot product of the node at level 1 or 2 whose top-left cell is (y, x).
+inline __host__ __device__ int unit_node_dot_slot(int lvl, int y, int x) {
+  return kUnitNodeDots + (((y >> 2) & 1) * 2 + ((x >> 2) & 1)) * 8 + (lvl == 2 ? 4 : ((y >> 1) & 1) * 2 + ((x >> 1) & 1));
 }
 inline __host__ __device__ int unit_cols(const Geo& g) { return (g.W + 7) >> 3; }
 inline __host__ __device__ int unit_rows(const Geo& g) { return (g.H + 7) >> 3; }
 // fp32 sums of the pyramid nodes at levels >= 3: [F][nsum_nodes][D]
 inline size_t nsum_nodes(const Geo& g) { return g.L >= 3 ? (size_t)(g.NN - g.lvl_base[3]) : 0; }
 // `match`: destination rule (0 = top-left-most passing, 1 = the one under the top-left cell only, 2 = most similar).
-// `cell_part`: the spatial pass's `part` when it holds the cell-to-cell dot products (else NULL).
-void launch_temporal_resolve(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
+// `cell_part`: the spatial pass's `part` when it holds frame-to-frame dot products (else NULL), `same_level`: of the
+// same node in both frames up to this level (0 = single cells only, 2 = up to 4x4 blocks).
+void launch_temporal_resolve(const Geo& g, int match, int same_level, const int32_t* node_map, const uint8_t* node_level,
                              const float* pd_part, const float* cell_part, const float* nrm2, float* sig, float* e,
-                             uint32_t* sel_key, SelState* sel, hipStream_t s);
+                             uint32_t* sel_key, SelState* sel, int* item_count, hipStream_t s);
 void launch_temporal_parent(const Geo& g, int match, const int32_t* node_map, const uint8_t* node_level,
                             const float* sig, float* tau, const SelState* pending, int32_t* parent, int32_t* ptr,
                             hipStream_t s);

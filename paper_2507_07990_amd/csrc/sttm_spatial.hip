@@ -142,7 +142,7 @@ __device__ __forceinline__ void tile_stats_reduce(const Geo& g, float* tb, int l
   wave_lds_fence();
 }
 
-template <int DT, bool CC>
+template <int DT, int CC>  // CC: 0 = statistics only, 1 = + cell-to-cell dot products, 2 = + the same for levels 1 and 2
 __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
                                                       float* __restrict__ part, float* __restrict__ nsum,
                                                       SelState* __restrict__ sel) {
@@ -201,6 +201,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
                       none ? x3 : x3 + (n & 1) * 4, none ? 1 : nh, none ? 1 : nw);
       }
       if (lane < 16) st[kUnitCellDots + q2 * 16 + lane] = 0.f;
+      if (lane < 8) st[kUnitNodeDots + q2 * 8 + lane] = 0.f;
       if (th > 0 && tw > 0) {
         tile_mask<DT>((q2 & 1) ? bufB : bufA, th, tw, act);
         tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, th, tw, st + q2 * kTileRows, S2[q2]);
@@ -219,10 +220,49 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
               const float d = R::dot(((q2 & 1) ? bufB : bufA)[i], bufN[i]);
               tb[i * kRowStride + lane] = act ? d : 0.f;  // (a lane beyond the last channel read channel 0's data)
             }
+            if (CC >= 2) {
+            // The same for the tile's four 2x2 blocks and for the tile itself: S_n(t) . S_n(t+1), the dot product the
+            // temporal stage needs where both frames keep the same node n at level 1 or 2. A block's is the sum of
+            // the sixteen products of its rows in the two frames (straight from the packed rows: the blocks' sums
+            // of the statistics above are gone, and keeping them would not fit the registers); the tile's comes
+            // from its sum, which is still at hand, and the partner tile's sum.
+            tile_mask<DT>(bufN, th, tw, act);
+            float SN2[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) SN2[v] = 0.f;
+#pragma unroll
+            for (int q1 = 0; q1 < 4; ++q1) {
+              float d1 = 0.f;
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) d1 += R::dot(((q2 & 1) ? bufB : bufA)[q1 * 4 + k], bufN[q1 * 4 + kk]);
+                float xv[VEC];
+                R::unpack(bufN[q1 * 4 + k], xv);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) SN2[v] += xv[v];
+              }
+              tb[(16 + q1) * kRowStride + lane] = d1;
+            }
+            float d2 = 0.f;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) d2 = fmaf(S2[q2][v], SN2[v], d2);
+            tb[20 * kRowStride + lane] = d2;
+            }
             wave_lds_fence();
-            if (lane < 16) {
-              const int q1 = lane >> 2, k = lane & 3;
-              if ((q1 >> 1) * 2 + (k >> 1) < th && (q1 & 1) * 2 + (k & 1) < tw) {
+            if (lane < (CC >= 2 ? 21 : 16)) {
+              bool live = true;  // the tile itself holds valid cells
+              int dst = kUnitNodeDots + q2 * 8 + 4;
+              if (lane < 16) {
+                const int q1 = lane >> 2, k = lane & 3;
+                live = (q1 >> 1) * 2 + (k >> 1) < th && (q1 & 1) * 2 + (k & 1) < tw;
+                dst = kUnitCellDots + q2 * 16 + lane;
+              } else if (lane < 20) {
+                const int q1 = lane - 16;
+                live = (q1 >> 1) * 2 < th && (q1 & 1) * 2 < tw;
+                dst = kUnitNodeDots + q2 * 8 + q1;
+              }
+              if (live) {
                 const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
                 float acc = 0.f;
 #pragma unroll
@@ -230,7 +270,7 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
                   float4 q = row[j];
                   acc += (q.x + q.y) + (q.z + q.w);
                 }
-                st[kUnitCellDots + q2 * 16 + lane] = acc;
+                st[dst] = acc;
               }
             }
             wave_lds_fence();
@@ -331,26 +371,32 @@ __device__ inline void pyramid_upper_node(const Geo& g, float* partu, float* nsu
   }
 }
 
-void launch_pyramid_stats(const Geo& g, const void* feats, bool cell_dots, float* part, float* nsum, SelState* sel,
-                          hipStream_t s) {
+template <int CC>
+static void launch_pyramid_cc(const Geo& g, const void* feats, float* part, float* nsum, SelState* sel, hipStream_t s) {
   const int NU = unit_cols(g) * unit_rows(g);
-  const dim3 block(64);
-  if (cell_dots) {
-    const dim3 grid((unsigned)(8 * ((g.F + 7) / 8) * NU * g.nC));
-    if (g.dtype == 1)
-      hipLaunchKernelGGL((k_pyramid_stats<1, true>), grid, block, 0, s, g, feats, part, nsum, sel);
-    else if (g.dtype == 2)
-      hipLaunchKernelGGL((k_pyramid_stats<2, true>), grid, block, 0, s, g, feats, part, nsum, sel);
-    else
-      hipLaunchKernelGGL((k_pyramid_stats<0, true>), grid, block, 0, s, g, feats, part, nsum, sel);
+  const dim3 grid((unsigned)(8 * ((g.F + 7) / 8) * NU * g.nC)), block(64);
+  if (g.dtype == 1)
+    hipLaunchKernelGGL((k_pyramid_stats<1, CC>), grid, block, 0, s, g, feats, part, nsum, sel);
+  else if (g.dtype == 2)
+    hipLaunchKernelGGL((k_pyramid_stats<2, CC>), grid, block, 0, s, g, feats, part, nsum, sel);
+  else
+    hipLaunchKernelGGL((k_pyramid_stats<0, CC>), grid, block, 0, s, g, feats, part, nsum, sel);
+}
+
+void launch_pyramid_stats(const Geo& g, const void* feats, int cell_dots, float* part, float* nsum, SelState* sel,
+                          hipStream_t s) {
+  if (cell_dots >= 2) {
+    launch_pyramid_cc<2>(g, feats, part, nsum, sel, s);
+  } else if (cell_dots == 1) {
+    launch_pyramid_cc<1>(g, feats, part, nsum, sel, s);
   } else {
-    const dim3 grid(g.nC, NU, g.F);
+    const dim3 grid(g.nC, unit_cols(g) * unit_rows(g), g.F), block(64);
     if (g.dtype == 1)
-      hipLaunchKernelGGL((k_pyramid_stats<1, false>), grid, block, 0, s, g, feats, part, nsum, sel);
+      hipLaunchKernelGGL((k_pyramid_stats<1, 0>), grid, block, 0, s, g, feats, part, nsum, sel);
     else if (g.dtype == 2)
-      hipLaunchKernelGGL((k_pyramid_stats<2, false>), grid, block, 0, s, g, feats, part, nsum, sel);
+      hipLaunchKernelGGL((k_pyramid_stats<2, 0>), grid, block, 0, s, g, feats, part, nsum, sel);
     else
-      hipLaunchKernelGGL((k_pyramid_stats<0, false>), grid, block, 0, s, g, feats, part, nsum, sel);
+      hipLaunchKernelGGL((k_pyramid_stats<0, 0>), grid, block, 0, s, g, feats, part, nsum, sel);
   }
 }
 

@@ -71,6 +71,7 @@ void launch(dim3 grid, dim3 block, void (*body)(void*), void* closure);
 inline void __syncthreads() { pthread_barrier_wait(&hip_emul::g_block_bar); }
 #define __builtin_amdgcn_fence(order, scope) __atomic_thread_fence(__ATOMIC_SEQ_CST)
 #define __builtin_amdgcn_wave_barrier() hip_emul::wave_sync()
+#define __builtin_amdgcn_readfirstlane(x) (x)  // only applied to values that are the same in every lane
 
 inline float __uint_as_float(unsigned u) { float f; memcpy(&f, &u, 4); return f; }
 inline unsigned __float_as_uint(float f) { unsigned u; memcpy(&u, &f, 4); return u; }
@@ -194,6 +195,7 @@ inline hipError_t hipMemcpyAsync(void* d, const void* s, size_t n, hipMemcpyKind
   memcpy(d, s, n);
   return hipSuccess;
 }
+inline hipError_t hipMemsetAsync(void* d, int v, size_t n, hipStream_t) { memset(d, v, n); return hipSuccess; }
 inline hipError_t hipEventCreate(hipEvent_t* e) { *e = nullptr; return hipSuccess; }
 inline hipError_t hipEventDestroy(hipEvent_t) { return hipSuccess; }
 inline hipError_t hipEventRecord(hipEvent_t, hipStream_t) { return hipSuccess; }

@@ -418,6 +418,7 @@ def test_positions_and_settings_error_paths(lib):
     (70, 2, 6, 13, 13, 136, "bf16", dict(keep=0.5)),
     (71, 1, 5, 16, 16, 64, "f32", dict(tau_s=0.95, tau_t=0.6)),
     (72, 1, 4, 14, 14, 520, "f16", dict(tau_s=0.7, tau_t=0.7, root_grid=4)),
+    (73, 1, 5, 27, 27, 72, "bf16", dict(tau_s=0.6, tau_t=0.5)),       # many 2x2 and 4x4 nodes, ragged edge
 ])
 def test_temporal_pass_without_the_cell_dot_products(lib, seed, B, T, H, W, D, dtype, kw):
     """sttm_set_cell_dots(0): the temporal pass computes the cell-to-cell pairs itself. Parity with the oracle, and
@@ -427,16 +428,17 @@ def test_temporal_pass_without_the_cell_dot_products(lib, seed, B, T, H, W, D, d
     s = lib.Sttm(0)
     off = P.run_gpu(lib, feats, ctx=s, cell_dots=0, **kw)
     P.check_parity(lib, feats, off, **kw)
-    on = P.run_gpu(lib, feats, ctx=s, cell_dots=1, **kw)     # same context: the setting applies to the next pass
-    assert (on.node_map == off.node_map).all() and (on.cluster_ids == off.cluster_ids).all() and on.K == off.K
-    P.check_parity(lib, feats, on, **kw)
+    for level in (1, 2):                                       # same context: the setting applies to the next pass
+        on = P.run_gpu(lib, feats, ctx=s, cell_dots=level, **kw)
+        assert (on.node_map == off.node_map).all() and (on.cluster_ids == off.cluster_ids).all() and on.K == off.K
+        P.check_parity(lib, feats, on, **kw)
 
 
 def test_cell_dot_setting_and_feature_pointer_error_paths(lib):
     import torch
     s = lib.Sttm(0)
     with pytest.raises(lib.SttmError) as e:
-        s.sttm_set_cell_dots(2)
+        s.sttm_set_cell_dots(3)
     assert e.value.code == lib.STTM_ERR_ARG
     cfg = wl.CONFIGS[0]
     feats = wl.generate(cfg)
@@ -473,9 +475,10 @@ def test_config2_encoder_width_budget(lib):
     _run_and_check(lib, cfg, keep=cfg.budgets[0])
 
 
-@pytest.mark.parametrize("keep,cell_dots", [(0.5, 1), (0.3, 1), (0.5, 0)])
+@pytest.mark.parametrize("keep,cell_dots", [(0.5, 1), (0.3, 1), (0.5, 0), (0.3, 2)])
 def test_config3_long_video_budget(lib, keep, cell_dots):
-    """The bench workload at both budgets; once more with the spatial and temporal passes kept separate."""
+    """The bench workload at both budgets; once more with the spatial and temporal passes kept separate, and once
+    with the frame-to-frame dot products of the 2x2 and 4x4 blocks taken in the spatial pass too."""
     cfg = wl.CONFIGS[3]
     _run_and_check(lib, cfg, keep=keep, cell_dots=cell_dots)
 
