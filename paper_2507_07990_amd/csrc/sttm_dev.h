@@ -81,6 +81,10 @@ template <> struct Row<0> {
   __device__ static inline float dot(const Raw& a, const Raw& b) {
     return fmaf(a.x, b.x, fmaf(a.y, b.y, fmaf(a.z, b.z, a.w * b.w)));
   }
+  // S += the row's channels
+  __device__ static inline void add_row(const Raw& r, float (&S)[4]) {
+    S[0] += r.x; S[1] += r.y; S[2] += r.z; S[3] += r.w;
+  }
 };
 
 template <> struct Row<1> {
@@ -111,6 +115,29 @@ template <> struct Row<1> {
     return d;
 #endif
   }
+  // S += the row's channels. The same packed instruction, with the pair (1, 0) or (0, 1) as its second operand,
+  // widens one element of a pair and adds it to the running sum in one step (x * 1 + y * 0: exact; only an
+  // infinity or a NaN in the other element of the pair spills over, into a sum that is undefined then anyway).
+  __device__ static inline void add_row(const Raw& r, float (&S)[8]) {
+#ifndef STTM_HOST_EMULATION
+    typedef __bf16 pair __attribute__((ext_vector_type(2)));
+    // (the two selectors are handed over as register contents the compiler cannot look into: written as constants
+    // it encodes (1, 0) as the inline operand "1.0", which the instruction does not read as this pair)
+    uint32_t klo, khi;
+    asm volatile("s_mov_b32 %0, 0x3f80\n\ts_mov_b32 %1, 0x3f800000" : "=s"(klo), "=s"(khi));
+    const pair lo = __builtin_bit_cast(pair, klo), hi = __builtin_bit_cast(pair, khi);
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      S[2 * j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, w[j]), lo, S[2 * j], false);
+      S[2 * j + 1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, w[j]), hi, S[2 * j + 1], false);
+    }
+#else
+    float x[8];
+    unpack(r, x);
+    for (int v = 0; v < 8; ++v) S[v] += x[v];
+#endif
+  }
 };
 
 template <> struct Row<2> {
@@ -137,6 +164,25 @@ template <> struct Row<2> {
     unpack(b, y);
     for (int v = 0; v < 8; ++v) d = fmaf(x[v], y[v], d);
     return d;
+#endif
+  }
+  // S += the row's channels (see Row<1>::add_row)
+  __device__ static inline void add_row(const Raw& r, float (&S)[8]) {
+#ifndef STTM_HOST_EMULATION
+    typedef _Float16 pair __attribute__((ext_vector_type(2)));
+    uint32_t klo, khi;  // (as register contents, see Row<1>::add_row)
+    asm volatile("s_mov_b32 %0, 0x3c00\n\ts_mov_b32 %1, 0x3c000000" : "=s"(klo), "=s"(khi));
+    const pair lo = __builtin_bit_cast(pair, klo), hi = __builtin_bit_cast(pair, khi);
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      S[2 * j] = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, w[j]), lo, S[2 * j], false);
+      S[2 * j + 1] = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, w[j]), hi, S[2 * j + 1], false);
+    }
+#else
+    float x[8];
+    unpack(r, x);
+    for (int v = 0; v < 8; ++v) S[v] += x[v];
 #endif
   }
 };

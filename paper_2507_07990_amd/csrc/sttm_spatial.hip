@@ -4,34 +4,12 @@
 
 namespace sttm {
 
-// ------------------------------------------------------------------------------------------------
-// k_pyramid_stats: the one pass over the features of the spatial stage.
-//
-// One workgroup per (chunk, unit, frame) -- a 3-D grid, or a 1-D grid decoded die by die when the cell-to-cell dot
-// products are wanted (template parameter CC, see below); a workgroup is ONE wavefront that owns a "unit" = an 8x8
-// cell block (level 3) of one frame for one chunk of the token rows. Units at the ragged edge of the grid are smaller, but every
-// workgroup is a single wavefront, so the hardware dispatcher evens the load out. A lane owns VEC
-// consecutive channels, so all pyramid sums are private to the lane and only scalars are reduced across
-// lanes: the wavefront stages its per-lane partial scalars in LDS as [scalar][lane] and then lets lane r
-// add up row r.
-// The unit is walked quadrant by quadrant: 4 tiles (4x4, level 2) of 4 level-1 blocks of 4 cells. The row
-// loads of the next tile are issued before the current one is worked on; cells and blocks beyond the
-// grid's edge cost no arithmetic (the tests are wave-uniform) and no memory traffic (their loads hit a row
-// the tile has just fetched).
-// Scalars: the squared norm of every cell, and for every node below the root the dot product of its sum
-// with its parent's sum. (The squared norm of a parent is the sum of its children's dot products with it,
-// which the finalize kernel adds up.)
-// With CC the wavefront also reads each tile of the next frame and forms x_c(t) . x_c(t+1) for the tile's cells (the
-// dot products the temporal stage needs where both frames keep single cells).
-// Output: part[f][chunk][unit][kUnitScalars] = the workgroup's scalars, partial over this chunk's channels, written
-//         as one block: per tile 16 squared norms, 16 cell and 4 level-1 dot products (child sum . parent sum), then
-//         the 4 level-2 dot products, then per tile the 16 cell-to-cell dot products (zeros without CC); the levels
-//         from 3 up are the finalize kernel's when the pyramid is taller than a unit;
-//         nsum[f][node - first level-3 node][D] = the per-channel sums of the level-3 nodes (fp32), which
-//         the later stages read instead of re-adding up to 64 token rows.
-// ------------------------------------------------------------------------------------------------
 constexpr int kTileRows = 36;    // 16 n0 + 16 d0 + 4 d1
-constexpr int kRowStride = 68;   // 64 lanes + pad, keeps 16-byte alignment of every row
+// Rows of the staging area per tile, in batches of eight: four batches of the 2x2 blocks' statistics, one of the
+// blocks' dot products with the tile (4) and with the next frame (4), two of the cell-to-cell dot products, one for
+// the tile with the next frame.
+constexpr int kStageRows = 64;
+constexpr int kStageStride = 8;  // floats per staging row: one per group of eight lanes
 
 // Issues the row loads of the tile whose top-left cell is (ty, tx); th x tw of its 4x4 cells are valid
 // (th, tw >= 1). Every one of the 16 loads is issued, without a condition: a cell beyond the edge, or a lane
@@ -62,11 +40,63 @@ __device__ __forceinline__ void tile_mask(typename Row<DT>::Raw (&raw)[16], int 
   }
 }
 
-// Sums and per-lane scalars of one tile; returns the tile's per-channel sum in S2 and leaves the lanes' partial
-// scalars of the tile's cells and level-1 blocks in the reduction buffer (tile_stats_reduce adds them up).
+// Eight scalars of the wavefront at once (v[i] = this lane's share of scalar i): returns, in lane l, the sum of
+// scalar (l & 7) over the eight lanes of l's group (l >> 3). Three exchanges, each halving the scalars a lane
+// carries: with the neighbour (lane ^ 1), across the quad (^ 2), across the two quads (^ 4).
+__device__ __forceinline__ float group_sums8(const float (&v)[8], int lane) {
+  const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+  float a[4], c[2];
+#ifndef STTM_HOST_EMULATION
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float keep = b0 ? v[2 * i + 1] : v[2 * i], give = b0 ? v[2 * i] : v[2 * i + 1];
+    a[i] = keep + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(give), 0xB1, 0xF, 0xF, true));  // quad_perm [1,0,3,2]
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float keep = b1 ? a[2 * i + 1] : a[2 * i], give = b1 ? a[2 * i] : a[2 * i + 1];
+    c[i] = keep + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(give), 0x4E, 0xF, 0xF, true));  // quad_perm [2,3,0,1]
+  }
+  const float keep = b2 ? c[1] : c[0], give = b2 ? c[0] : c[1];
+  int r = __builtin_amdgcn_update_dpp(0, __float_as_int(give), 0x104, 0xF, 0x5, true);  // lanes 0-3, 8-11 of a row: from lane + 4
+  r = __builtin_amdgcn_update_dpp(r, __float_as_int(give), 0x114, 0xF, 0xA, true);      // lanes 4-7, 12-15: from lane - 4
+  return keep + __int_as_float(r);
+#else
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float keep = b0 ? v[2 * i + 1] : v[2 * i], give = b0 ? v[2 * i] : v[2 * i + 1];
+    a[i] = keep + __shfl_xor(give, 1, 64);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float keep = b1 ? a[2 * i + 1] : a[2 * i], give = b1 ? a[2 * i] : a[2 * i + 1];
+    c[i] = keep + __shfl_xor(give, 2, 64);
+  }
+  const float keep = b2 ? c[1] : c[0], give = b2 ? c[0] : c[1];
+  return keep + __shfl_xor(give, 4, 64);
+#endif
+}
+
+// Eight scalars go into the staging area as rows 8 * batch .. 8 * batch + 7, each row the eight partial sums of one
+// scalar over the groups of eight lanes: one store per lane, all to different words. (Every lane calls it.)
+__device__ __forceinline__ void stage8(float* tbs, int batch, int lane, const float (&v)[8]) {
+  tbs[(batch * 8 + (lane & 7)) * kStageStride + (lane >> 3)] = group_sums8(v, lane);
+}
+
+// Adds row `row` of the staging area up (a fixed order).
+__device__ __forceinline__ float staged_row_sum(const float* tbs, int row) {
+  const float4* p = reinterpret_cast<const float4*>(tbs + row * kStageStride);
+  const float4 a = p[0], b = p[1];
+  return ((a.x + a.y) + (a.z + a.w)) + ((b.x + b.y) + (b.z + b.w));
+}
+
+// Sums and per-lane scalars of one tile: returns the tile's per-channel sum in S2 and stages the tile's scalars --
+// batch q1 (rows 8 q1 .. 8 q1 + 7): squared norms of the four cells of 2x2 block q1, then each cell . the block's
+// sum; p1[q1]: block sum . tile sum, left to the caller to stage (zero for cells and blocks beyond the edge).
+// The rows must be zero for cells beyond the edge and for lanes beyond the last channel (tile_mask).
 template <int DT>
-__device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>::Raw (&raw)[16], float* tb,
-                                           int lane, int th, int tw, float* st, float (&S2)[Row<DT>::VEC]) {
+__device__ __forceinline__ void tile_stats(const typename Row<DT>::Raw (&raw)[16], float* tbs, int lane, int th, int tw,
+                                           float (&p1)[4], float (&S2)[Row<DT>::VEC]) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
 #pragma unroll
@@ -77,86 +107,111 @@ __device__ __forceinline__ void tile_stats(const Geo& g, const typename Row<DT>:
 #pragma unroll
     for (int v = 0; v < VEC; ++v) S1[q1][v] = 0.f;
     if ((q1 >> 1) * 2 >= th || (q1 & 1) * 2 >= tw) continue;  // block beyond the edge (wave-uniform)
-    float x[4][VEC];
+    // the block's sum, channel by channel; a cell's dot product with it is the sum of the cell's dot products with
+    // the block's four cells, which come straight from the packed rows (no element is widened for them)
 #pragma unroll
-    for (int k = 0; k < 4; ++k) R::unpack(raw[q1 * 4 + k], x[k]);
+    for (int k = 0; k < 4; ++k) R::add_row(raw[q1 * 4 + k], S1[q1]);
+    float nd[8];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) S1[q1][v] = (x[0][v] + x[1][v]) + (x[2][v] + x[3][v]);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if ((q1 >> 1) * 2 + (k >> 1) >= th || (q1 & 1) * 2 + (k & 1) >= tw) continue;
-      float n0 = 0.f, d0 = 0.f;
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) {
-        n0 = fmaf(x[k][v], x[k][v], n0);
-        d0 = fmaf(x[k][v], S1[q1][v], d0);
-      }
-      tb[(q1 * 4 + k) * kRowStride + lane] = n0;
-      tb[(16 + q1 * 4 + k) * kRowStride + lane] = d0;
+    for (int k = 0; k < 4; ++k) nd[k] = R::dot(raw[q1 * 4 + k], raw[q1 * 4 + k]);  // (zero rows give zero)
+    {
+      const float p01 = R::dot(raw[q1 * 4 + 0], raw[q1 * 4 + 1]), p02 = R::dot(raw[q1 * 4 + 0], raw[q1 * 4 + 2]);
+      const float p03 = R::dot(raw[q1 * 4 + 0], raw[q1 * 4 + 3]), p12 = R::dot(raw[q1 * 4 + 1], raw[q1 * 4 + 2]);
+      const float p13 = R::dot(raw[q1 * 4 + 1], raw[q1 * 4 + 3]), p23 = R::dot(raw[q1 * 4 + 2], raw[q1 * 4 + 3]);
+      nd[4] = (nd[0] + p01) + (p02 + p03);
+      nd[5] = (nd[1] + p01) + (p12 + p13);
+      nd[6] = (nd[2] + p02) + (p12 + p23);
+      nd[7] = (nd[3] + p03) + (p13 + p23);
     }
+    stage8(tbs, q1, lane, nd);
 #pragma unroll
     for (int v = 0; v < VEC; ++v) S2[v] += S1[q1][v];
   }
 #pragma unroll
   for (int q1 = 0; q1 < 4; ++q1) {
-    if ((q1 >> 1) * 2 >= th || (q1 & 1) * 2 >= tw) continue;
     float d1 = 0.f;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) d1 = fmaf(S1[q1][v], S2[v], d1);
-    tb[(32 + q1) * kRowStride + lane] = d1;
+    p1[q1] = d1;
   }
 }
 
-// Second half of a tile's statistics: adds the per-lane scalars up across the wavefront and leaves them in `st`.
-__device__ __forceinline__ void tile_stats_reduce(const Geo& g, float* tb, int lane, int th, int tw, float* st) {
-  wave_lds_fence();
-  if (lane < kTileRows) {
-    // which node / table does row `lane` belong to
-    const int r = lane;
-    int lvl, dy, dx;
-    bool is_dot;
-    if (r < 32) {
-      is_dot = r >= 16;
-      const int q1 = (r & 15) >> 2, k = r & 3;
-      lvl = 0;
-      dy = (q1 >> 1) * 2 + (k >> 1);
-      dx = (q1 & 1) * 2 + (k & 1);
-    } else {
-      is_dot = true;
-      const int q1 = r - 32;
-      lvl = 1;
-      dy = (q1 >> 1) * 2;
-      dx = (q1 & 1) * 2;
-    }
-    float acc = 0.f;
-    if (dy < th && dx < tw && !(is_dot && lvl >= g.L) && lvl <= g.L) {
-      const float4* row = reinterpret_cast<const float4*>(tb + r * kRowStride);
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        float4 q = row[j];
-        acc += (q.x + q.y) + (q.z + q.w);
-      }
-    }
-    st[r] = acc;
-  }
-  wave_lds_fence();
+// Asks for 16 bytes per lane straight into LDS: lane l's piece lands at byte address lds_row + 16 l of the
+// workgroup's LDS (`lds_row` is the same in all lanes). No registers are involved; it completes in order with the
+// wavefront's other loads. Written as an instruction of its own (the register that carries the LDS address is
+// saved and put back) so that the compiler, which would wait for every load in flight at the next use of any loaded
+// register once it has seen such a request, goes on counting the ordinary loads exactly; the wavefront waits for
+// these rows itself (wait_loads_but) before it reads them.
+template <class Elem>
+__device__ __forceinline__ void load_row_to_lds(void* lds_base, int row_bytes, const Elem* src_lane, int lane) {
+#ifndef STTM_HOST_EMULATION
+  const unsigned dst = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds_base + (unsigned)row_bytes;
+  unsigned keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(src_lane), "s"(dst)
+               : "memory");
+#else
+  memcpy(static_cast<char*>(lds_base) + row_bytes + 16 * lane, src_lane, 16);
+#endif
 }
 
+// Waits until at most `newer` (0 or 16) of the wavefront's loads are still on their way (they complete in issue
+// order), and until its earlier LDS traffic is through.
+__device__ __forceinline__ void wait_loads_but(int newer) {
+#ifndef STTM_HOST_EMULATION
+  if (newer >= 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#endif
+}
+
+// ------------------------------------------------------------------------------------------------
+// k_pyramid_stats: the one pass over the features of the spatial stage.
+//
+// One workgroup per (chunk, unit, frame) -- a 3-D grid, or a 1-D grid decoded die by die when the frame-to-frame dot
+// products are wanted (template parameter CC, see below); a workgroup is ONE wavefront that owns a "unit" = an 8x8
+// cell block (level 3) of one frame for one chunk of the token rows. Units at the ragged edge of the grid are
+// smaller, but every workgroup is a single wavefront, so the hardware dispatcher evens the load out. A lane owns VEC
+// consecutive channels, so all pyramid sums are private to the lane and only scalars are reduced across lanes:
+// three exchanges between lanes leave eight partial sums per scalar, which go through a small LDS area
+// ([scalar][8]) to the lane that adds them up.
+// The unit is walked quadrant by quadrant: 4 tiles (4x4, level 2) of 4 level-1 blocks of 4 cells. The row
+// loads of the next tile are issued before the current one is worked on; cells and blocks beyond the
+// grid's edge cost no arithmetic (the tests are wave-uniform) and no memory traffic (their loads hit a row
+// the tile has just fetched).
+// Scalars: the squared norm of every cell, and for every node below the root the dot product of its sum
+// with its parent's sum. (The squared norm of a parent is the sum of its children's dot products with it,
+// which the finalize kernel adds up.)
+// With CC the wavefront also needs each tile of the next frame, for x_c(t) . x_c(t+1) of the tile's cells (the dot
+// products the temporal stage needs where both frames keep single cells): its 16 rows are asked for straight into
+// LDS as soon as the tile's own rows have arrived -- no registers are held for them -- travel while the tile's
+// statistics are worked out, and are read back for the dot products.
+// Output: part[f][chunk][unit][kUnitScalars] = the workgroup's scalars, partial over this chunk's channels, written
+//         as one block: per tile 16 squared norms, 16 cell and 4 level-1 dot products (child sum . parent sum), then
+//         the 4 level-2 dot products, then per tile the 16 cell-to-cell dot products and the 4 + 1 of its blocks and
+//         itself (zeros without CC); the levels from 3 up are the finalize kernel's when the pyramid is taller than
+//         a unit;
+//         nsum[f][node - first level-3 node][D] = the per-channel sums of the level-3 nodes (fp32), which
+//         the later stages read instead of re-adding up to 64 token rows.
+// (Two wavefronts per SIMD asked for: the CC = 2 instances would otherwise take a few registers more than half the
+// file and run alone on their SIMD.)
+// ------------------------------------------------------------------------------------------------
 template <int DT, int CC>  // CC: 0 = statistics only, 1 = + cell-to-cell dot products, 2 = + the same for levels 1 and 2
-__global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
-                                                      float* __restrict__ part, float* __restrict__ nsum,
-                                                      SelState* __restrict__ sel) {
+__global__ __launch_bounds__(64, 2) void k_pyramid_stats(Geo g, const void* __restrict__ feats_v,
+                                                         float* __restrict__ part, float* __restrict__ nsum,
+                                                         SelState* __restrict__ sel) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
-  __shared__ float tb[kTileRows * kRowStride];
+  __shared__ __attribute__((aligned(16))) float tbs[kStageRows * kStageStride];
   __shared__ __attribute__((aligned(16))) float st[kUnitScalars];
+  __shared__ typename R::Raw pbuf[CC ? 16 * 64 : 1];  // the partner tile (the same tile of frame t + 1), as loaded
   const int NU = unit_cols(g) * unit_rows(g), lane = threadIdx.x;
   int chunk, u, f;
   if (CC) {
-    // With the cell-to-cell dot products a tile is read by two workgroups: its own frame's and the one of the frame
-    // before. Workgroups go to the eight dies round-robin by their index; each die gets a contiguous range of
-    // frames and walks it in order, so the two readers run on the same die within microseconds of each other and
-    // part of the second reads comes from that die's L2.
+    // With the frame-to-frame dot products a tile is asked for by two workgroups: its own frame's and the one of the
+    // frame before. Workgroups go to the eight dies round-robin by their index; each die gets a contiguous range of
+    // frames and walks it in order, so the two requests come from the same die within a few microseconds of each
+    // other and the second one is served by that die's L2.
     const int per_die = (g.F + 7) / 8, die = blockIdx.x & 7;
     int slot = blockIdx.x >> 3;
     chunk = slot % g.nC;
@@ -183,145 +238,169 @@ __global__ __launch_bounds__(64) void k_pyramid_stats(Geo g, const void* __restr
   const typename R::Elem* nbase = has_next ? fbase + (size_t)g.HW * g.D : fbase;
   typename R::Raw bufA[16], bufB[16];
   tile_load<DT>(bufA, fbase, W, g.D, y3, x3, min(vh, 4), min(vw, 4));
-  {
-    if (chunk == 0 && u == 0 && f % g.T == 0) sel_clear(sel + f / g.T);  // this video's budget search starts afresh
-    float S3[VEC], S2[4][VEC];
+  if (chunk == 0 && u == 0 && f % g.T == 0) sel_clear(sel + f / g.T);  // this video's budget search starts afresh
+  float S3[VEC], S2[4][VEC];
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) S3[v] = 0.f;
+  for (int v = 0; v < VEC; ++v) S3[v] = 0.f;
 #pragma unroll
-    for (int q2 = 0; q2 < 4; ++q2) {
-      const int th = max(0, min(4, vh - (q2 >> 1) * 4)), tw = max(0, min(4, vw - (q2 & 1) * 4));
-      if (q2 < 3) {
-        // the next tile's rows fly while this one is worked on; a tile wholly beyond the edge reads the
-        // first tile again instead (nothing is done with it), so that the loads stay unconditional
-        const int n = q2 + 1;
-        const int nh = max(0, min(4, vh - (n >> 1) * 4)), nw = max(0, min(4, vw - (n & 1) * 4));
-        const bool none = nh == 0 || nw == 0;
-        tile_load<DT>((q2 & 1) ? bufA : bufB, fbase, W, g.D, none ? y3 : y3 + (n >> 1) * 4,
-                      none ? x3 : x3 + (n & 1) * 4, none ? 1 : nh, none ? 1 : nw);
+  for (int q2 = 0; q2 < 4; ++q2) {
+    const int th = max(0, min(4, vh - (q2 >> 1) * 4)), tw = max(0, min(4, vw - (q2 & 1) * 4));
+    const bool some = th > 0 && tw > 0;
+    // the tile's own rows are waited for here (nothing newer is in flight at this point); a full tile of a full
+    // chunk needs no masking
+    const bool ragged = th < 4 || tw < 4 || (chunk + 1) * g.cch > g.D;
+    if (some && ragged) tile_mask<DT>((q2 & 1) ? bufB : bufA, th, tw, act);
+    if (CC && has_next && some) {
+      // the partner tile, with the same clamping as the tile's own loads: sixteen requests, whatever the edge
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int q1 = i >> 2, k = i & 3;
+        const int dy = min((q1 >> 1) * 2 + (k >> 1), th - 1), dx = min((q1 & 1) * 2 + (k & 1), tw - 1);
+        load_row_to_lds(pbuf, i * 1024,
+                        nbase + (size_t)((y3 + (q2 >> 1) * 4 + dy) * W + x3 + (q2 & 1) * 4 + dx) * g.D, lane);
       }
-      if (lane < 16) st[kUnitCellDots + q2 * 16 + lane] = 0.f;
-      if (lane < 8) st[kUnitNodeDots + q2 * 8 + lane] = 0.f;
-      if (th > 0 && tw > 0) {
-        tile_mask<DT>((q2 & 1) ? bufB : bufA, th, tw, act);
-        tile_stats<DT>(g, (q2 & 1) ? bufB : bufA, tb, lane, th, tw, st + q2 * kTileRows, S2[q2]);
-        if (!CC) tile_stats_reduce(g, tb, lane, th, tw, st + q2 * kTileRows);
-        if (CC) {
-          // x_c(t) . x_c(t+1) for the tile's cells: where both frames keep single cells the temporal stage needs
-          // nothing else (Sec. 3.3 compares node features; a cell's feature is its own row). The next frame's rows
-          // are asked for only now: held across the statistics above they would not fit the register file. The
-          // last frame of a video reads its own rows again and stores zeros.
-          typename R::Raw bufN[16];
-          tile_load<DT>(bufN, nbase, W, g.D, y3 + (q2 >> 1) * 4, x3 + (q2 & 1) * 4, th, tw);
-          tile_stats_reduce(g, tb, lane, th, tw, st + q2 * kTileRows);  // (the rows above travel meanwhile)
-          if (has_next) {
+    }
+    if (q2 < 3) {
+      // the next tile's rows fly while this one is worked on; a tile wholly beyond the edge reads the
+      // first tile again instead (nothing is done with it), so that the loads stay unconditional
+      const int n = q2 + 1;
+      const int nh = max(0, min(4, vh - (n >> 1) * 4)), nw = max(0, min(4, vw - (n & 1) * 4));
+      const bool none = nh == 0 || nw == 0;
+      tile_load<DT>((q2 & 1) ? bufA : bufB, fbase, W, g.D, none ? y3 : y3 + (n >> 1) * 4,
+                    none ? x3 : x3 + (n & 1) * 4, none ? 1 : nh, none ? 1 : nw);
+    }
+    if (some) {
+      float b4[8];  // the blocks' dot products with the tile, then (CC = 2) with the same blocks of the next frame
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const float d = R::dot(((q2 & 1) ? bufB : bufA)[i], bufN[i]);
-              tb[i * kRowStride + lane] = act ? d : 0.f;  // (a lane beyond the last channel read channel 0's data)
+      for (int i = 0; i < 8; ++i) b4[i] = 0.f;
+      {
+        float p1[4];
+        tile_stats<DT>((q2 & 1) ? bufB : bufA, tbs, lane, th, tw, p1, S2[q2]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) b4[i] = p1[i];
+      }
+      if (CC && has_next) {
+        // x_c(t) . x_c(t+1) for the tile's cells: where both frames keep single cells the temporal stage needs
+        // nothing else (Sec. 3.3 compares node features; a cell's feature is its own row).
+        wait_loads_but(q2 < 3 ? 16 : 0);  // the partner rows are there; the next tile's may still be on their way
+        float SN2[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) SN2[v] = 0.f;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          float cd[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) cd[i] = 0.f;
+#pragma unroll
+          for (int qq = 0; qq < 2; ++qq) {
+            const int q1 = h * 2 + qq;
+            if ((q1 >> 1) * 2 >= th || (q1 & 1) * 2 >= tw) continue;
+            typename R::Raw pr[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              pr[k] = pbuf[(q1 * 4 + k) * 64 + lane];
+              if (ragged) {  // (a clamped request repeated another cell; a lane beyond the last channel read channel 0)
+                const bool in = (q1 >> 1) * 2 + (k >> 1) < th && (q1 & 1) * 2 + (k & 1) < tw && act;
+                if (!in) pr[k] = R::zero();
+              }
+              cd[qq * 4 + k] = R::dot(((q2 & 1) ? bufB : bufA)[q1 * 4 + k], pr[k]);
             }
             if (CC >= 2) {
-            // The same for the tile's four 2x2 blocks and for the tile itself: S_n(t) . S_n(t+1), the dot product the
-            // temporal stage needs where both frames keep the same node n at level 1 or 2. A block's is the sum of
-            // the sixteen products of its rows in the two frames (straight from the packed rows: the blocks' sums
-            // of the statistics above are gone, and keeping them would not fit the registers); the tile's comes
-            // from its sum, which is still at hand, and the partner tile's sum.
-            tile_mask<DT>(bufN, th, tw, act);
-            float SN2[VEC];
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) SN2[v] = 0.f;
-#pragma unroll
-            for (int q1 = 0; q1 < 4; ++q1) {
+              // The same for the tile's 2x2 blocks and for the tile itself: S_n(t) . S_n(t+1), what the temporal
+              // stage needs where both frames keep the same node n at level 1 or 2. A block's is the sum of the
+              // sixteen products of its rows in the two frames (straight from the packed rows); the tile's comes
+              // from its sum and the partner tile's sum.
               float d1 = 0.f;
 #pragma unroll
               for (int k = 0; k < 4; ++k) {
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) d1 += R::dot(((q2 & 1) ? bufB : bufA)[q1 * 4 + k], bufN[q1 * 4 + kk]);
+                for (int kk = 0; kk < 4; ++kk) d1 += R::dot(((q2 & 1) ? bufB : bufA)[q1 * 4 + k], pr[kk]);
                 float xv[VEC];
-                R::unpack(bufN[q1 * 4 + k], xv);
+                R::unpack(pr[k], xv);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) SN2[v] += xv[v];
               }
-              tb[(16 + q1) * kRowStride + lane] = d1;
+              b4[4 + q1] = d1;
             }
-            float d2 = 0.f;
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) d2 = fmaf(S2[q2][v], SN2[v], d2);
-            tb[20 * kRowStride + lane] = d2;
-            }
-            wave_lds_fence();
-            if (lane < (CC >= 2 ? 21 : 16)) {
-              bool live = true;  // the tile itself holds valid cells
-              int dst = kUnitNodeDots + q2 * 8 + 4;
-              if (lane < 16) {
-                const int q1 = lane >> 2, k = lane & 3;
-                live = (q1 >> 1) * 2 + (k >> 1) < th && (q1 & 1) * 2 + (k & 1) < tw;
-                dst = kUnitCellDots + q2 * 16 + lane;
-              } else if (lane < 20) {
-                const int q1 = lane - 16;
-                live = (q1 >> 1) * 2 < th && (q1 & 1) * 2 < tw;
-                dst = kUnitNodeDots + q2 * 8 + q1;
-              }
-              if (live) {
-                const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
-                float acc = 0.f;
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                  float4 q = row[j];
-                  acc += (q.x + q.y) + (q.z + q.w);
-                }
-                st[dst] = acc;
-              }
-            }
-            wave_lds_fence();
           }
+          stage8(tbs, 5 + h, lane, cd);
         }
-      } else {
+        if (CC >= 2) {
+          float t8[8];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) S2[q2][v] = 0.f;
-        if (lane < kTileRows) st[q2 * kTileRows + lane] = 0.f;
-      }
+          for (int i = 0; i < 8; ++i) t8[i] = 0.f;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) S3[v] += S2[q2][v];
-    }
-    // level-2 dot products of the four tiles with the unit's sum
-    if (lane < kUnitCellDots - 4 * kTileRows) st[4 * kTileRows + lane] = 0.f;
-    if (L >= 3) {
-#pragma unroll
-      for (int q2 = 0; q2 < 4; ++q2) {
-        float d2 = 0.f;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) d2 = fmaf(S2[q2][v], S3[v], d2);
-        tb[q2 * kRowStride + lane] = d2;
-      }
-      wave_lds_fence();
-      if (lane < 4) {
-        const int q2 = lane;
-        if ((q2 >> 1) * 4 < vh && (q2 & 1) * 4 < vw) {
-          const float4* row = reinterpret_cast<const float4*>(tb + lane * kRowStride);
-          float acc = 0.f;
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            float4 q = row[j];
-            acc += (q.x + q.y) + (q.z + q.w);
-          }
-          st[4 * kTileRows + q2] = acc;
+          for (int v = 0; v < VEC; ++v) t8[0] = fmaf(S2[q2][v], SN2[v], t8[0]);
+          stage8(tbs, 7, lane, t8);
         }
       }
+      stage8(tbs, 4, lane, b4);
+      // row r of the staging area is added up by lane r and goes to its place in the unit's block (zero where the
+      // row stands for nothing: beyond the edge, above the root level, no next frame)
       wave_lds_fence();
-      if (act) {
-        float* o = nsum + ((size_t)f * (g.NN - g.lvl_base[3]) + (y3 >> 3) * (g.P >> 3) + (x3 >> 3)) * g.D + ch0;
-#pragma unroll
-        for (int v = 0; v < VEC; v += 4)
-          *reinterpret_cast<float4*>(o + v) = make_float4(S3[v], S3[v + 1], S3[v + 2], S3[v + 3]);
+      if (lane < 57) {
+        const int r = lane;
+        bool live;
+        int dst;
+        if (r < 32 || (r >= 40 && r < 56)) {  // a cell's row: norm, dot with its block, or with the next frame
+          const int q1 = r < 32 ? r >> 3 : (r - 40) >> 2, k = r & 3;
+          live = (q1 >> 1) * 2 + (k >> 1) < th && (q1 & 1) * 2 + (k & 1) < tw;
+          if (r < 32 && (r & 4)) live = live && 0 < L;
+          if (r >= 40) live = live && has_next;
+          dst = r < 32 ? q2 * kTileRows + ((r & 4) ? 16 : 0) + q1 * 4 + k : kUnitCellDots + q2 * 16 + (r - 40);
+        } else if (r < 40) {  // a 2x2 block's row: dot with the tile, or with the next frame
+          const int q1 = r & 3;
+          live = (q1 >> 1) * 2 < th && (q1 & 1) * 2 < tw;
+          live = live && (r < 36 ? 1 < L : (CC >= 2 && has_next));
+          dst = r < 36 ? q2 * kTileRows + 32 + q1 : kUnitNodeDots + q2 * 8 + q1;
+        } else {  // the tile with the next frame's
+          live = CC >= 2 && has_next;
+          dst = kUnitNodeDots + q2 * 8 + 4;
+        }
+        st[dst] = live ? staged_row_sum(tbs, r) : 0.f;
       }
+      wave_lds_fence();
+    } else {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) S2[q2][v] = 0.f;
+      if (lane < kTileRows) st[q2 * kTileRows + lane] = 0.f;
+      if (lane < 16) st[kUnitCellDots + q2 * 16 + lane] = 0.f;
+      if (lane < 5) st[kUnitNodeDots + q2 * 8 + lane] = 0.f;
     }
-    // the workgroup's scalars leave in one piece: whole, aligned 128-byte lines that no other workgroup touches
-    wave_lds_fence();
-    if (lane < kUnitScalars / 4)
-      reinterpret_cast<float4*>(part + ((size_t)(f * g.nC + chunk) * NU + u) * kUnitScalars)[lane] =
-          reinterpret_cast<const float4*>(st)[lane];
+    if (lane >= 5 && lane < 8) st[kUnitNodeDots + q2 * 8 + lane] = 0.f;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) S3[v] += S2[q2][v];
   }
+  // level-2 dot products of the four tiles with the unit's sum
+  if (lane < kUnitCellDots - 4 * kTileRows) st[4 * kTileRows + lane] = 0.f;
+  if (L >= 3) {
+    float d2[8];
+#pragma unroll
+    for (int q2 = 0; q2 < 8; ++q2) d2[q2] = 0.f;
+#pragma unroll
+    for (int q2 = 0; q2 < 4; ++q2) {
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) d2[q2] = fmaf(S2[q2][v], S3[v], d2[q2]);
+    }
+    stage8(tbs, 0, lane, d2);
+    wave_lds_fence();
+    if (lane < 4) {
+      const int q2 = lane;
+      if ((q2 >> 1) * 4 < vh && (q2 & 1) * 4 < vw) st[4 * kTileRows + q2] = staged_row_sum(tbs, lane);
+    }
+    wave_lds_fence();
+    if (act) {
+      float* o = nsum + ((size_t)f * (g.NN - g.lvl_base[3]) + (y3 >> 3) * (g.P >> 3) + (x3 >> 3)) * g.D + ch0;
+#pragma unroll
+      for (int v = 0; v < VEC; v += 4)
+        *reinterpret_cast<float4*>(o + v) = make_float4(S3[v], S3[v + 1], S3[v + 2], S3[v + 3]);
+    }
+  }
+  // the workgroup's scalars leave in one piece: whole, aligned 128-byte lines that no other workgroup touches
+  wave_lds_fence();
+  if (lane < kUnitScalars / 4)
+    reinterpret_cast<float4*>(part + ((size_t)(f * g.nC + chunk) * NU + u) * kUnitScalars)[lane] =
+        reinterpret_cast<const float4*>(st)[lane];
 }
 
 // ------------------------------------------------------------------------------------------------
