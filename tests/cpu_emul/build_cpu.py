@@ -11,14 +11,27 @@ LIB = os.path.join(HERE, "libsttm_cpu.so")
 SOURCES = ["sttm_api.hip", "sttm_spatial.hip", "sttm_temporal.hip", "sttm_reduce.hip"]
 
 
-def build(sanitize: bool = False, verbose: bool = False) -> str:
+SANITIZE_EXE = os.path.join(HERE, "sanitize_run")
+
+
+def build_sanitized(verbose: bool = False) -> str:
+    """tests/cpu_emul/sanitize_main.cpp and the library's sources in one executable, under AddressSanitizer and
+    UndefinedBehaviorSanitizer (any report ends the run with a non-zero status)."""
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-pthread", "-I", HERE, "-I", CSRC, "-Wno-unknown-pragmas", "-Wno-attributes",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"]
+    for s in SOURCES:
+        cmd += ["-x", "c++", os.path.join(CSRC, s)]
+    cmd += ["-x", "c++", os.path.join(HERE, "emul.cpp"), "-x", "c++", os.path.join(HERE, "sanitize_main.cpp"),
+            "-o", SANITIZE_EXE]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return SANITIZE_EXE
+
+
+def build(verbose: bool = False) -> str:
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-pthread", "-I", HERE, "-I", CSRC,
            "-Wno-unknown-pragmas", "-Wno-attributes"]
-    if sanitize:
-        # AddressSanitizer only: with -fsanitize=undefined g++ 11 sends the conditional-pointer stores of the
-        # pyramid kernel ("(is_dot ? pd : pn)[i] = v") to the wrong element without any report, so results of
-        # such a build mean nothing.
-        cmd += ["-fsanitize=address", "-fno-omit-frame-pointer"]
     for s in SOURCES:
         cmd += ["-x", "c++", os.path.join(CSRC, s)]
     cmd += ["-x", "c++", os.path.join(HERE, "emul.cpp"), "-o", LIB]
@@ -29,4 +42,4 @@ def build(sanitize: bool = False, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(sanitize="--asan" in sys.argv, verbose=True))
+    print(build_sanitized(verbose=True) if "--sanitize" in sys.argv else build(verbose=True))

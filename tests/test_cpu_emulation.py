@@ -120,3 +120,15 @@ def test_emulated_temporal_work_lists_at_their_largest(emul):
     r = run_cpu.run_cpu(feats, tau_s=0.5, tau_t=0.3, node_map_override=(nm, nl))
     tm, _ = P.check_temporal(fake, feats, r, sp, 0.3)
     P.check_reduce(feats, r, tm, False)
+
+
+def test_emulated_kernels_run_clean_under_address_and_undefined_behaviour_sanitizers():
+    """The host-thread build with -fsanitize=address,undefined (any report aborts): both dtypes, fixed thresholds and
+    a budget, every output in a heap block of its exact size, the workspace of exactly sttm_workspace_bytes()."""
+    import subprocess
+    from tests.cpu_emul import build_cpu
+    exe = build_cpu.build_sanitized()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, (r.stdout[-2000:], r.stderr[-4000:])
+    assert r.stdout.count("case ") == 2
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
