@@ -130,10 +130,15 @@ def main() -> int:
     ap.add_argument("--positions", action="store_true", help="also emit the position indices of the rows each step")
     ap.add_argument("--no-cell-dots", action="store_true",
                     help="keep the spatial and temporal passes separate (sttm_set_cell_dots(0))")
+    ap.add_argument("--cell-dots-only", action="store_true",
+                    help="keep the spatial pass to the cell-against-cell products at every budget (default: the 2x2 and "
+                         "4x4 block products ride along too when the budget keeps 35 % of the tokens or less)")
     ap.add_argument("--node-dots", action="store_true",
                     help="frame-to-frame dot products of the 2x2 and 4x4 blocks in the spatial pass too (sttm_set_cell_dots(2))")
     ap.add_argument("--no-node-sums", action="store_true",
                     help="reduce stage without the stage-1 partition: every cell is read again")
+    ap.add_argument("--no-two-streams", action="store_true",
+                    help="skip the extra leg that runs the timed steps alternately on two contexts and streams")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed steps, run one plain device-to-device copy of the input tensor "
                          "(known size: reads and writes N*D*esz bytes) so that a counter run can scale "
@@ -184,7 +189,19 @@ def main() -> int:
     s = lib.Sttm(0)
     s.sttm_set_match_mode({"first_passing": 0, "topleft_only": 1, "most_similar": 2}[args.match])
     s.sttm_set_output_order({"raster": 0, "zscan": 1}[args.order])
-    s.sttm_set_cell_dots(0 if args.no_cell_dots else (2 if args.node_dots else 1))
+
+    def dots_level(keep):
+        """Which frame-to-frame dot products the spatial pass leaves for the temporal stage (sttm_set_cell_dots):
+        measured on the bench workload, the block products (level 2) cost the spatial pass about 19 us and pay
+        once many tokens merge spatially, i.e. at budgets of about a third and below."""
+        if args.no_cell_dots:
+            return 0
+        if args.node_dots:
+            return 2
+        if args.cell_dots_only or keep is None:
+            return 1
+        return 2 if keep <= 0.35 else 1
+
     s.ensure_workspace(B, T, H, W, D, dt, R)
     node_map = torch.empty(N, dtype=torch.int32, device=dev)
     node_level = torch.empty(N, dtype=torch.uint8, device=dev)
@@ -220,6 +237,8 @@ def main() -> int:
     def measure(keep):
         """W warm-up steps, then exactly K timed steps: the wall clock around all of them, and one HIP event
         between consecutive steps on the stream the library launches on, for the median step time."""
+        level = dots_level(keep)
+        s.sttm_set_cell_dots(level)
         for _ in range(args.warmup):
             step(keep)
         torch.cuda.synchronize()
@@ -252,9 +271,9 @@ def main() -> int:
             a, b = lv[:, 1:].int(), lv[:, :-1].int()
             J = torch.maximum(a, b)
             small = J <= 2
-            if args.node_dots:
+            if level == 2:
                 small = small & (a != b)
-            elif not args.no_cell_dots:
+            elif level == 1:
                 small = small & (J > 0)
             need_t = small | ((J >= 3) & (a < b))   # rows of the later frame of a pair
             need_p = small | ((J >= 3) & (b < a))   # rows of the earlier frame
@@ -291,7 +310,7 @@ def main() -> int:
             tot = sum(traffic.values())      # every kernel of the step that moves more than 2 MB
             path.update(traffic_bytes_per_step=tot, measured_GBps=tot / step_s / 1e9,
                         measured_frac_of_peak=tot / step_s / 1e9 / HBM_PEAK_GBS)
-        return {"keep": keep, "value": N / step_s / 1e6, "ms_per_step": median_ms,
+        return {"keep": keep, "cell_dots_level": level, "value": N / step_s / 1e6, "ms_per_step": median_ms,
                 "ms_per_step_wall_mean": elapsed / args.steps * 1e3, "ms_per_step_min": per_step[0],
                 "ms_per_step_max": per_step[-1], "kept_tokens": K, "kept_fraction": K / N,
                 "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
@@ -301,6 +320,60 @@ def main() -> int:
                 "path": path}
 
     runs = [measure(k) for k in budgets]
+
+    def two_streams(keep):
+        """The same K steps, issued alternately on two library contexts with a stream, a workspace and output buffers
+        each (default stream priority): the latency-bound integer kernels of one video then run beside the feature
+        passes of the other, as they would in a server that merges one video per stream. Whole-job rate by the host
+        clock between two device-wide synchronisations; never the headline value."""
+        lanes = []
+        for _ in range(2):
+            st = torch.cuda.Stream(device=dev)
+            c = lib.Sttm(0, stream_ptr=st.cuda_stream)
+            c.sttm_set_match_mode({"first_passing": 0, "topleft_only": 1, "most_similar": 2}[args.match])
+            c.sttm_set_output_order({"raster": 0, "zscan": 1}[args.order])
+            c.sttm_set_cell_dots(dots_level(keep))
+            c.ensure_workspace(B, T, H, W, D, dt, R)
+            bufs = dict(node_map=torch.empty_like(node_map), node_level=torch.empty_like(node_level),
+                        cluster=torch.empty_like(cluster), merged=torch.empty_like(merged),
+                        counts=torch.empty_like(counts), out_ids=torch.empty_like(out_ids),
+                        offsets=torch.zeros_like(offsets))
+            lanes.append((c, bufs))
+        torch.cuda.synchronize()
+
+        def lane_step(i, c, b):
+            xin = xs[i % copies]
+            if budget_mode:
+                c.sttm_spatial_stats(xin, dt, B, T, H, W, D, R)
+                c.sttm_budget_threshold(lib.STTM_STAGE_SPATIAL, keep, want_tau=False)
+                c.sttm_spatial_quadtree(xin, dt, B, T, H, W, D, R, None, b["node_map"], b["node_level"])
+                c.sttm_temporal_stats(xin, b["node_map"], b["node_level"])
+                c.sttm_budget_threshold(lib.STTM_STAGE_TEMPORAL, keep, want_tau=False)
+                c.sttm_temporal_merge(xin, b["node_map"], b["node_level"], None, b["cluster"])
+            else:
+                c.sttm_spatial_quadtree(xin, dt, B, T, H, W, D, R, [cfg.tau_s], b["node_map"], b["node_level"])
+                c.sttm_temporal_merge(xin, b["node_map"], b["node_level"], [cfg.tau_t], b["cluster"])
+            c.sttm_reduce(xin, b["cluster"], None if args.no_node_sums else b["node_map"],
+                          None if args.no_node_sums else b["node_level"], dt, N, b["merged"], b["counts"],
+                          b["out_ids"], b["offsets"], want_n=False)
+
+        for i in range(2 * max(1, args.warmup)):
+            lane_step(i, *lanes[i % 2])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            lane_step(i, *lanes[i % 2])
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        ks = [int(b["offsets"][B].item()) for _, b in lanes]
+        for (c, b), k in zip(lanes, ks):
+            assert int(b["counts"][:k].sum().item()) == N, "member counts do not add up to the number of input tokens"
+            c.close()
+        return {"keep": keep, "streams": 2, "steps": args.steps, "ms_per_step": elapsed / args.steps * 1e3,
+                "value": N * args.steps / elapsed / 1e6, "unit": "Mtok/s", "kept_tokens": ks,
+                "timing": "host clock around all steps, device-wide synchronisation on both sides"}
+
+    overlapped = None if args.no_two_streams else two_streams(budgets[0])
     if args.calibrate_copy:
         merged.view(-1)[:x.numel()].copy_(x.view(-1))
         torch.cuda.synchronize()
@@ -324,7 +397,7 @@ def main() -> int:
                                + (f", order={args.order}" if args.order != "raster" else "")
                                + (", with position indices" if args.positions else "")
                                + (", separate spatial and temporal passes" if args.no_cell_dots else "")
-                               + (", block dot products in the spatial pass" if args.node_dots else ""),
+                               + (", block dot products in the spatial pass" if head["cell_dots_level"] == 2 else ""),
                    "tokens": N, "kept_tokens": head["kept_tokens"], "kept_fraction": head["kept_fraction"],
                    "generate_s": gen_s, "input_copies": copies},
         "roofline": head["roofline"],
@@ -334,6 +407,8 @@ def main() -> int:
     }
     if len(runs) > 1:   # the workload's other budgets, each measured the same way (warm-up, then the same number of steps)
         out["budgets"] = {f"keep={r['keep']}": r for r in runs[1:]}
+    if overlapped is not None:
+        out["two_streams"] = overlapped
     if cpu is not None:
         out["cpu_baseline"], out["cpu_baseline_all_cores"] = cpu
     print(json.dumps(out))
