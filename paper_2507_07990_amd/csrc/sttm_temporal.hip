@@ -230,7 +230,12 @@ __global__ __launch_bounds__(256) void k_temporal_dots(Geo g, const void* __rest
   const int H = g.H, W = g.W, HW = g.HW;
   const int NB = g.NN - g.lvl_base[3];
   float* tb = tbuf[wave];
-  const int queue = blockIdx.x % kTQueues, share = blockIdx.x / kTQueues;
+  // Workgroups go to the eight dies round-robin by their index: the workgroups of die d serve the queues 8d .. 8d+7,
+  // i.e. eight consecutive frames of every 64, so that the two frame pairs that need a frame's rows mostly meet in
+  // one L2.
+  const int slot = blockIdx.x % kTQueues, share = blockIdx.x / kTQueues;
+  static_assert(kTQueues == 64, "queue <-> die mapping below");
+  const int queue = ((slot & 7) << 3) | (slot >> 3);
   items += (size_t)queue * temporal_queue_items(g);
   const int ntasks = count[queue * kTCountStride] * g.nC, stride = (int)(gridDim.x / kTQueues) * 4;
   for (int task = share * 4 + wave; task < ntasks; task += stride) {
