@@ -66,6 +66,40 @@ __host__ __device__ inline void node_decode(const Geo& g, int idx, int& lvl, int
   bx = r & ((1 << sh) - 1);
 }
 
+// ---- the packed dot product of the target -----------------------------------------------------------------
+// c + a.lo * b.lo + a.hi * b.hi on the two 16-bit values each register holds (v_dot2c_f32_bf16, v_dot2_f32_f16: the
+// products of two 16-bit values are exact in fp32), and a pair of constants handed over as register contents the
+// compiler cannot look into: written as literals, the bf16 pair (1, 0) = 0x00003f80 is encoded as the inline operand
+// "1.0", which the instruction does not read as this pair. These three are all that differs in the host-thread
+// build of the tests; everything built on them is the same code in both.
+#ifndef STTM_HOST_EMULATION
+__device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  typedef __bf16 pair __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a), __builtin_bit_cast(pair, b), c, false);
+}
+__device__ inline float dot2_f16(uint32_t a, uint32_t b, float c) {
+  typedef _Float16 pair __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a), __builtin_bit_cast(pair, b), c, false);
+}
+template <uint32_t LO, uint32_t HI>
+__device__ inline void opaque_pairs(uint32_t& lo, uint32_t& hi) {
+  asm volatile("s_mov_b32 %0, %2\n\ts_mov_b32 %1, %3" : "=s"(lo), "=s"(hi) : "i"(LO), "i"(HI));
+}
+#else
+inline float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return fmaf(__uint_as_float(a & 0xffff0000u), __uint_as_float(b & 0xffff0000u),
+              fmaf(__uint_as_float(a << 16), __uint_as_float(b << 16), c));
+}
+inline float dot2_f16(uint32_t a, uint32_t b, float c) {
+  return fmaf(__half2float(__ushort_as_half((unsigned short)(a >> 16))),
+              __half2float(__ushort_as_half((unsigned short)(b >> 16))),
+              fmaf(__half2float(__ushort_as_half((unsigned short)(a & 0xffffu))),
+                   __half2float(__ushort_as_half((unsigned short)(b & 0xffffu))), c));
+}
+template <uint32_t LO, uint32_t HI>
+inline void opaque_pairs(uint32_t& lo, uint32_t& hi) { lo = LO; hi = HI; }
+#endif
+
 // ---- feature row access: one lane owns `VEC` consecutive channels ------------------------------------
 template <int DT> struct Row;  // DT: 0 = f32, 1 = bf16, 2 = f16
 
@@ -99,44 +133,22 @@ template <> struct Row<1> {
     x[6] = __uint_as_float(r.w << 16); x[7] = __uint_as_float(r.w & 0xffff0000u);
   }
   // Straight from the packed pairs: one instruction multiplies two pairs and adds both products to the running
-  // fp32 sum (a product of two bf16 values is exact in fp32), so nothing has to be unpacked.
+  // fp32 sum, so nothing has to be unpacked.
   __device__ static inline float dot(const Raw& a, const Raw& b) {
-#ifndef STTM_HOST_EMULATION
-    typedef __bf16 pair __attribute__((ext_vector_type(2)));
-    float d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.x), __builtin_bit_cast(pair, b.x), 0.f, false);
-    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.y), __builtin_bit_cast(pair, b.y), d, false);
-    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.z), __builtin_bit_cast(pair, b.z), d, false);
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, a.w), __builtin_bit_cast(pair, b.w), d, false);
-#else
-    float x[8], y[8], d = 0.f;
-    unpack(a, x);
-    unpack(b, y);
-    for (int v = 0; v < 8; ++v) d = fmaf(x[v], y[v], d);
-    return d;
-#endif
+    return dot2_bf16(a.w, b.w, dot2_bf16(a.z, b.z, dot2_bf16(a.y, b.y, dot2_bf16(a.x, b.x, 0.f))));
   }
-  // S += the row's channels. The same packed instruction, with the pair (1, 0) or (0, 1) as its second operand,
-  // widens one element of a pair and adds it to the running sum in one step (x * 1 + y * 0: exact; only an
+  // S += the row's channels: the same instruction against the constant pairs (1, 0) and (0, 1) widens a channel and
+  // adds it in one step (multiplying the other channel by zero: exact for every finite value, and where a value is an
   // infinity or a NaN in the other element of the pair spills over, into a sum that is undefined then anyway).
   __device__ static inline void add_row(const Raw& r, float (&S)[8]) {
-#ifndef STTM_HOST_EMULATION
-    typedef __bf16 pair __attribute__((ext_vector_type(2)));
-    // (the two selectors are handed over as register contents the compiler cannot look into: written as constants
-    // it encodes (1, 0) as the inline operand "1.0", which the instruction does not read as this pair)
     uint32_t klo, khi;
-    asm volatile("s_mov_b32 %0, 0x3f80\n\ts_mov_b32 %1, 0x3f800000" : "=s"(klo), "=s"(khi));
-    const pair lo = __builtin_bit_cast(pair, klo), hi = __builtin_bit_cast(pair, khi);
+    opaque_pairs<0x3f80u, 0x3f800000u>(klo, khi);
     const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      S[2 * j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, w[j]), lo, S[2 * j], false);
-      S[2 * j + 1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(pair, w[j]), hi, S[2 * j + 1], false);
+      S[2 * j] = dot2_bf16(w[j], klo, S[2 * j]);
+      S[2 * j + 1] = dot2_bf16(w[j], khi, S[2 * j + 1]);
     }
-#else
-    float x[8];
-    unpack(r, x);
-    for (int v = 0; v < 8; ++v) S[v] += x[v];
-#endif
   }
 };
 
@@ -152,38 +164,18 @@ template <> struct Row<2> {
     x[4] = lo(r.z); x[5] = hi(r.z); x[6] = lo(r.w); x[7] = hi(r.w);
   }
   __device__ static inline float dot(const Raw& a, const Raw& b) {
-#ifndef STTM_HOST_EMULATION
-    typedef _Float16 pair __attribute__((ext_vector_type(2)));
-    float d = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.x), __builtin_bit_cast(pair, b.x), 0.f, false);
-    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.y), __builtin_bit_cast(pair, b.y), d, false);
-    d = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.z), __builtin_bit_cast(pair, b.z), d, false);
-    return __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, a.w), __builtin_bit_cast(pair, b.w), d, false);
-#else
-    float x[8], y[8], d = 0.f;
-    unpack(a, x);
-    unpack(b, y);
-    for (int v = 0; v < 8; ++v) d = fmaf(x[v], y[v], d);
-    return d;
-#endif
+    return dot2_f16(a.w, b.w, dot2_f16(a.z, b.z, dot2_f16(a.y, b.y, dot2_f16(a.x, b.x, 0.f))));
   }
   // S += the row's channels (see Row<1>::add_row)
   __device__ static inline void add_row(const Raw& r, float (&S)[8]) {
-#ifndef STTM_HOST_EMULATION
-    typedef _Float16 pair __attribute__((ext_vector_type(2)));
-    uint32_t klo, khi;  // (as register contents, see Row<1>::add_row)
-    asm volatile("s_mov_b32 %0, 0x3c00\n\ts_mov_b32 %1, 0x3c000000" : "=s"(klo), "=s"(khi));
-    const pair lo = __builtin_bit_cast(pair, klo), hi = __builtin_bit_cast(pair, khi);
+    uint32_t klo, khi;
+    opaque_pairs<0x3c00u, 0x3c000000u>(klo, khi);
     const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      S[2 * j] = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, w[j]), lo, S[2 * j], false);
-      S[2 * j + 1] = __builtin_amdgcn_fdot2(__builtin_bit_cast(pair, w[j]), hi, S[2 * j + 1], false);
+      S[2 * j] = dot2_f16(w[j], klo, S[2 * j]);
+      S[2 * j + 1] = dot2_f16(w[j], khi, S[2 * j + 1]);
     }
-#else
-    float x[8];
-    unpack(r, x);
-    for (int v = 0; v < 8; ++v) S[v] += x[v];
-#endif
   }
 };
 
