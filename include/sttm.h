@@ -240,7 +240,8 @@ int sttm_export(sttm_ctx* ctx, int table, void* dst_dev, size_t bytes);
 /* The three kernels that read the features (one per stage); everything else touches O(1) scalars per token. */
 typedef enum {
   STTM_KERNEL_PYRAMID_STATS = 0, /* stage 1: block sums, norms, parent-child dot products */
-  STTM_KERNEL_TEMPORAL_DOTS = 1, /* stage 2: dot products of overlapping nodes of consecutive frames */
+  STTM_KERNEL_TEMPORAL_DOTS = 1, /* stage 2: dot products of overlapping nodes of consecutive frames (the timed
+                                    region is the planner that lists the work plus the pass over the features) */
   STTM_KERNEL_REDUCE_GATHER = 2, /* stage 3: gather and average the member rows */
   STTM_KERNEL_COUNT = 3
 } sttm_kernel;
