@@ -269,14 +269,39 @@ def check_reduce(feats, r: GpuResult, tm, out_is_bf16: bool, order: str = "raste
     assert (r.offsets == rd.offsets).all()
     assert int(r.counts.sum()) == feats.shape[0] * feats.shape[1] * feats.shape[2] * feats.shape[3]
     if feats.dtype == np.uint16 or out_is_bf16:
-        tol = TOL_BF16
+        tol, half_ulp = TOL_BF16, 2.0 ** -8
     elif feats.dtype == np.float16 or out_is_f16:
-        tol = TOL_F16
+        tol, half_ulp = TOL_F16, 2.0 ** -11
     else:
-        tol = TOL_F32
-    err = float(np.abs(r.merged.astype(np.float64) - rd.merged).max()) if r.K else 0.0
-    assert err <= tol, f"merged feature error {err} > {tol}"
+        tol, half_ulp = TOL_F32, 2.0 ** -23
+    if not r.K:
+        return rd, 0.0
+    # The absolute figures above are half an ulp of the output for values of a few units (what the workloads hold)
+    # plus the fp32 sums; the rounding of the output scales with the value, so beyond that range the bound does too.
+    diff = np.abs(r.merged.astype(np.float64) - rd.merged)
+    bound = np.maximum(tol, half_ulp * np.abs(rd.merged) + TOL_F32)
+    err = float(diff.max())
+    assert (diff <= bound).all(), f"merged feature error {float((diff - bound).max())} beyond its bound (largest error {err})"
     return rd, err
+
+
+def budget_tau_acceptable(tau_g: float, vals, wts, base: int, target: int, tau: float, lo: float, hi: float) -> bool:
+    """Whether the threshold the GPU found is one the budget rule allows, given that the two sides know every
+    similarity only to within BAND of each other. Either it lies in the oracle's own last interval (widened by
+    BAND), or -- when values closer together than BAND straddle that interval's edge, e.g. a group of similarities
+    that are exactly 1 in fp32 and 1 - 2e-16 for some of them in fp64 -- it is feasible and maximal under the
+    band: everything surely below it fits the budget, and taking in the next value above it together with
+    everything within BAND of that value would not."""
+    if lo - BAND <= tau_g <= hi + BAND or tau_g == tau:
+        return True
+    v = np.asarray(vals, dtype=np.float64)
+    w = np.asarray(wts, dtype=np.float64) if wts is not None else np.ones(len(v))
+    if base + w[v <= tau_g - BAND].sum() > target:
+        return False
+    above = v[v > tau_g + BAND]
+    if above.size == 0:
+        return tau_g >= 1.0 - BAND or base + w.sum() <= target
+    return base + w[v <= above.min() + BAND].sum() > target
 
 
 def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None, root_grid=1,
@@ -295,7 +320,7 @@ def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None,
             keep_b = float(np.broadcast_to(np.asarray(keep, dtype=np.float64), (B,))[b])
             target = int(math.floor(math.sqrt(keep_b) * N1))
             tau, lo, hi, K = O.budget_threshold(vals, wts, base, target)
-            assert lo - BAND <= ts[b] <= hi + BAND or ts[b] == tau, \
+            assert budget_tau_acceptable(ts[b], vals, wts, base, target, tau, lo, hi), \
                 f"tau_s {ts[b]} outside the oracle's interval [{lo}, {hi})"
             assert len(np.unique(r.node_map[b])) <= target or base > target
         info["tau_s"] = ts
@@ -309,7 +334,7 @@ def check_parity(lib, feats, r: GpuResult, *, tau_s=None, tau_t=None, keep=None,
             keep_b = float(np.broadcast_to(np.asarray(keep, dtype=np.float64), (B,))[b])
             target = int(math.floor(keep_b * N1))
             tau, lo, hi, K = O.budget_threshold(vals, wts, base, target)
-            assert lo - BAND <= tt[b] <= hi + BAND or tt[b] == tau, \
+            assert budget_tau_acceptable(tt[b], vals, wts, base, target, tau, lo, hi), \
                 f"tau_t {tt[b]} outside the oracle's interval [{lo}, {hi})"
             assert len(np.unique(r.cluster_ids[b])) <= target or base > target
         info["tau_t"] = tt

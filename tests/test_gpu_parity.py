@@ -640,3 +640,43 @@ def test_non_default_stream_and_two_contexts_on_one_device(lib):
         assert (o["cl"].cpu().numpy().reshape(r.cluster_ids.shape) == r.cluster_ids).all()
         assert (o["ct"][:K].cpu().numpy() == r.counts).all() and (o["oi"][:K].cpu().numpy() == r.out_ids).all()
         np.testing.assert_array_equal(o["mg"][:K].float().cpu().numpy(), r.merged)
+
+
+def test_randomized_shapes_and_settings(lib):
+    """Sixty seeded random draws over everything the boundary lets a caller choose -- grid (1x1 to 32x32, any aspect),
+    frames, videos, width, element type, root grid, destination rule, row order, which dot products ride along in
+    the spatial pass, noise level, fixed thresholds or a budget -- each compared with the oracle like the named
+    cases above, position indices included."""
+    import random
+    rng = random.Random(20250711)
+    for case in range(60):
+        H = rng.choice([1, 2, 3, 5, 7, 8, 9, 12, 13, 14, 16, 17, 20, 24, 27, 31, 32])
+        W = rng.choice([1, 2, 4, 6, 8, 11, 13, 14, 16, 18, 23, 27, 32])
+        P2 = wl.pow2_ceil(max(H, W))
+        T = rng.choice([1, 2, 3, 4, 5, 7, 9, 12])
+        B = rng.choice([1, 1, 2, 3])
+        dtype = rng.choice(["bf16", "bf16", "f16", "f32"])
+        D = 8 * rng.choice([1, 2, 3, 5, 9, 17, 25, 33, 64, 65, 96, 129, 144])
+        while B * T * H * W * D > 3.0e6:
+            D = max(8, D // 2 // 8 * 8)
+            if B * T * H * W * D > 3.0e6 and T > 2:
+                T -= 1
+        R = rng.choice([r for r in (1, 1, 1, 2, 4, 8, 16, 32) if r <= P2])
+        mode = rng.choice(["first_passing", "first_passing", "topleft_only", "most_similar"])
+        order = rng.choice(["raster", "zscan"])
+        cell_dots = rng.choice([0, 1, 1, 2])
+        sigma = rng.choice([0.02, 0.1, 0.3, 0.8])
+        persist = rng.choice([0.3, 0.7, 0.95])
+        cfg = wl.Workload("random", 5000 + case, B, T, H, W, D, dtype, int(math.log2(P2)), sigma, persist)
+        if rng.random() < 0.5:
+            kw = dict(keep=rng.choice([0.1, 0.25, 0.3, 0.5, 0.75, 0.9, 1.0]))
+        else:
+            kw = dict(tau_s=rng.choice([0.5, 0.7, 0.8, 0.9, 0.95, 1.0, -2.0]),
+                      tau_t=rng.choice([0.3, 0.6, 0.8, 0.9, 0.97, 1.0, -2.0]))
+        alternating = rng.random() < 0.3
+        feats = wl.generate_alternating(cfg, sigma * 4) if alternating else wl.generate(cfg)
+        print(f"case {case}: B={B} T={T} {H}x{W} D={D} {dtype} R={R} {mode} {order} cell_dots={cell_dots} "
+              f"sigma={sigma} persist={persist} alternating={alternating} {kw}", flush=True)
+        r = P.run_gpu(lib, feats, root_grid=R, mode=mode, order=order, positions=True, cell_dots=cell_dots, **kw)
+        info = P.check_parity(lib, feats, r, root_grid=R, mode=mode, order=order, **kw)
+        assert info["K"] >= 1
