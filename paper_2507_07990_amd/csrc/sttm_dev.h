@@ -213,6 +213,27 @@ __device__ inline uint32_t f32_to_bf16_rne(float f) {
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Two fp32 values rounded to nearest even and packed into one register (a in the low half): one conversion
+// instruction of the target per pair (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32); the host-thread build of the tests
+// rounds in integer arithmetic.
+#ifndef STTM_HOST_EMULATION
+__device__ inline uint32_t pack2_bf16(float a, float b) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ inline uint32_t pack2_f16(float a, float b) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+#else
+inline uint32_t pack2_bf16(float a, float b) { return f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16); }
+inline uint32_t pack2_f16(float a, float b) { return f32_to_f16_rne(a) | (f32_to_f16_rne(b) << 16); }
+#endif
+
 // cos(a, b) from the dot product and the two squared norms: clamped to <= 1, 0 for a zero norm.
 __device__ inline float cosine_from(float dot, float na2, float nb2) {
   if (na2 == 0.f || nb2 == 0.f) return 0.f;

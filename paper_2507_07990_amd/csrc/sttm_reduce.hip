@@ -514,10 +514,7 @@ __device__ inline void acc_slot(const float4& r, int, float (&acc)[4]) {  // fp3
 template <int DT>
 __device__ inline void acc_slot(const uint4& r, int kind, float (&acc)[8]) {
   if (kind == 0) {
-    float t[8];
-    Row<DT>::unpack(r, t);
-#pragma unroll
-    for (int v = 0; v < 8; ++v) acc[v] += t[v];
+    Row<DT>::add_row(r, acc);
   } else {
     const float f0 = __uint_as_float(r.x), f1 = __uint_as_float(r.y);
     const float f2 = __uint_as_float(r.z), f3 = __uint_as_float(r.w);
@@ -543,8 +540,7 @@ __device__ inline void store_mean(void* merged_v, size_t elem_off, const float (
     uint32_t w[VEC / 2];
 #pragma unroll
     for (int v = 0; v < VEC; v += 2)
-      w[v / 2] = ODT == 1 ? (f32_to_bf16_rne(acc[v] * inv) | (f32_to_bf16_rne(acc[v + 1] * inv) << 16))
-                          : (f32_to_f16_rne(acc[v] * inv) | (f32_to_f16_rne(acc[v + 1] * inv) << 16));
+      w[v / 2] = ODT == 1 ? pack2_bf16(acc[v] * inv, acc[v + 1] * inv) : pack2_f16(acc[v] * inv, acc[v + 1] * inv);
     if (VEC == 8)
       store_once(reinterpret_cast<uint4*>(o), make_uint4(w[0], w[1], w[2 % (VEC / 2)], w[3 % (VEC / 2)]));
     else
@@ -635,10 +631,18 @@ __global__ __launch_bounds__(64) void k_reduce(Geo g, GatherArgs a) {
       const int kind = __shfl(sv.kind, j, 64), wgt = __shfl(sv.weight, j, 64);
       const bool big = end - beg > kBig;
       const bool use = p0 + j < p1 && (beg >= p0 || big);
-      if (use) {
+      const int p = p0 + j;
+      // a cluster of one cell whose row is written in the type it came in: the mean is the row itself
+      const bool one = (DT == ODT) && use && !big && beg == p && end == p + 1 && kind == 0;
+      if (one) {
+        if (row < a.capacity) {
+          if (act) store_once(reinterpret_cast<typename R::Raw*>(
+                                  reinterpret_cast<typename R::Elem*>(a.merged) + (size_t)row * g.D + ch0), raw[j]);
+          if (chunk == 0 && lane == 0 && a.counts) a.counts[row] = 1;
+        }
+      } else if (use) {
         acc_slot<DT>(raw[j], kind, acc);
         members += wgt;
-        const int p = p0 + j;
         const bool closes = p + 1 == end, last = p + 1 == p1;
         if (big) {
           if (closes || last) {  // this item's share of a big cluster
