@@ -96,12 +96,12 @@ __device__ __forceinline__ float staged_row_sum(const float* tbs, int row) {
 // The rows must be zero for cells beyond the edge and for lanes beyond the last channel (tile_mask).
 template <int DT>
 __device__ __forceinline__ void tile_stats(const typename Row<DT>::Raw (&raw)[16], float* tbs, int lane, int th, int tw,
-                                           float (&p1)[4], float (&S2)[Row<DT>::VEC]) {
+                                           float (&p1)[4], float (&S2)[Row<DT>::VEC],
+                                           float (&S1)[4][Row<DT>::VEC]) {
   typedef Row<DT> R;
   constexpr int VEC = R::VEC;
 #pragma unroll
   for (int v = 0; v < VEC; ++v) S2[v] = 0.f;
-  float S1[4][VEC];
 #pragma unroll
   for (int q1 = 0; q1 < 4; ++q1) {
 #pragma unroll
@@ -270,12 +270,13 @@ __global__ __launch_bounds__(64, 2) void k_pyramid_stats(Geo g, const void* __re
                     none ? x3 : x3 + (n & 1) * 4, none ? 1 : nh, none ? 1 : nw);
     }
     if (some) {
+      float S1[4][VEC];  // the tile's 2x2 block sums
       float b4[8];  // the blocks' dot products with the tile, then (CC = 2) with the same blocks of the next frame
 #pragma unroll
       for (int i = 0; i < 8; ++i) b4[i] = 0.f;
       {
         float p1[4];
-        tile_stats<DT>((q2 & 1) ? bufB : bufA, tbs, lane, th, tw, p1, S2[q2]);
+        tile_stats<DT>((q2 & 1) ? bufB : bufA, tbs, lane, th, tw, p1, S2[q2], S1);
 #pragma unroll
         for (int i = 0; i < 4; ++i) b4[i] = p1[i];
       }
@@ -307,18 +308,18 @@ __global__ __launch_bounds__(64, 2) void k_pyramid_stats(Geo g, const void* __re
             }
             if (CC >= 2) {
               // The same for the tile's 2x2 blocks and for the tile itself: S_n(t) . S_n(t+1), what the temporal
-              // stage needs where both frames keep the same node n at level 1 or 2. A block's is the sum of the
-              // sixteen products of its rows in the two frames (straight from the packed rows); the tile's comes
-              // from its sum and the partner tile's sum.
-              float d1 = 0.f;
+              // stage needs where both frames keep the same node n at level 1 or 2: the block's sum (kept from the
+              // tile's statistics) with the sum of the partner block's four rows, the tile's sum with the sum of
+              // the partner blocks.
+              float SN1[VEC], d1 = 0.f;
 #pragma unroll
-              for (int k = 0; k < 4; ++k) {
+              for (int v = 0; v < VEC; ++v) SN1[v] = 0.f;
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) d1 += R::dot(((q2 & 1) ? bufB : bufA)[q1 * 4 + k], pr[kk]);
-                float xv[VEC];
-                R::unpack(pr[k], xv);
+              for (int k = 0; k < 4; ++k) R::add_row(pr[k], SN1);
 #pragma unroll
-                for (int v = 0; v < VEC; ++v) SN2[v] += xv[v];
+              for (int v = 0; v < VEC; ++v) {
+                d1 = fmaf(S1[q1][v], SN1[v], d1);
+                SN2[v] += SN1[v];
               }
               b4[4 + q1] = d1;
             }
