@@ -192,7 +192,7 @@ def main() -> int:
 
     def dots_level(keep):
         """Which frame-to-frame dot products the spatial pass leaves for the temporal stage (sttm_set_cell_dots):
-        measured on the bench workload, the block products (level 2) cost the spatial pass about 19 us and pay
+        measured on the bench workload, the block products (level 2) cost the spatial pass about 6 us and pay
         once many tokens merge spatially, i.e. at budgets of about a third and below."""
         if args.no_cell_dots:
             return 0

@@ -122,9 +122,10 @@ int sttm_set_output_order(sttm_ctx* ctx, int order);
  * that is this dot product), and the temporal pass leaves those pairs out instead of reading both rows again.
  * level = 2: the same also for every 2x2 and 4x4 block (S_n(t) . S_n(t+1), used where both frames keep the same
  * node n at level 1 or 2). level = 0 keeps the two passes separate. Each level makes the statistics pass slower
- * and the temporal pass faster: 1 pays wherever many tokens stay unmerged in space, 0 when almost everything
- * merges spatially, 2 only at small budgets (the extra arithmetic costs the statistics pass more than the
- * temporal pass gains at budgets of 30 % and above). Results agree to rounding. Takes effect with the next
+ * and the temporal pass faster: 1 pays wherever many tokens stay unmerged in space, 2 where many of them merge
+ * spatially (measured on a 512-frame video: from budgets of about a third of the tokens downwards; at a half it costs
+ * the statistics pass slightly more than the temporal pass gains), 0 never did on the workloads measured. Results
+ * agree to rounding. Takes effect with the next
  * statistics pass (sttm_spatial_stats / sttm_spatial_quadtree with thresholds). */
 int sttm_set_cell_dots(sttm_ctx* ctx, int level);
 
