@@ -646,9 +646,10 @@ def test_randomized_shapes_and_settings(lib):
     """Sixty seeded random draws over everything the boundary lets a caller choose -- grid (1x1 to 32x32, any aspect),
     frames, videos, width, element type, root grid, destination rule, row order, which dot products ride along in
     the spatial pass, noise level, fixed thresholds or a budget -- each compared with the oracle like the named
-    cases above, position indices included."""
+    cases above, position indices included. Every second draw reuses one long-lived context."""
     import random
     rng = random.Random(20250711)
+    shared = lib.Sttm(0)   # every second draw runs on one context that is never renewed: shapes and settings change under it
     for case in range(60):
         H = rng.choice([1, 2, 3, 5, 7, 8, 9, 12, 13, 14, 16, 17, 20, 24, 27, 31, 32])
         W = rng.choice([1, 2, 4, 6, 8, 11, 13, 14, 16, 18, 23, 27, 32])
@@ -677,6 +678,7 @@ def test_randomized_shapes_and_settings(lib):
         feats = wl.generate_alternating(cfg, sigma * 4) if alternating else wl.generate(cfg)
         print(f"case {case}: B={B} T={T} {H}x{W} D={D} {dtype} R={R} {mode} {order} cell_dots={cell_dots} "
               f"sigma={sigma} persist={persist} alternating={alternating} {kw}", flush=True)
-        r = P.run_gpu(lib, feats, root_grid=R, mode=mode, order=order, positions=True, cell_dots=cell_dots, **kw)
+        r = P.run_gpu(lib, feats, root_grid=R, mode=mode, order=order, positions=True, cell_dots=cell_dots,
+                      ctx=shared if case % 2 == 0 else None, **kw)
         info = P.check_parity(lib, feats, r, root_grid=R, mode=mode, order=order, **kw)
         assert info["K"] >= 1
